@@ -1,0 +1,155 @@
+/*
+ * dsmoe.h - C ABI of the MI355X (gfx950) implementation of the DS-MoE expert layer
+ * ("Dense Training, Sparse Inference", arXiv 2404.05567).
+ *
+ * The layer (paper Sec. 3.1, Eq. 1): a router h gives every token X a score vector
+ * S = softmax(h(X)) over N experts; sparse inference evaluates only a selected index set A of
+ * experts and returns O = sum_{i in A} S_i * e_i(X).  Dense training (Sec. 3.2, Eq. 3) evaluates
+ * every expert on every token, O = sum_{j=1..N} S_j * e_j(X), and back-propagates through all of them.
+ *
+ * Conventions shared by every call
+ *   - All tensor arguments are DEVICE pointers (HIP global memory) unless marked "host".  They must be
+ *     16-byte aligned and are owned by the caller; the library never allocates, frees or retains them
+ *     beyond the asynchronous work it enqueues.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls enqueue work and
+ *     return; they never synchronise the stream (dsmoe_poll_error excepted).
+ *   - Layouts are row-major: X[T,d], W_r[d,E], b_r[E], W_gate[E,d,f], W_up[E,d,f], W_down[E,f,d],
+ *     with d = d_model, E = n_experts, f = d_ff.  "dtype" tensors hold fp32 or bf16 values as chosen
+ *     in the descriptor; router probabilities, row weights and all accumulators are fp32.
+ *   - The expert is a SwiGLU MLP without biases: e(x) = (silu(x W_gate) * (x W_up)) W_down.
+ *   - T = 0 is a valid no-op.
+ *   - Return value: DSMOE_OK or a negative dsmoe_status; dsmoe_last_error() gives a message for the
+ *     last failing call on that context.  Errors found on the host (bad arguments) enqueue nothing.
+ *     A capacity overflow (more dispatched rows than max_rows) is found on the device: the dispatch
+ *     then publishes an empty routing (every later stage does no work) and raises a flag that
+ *     dsmoe_poll_error() reports.
+ */
+#ifndef DSMOE_H_
+#define DSMOE_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct dsmoe_ctx dsmoe_ctx;
+
+typedef enum { DSMOE_F32 = 0, DSMOE_BF16 = 1 } dsmoe_dtype;
+typedef enum { DSMOE_SEL_TOPK = 0, DSMOE_SEL_THRESHOLD = 1 } dsmoe_sel_mode;
+
+typedef enum {
+  DSMOE_OK = 0,
+  DSMOE_ERR_INVALID_ARG = -1, /* null pointer, negative size, k outside [1,E], eps < 0 or NaN, misaligned */
+  DSMOE_ERR_UNSUPPORTED = -2, /* E > 64, d_model or d_ff not a multiple of 64, unknown dtype */
+  DSMOE_ERR_WORKSPACE = -3,   /* workspace missing or too small */
+  DSMOE_ERR_CAPACITY = -4,    /* device-side: dispatched rows exceeded max_rows */
+  DSMOE_ERR_HIP = -5,         /* a HIP runtime call failed */
+  DSMOE_ERR_NOT_IMPL = -6
+} dsmoe_status;
+
+/* Layer description (host struct). max_tokens bounds T of every call; max_rows bounds the number of
+ * dispatched (token, expert) pairs nnz = sum_t |A(t)| (at most max_tokens * n_experts). */
+typedef struct {
+  int32_t d_model;
+  int32_t d_ff;
+  int32_t n_experts;
+  int32_t dtype; /* dsmoe_dtype */
+  int32_t max_tokens;
+  int64_t max_rows;
+} dsmoe_desc;
+
+/* Create / destroy a context (host object; no device memory is allocated). */
+int32_t dsmoe_create(const dsmoe_desc* desc, dsmoe_ctx** out);
+int32_t dsmoe_destroy(dsmoe_ctx* ctx);
+const char* dsmoe_last_error(const dsmoe_ctx* ctx);
+
+/* Scratch memory the library needs (intermediate H = silu(G)*U rows, block histograms, the routing
+ * objects and permuted outputs of dsmoe_sparse_fwd).  The caller allocates `bytes` of device memory,
+ * 256-byte aligned, and lends it with dsmoe_set_workspace; it must stay valid until the last enqueued
+ * call has finished.  Calls on one context share the workspace and therefore must be issued on one
+ * stream (or otherwise serialised). */
+int32_t dsmoe_workspace_bytes(const dsmoe_ctx* ctx, size_t* bytes /* host */);
+int32_t dsmoe_set_workspace(dsmoe_ctx* ctx, void* dptr, size_t bytes);
+
+/* Synchronises `stream`, then returns and clears the deferred device status (DSMOE_OK or
+ * DSMOE_ERR_CAPACITY). */
+int32_t dsmoe_poll_error(dsmoe_ctx* ctx, void* stream);
+
+/* Router, Eq. 1 first half: probs[T,E] = softmax over all E experts of X W_r (+ b_r).
+ * x: dtype [T,d]; w_r: dtype [d,E]; b_r: dtype [E] or NULL; probs: fp32 [T,E] (written). */
+int32_t dsmoe_route(dsmoe_ctx* ctx, const void* x, const void* w_r, const void* b_r, int32_t T,
+                    float* probs, void* stream);
+
+/* Expert selection (Sec. 3.1 "K experts with the highest scores"; Sec. 3.2 "Sparse Inference": scores
+ * above a threshold eps).  TOPK keeps the k highest probabilities, equal values going to the lower
+ * expert index.  THRESHOLD keeps {e : probs[t,e] > eps} (raw probability, strict; the paper's
+ * normalised threshold of Sec. 4.2 is eps * E) and falls back to the arg-max expert (lowest index)
+ * when that set is empty.
+ * probs: fp32 [T,E]; mask: u64 [T], bit e set <=> expert e selected (written);
+ * cnt_tok: i32 [T] number of selected experts (written; may be NULL). */
+int32_t dsmoe_select(dsmoe_ctx* ctx, const float* probs, int32_t T, int32_t mode, int32_t k, float eps,
+                     uint64_t* mask, int32_t* cnt_tok, void* stream);
+
+/* Token-to-expert dispatch (the "duplication of intermediate tokens" of Sec. 4.4): groups the
+ * (token, expert) pairs by expert, experts ascending, tokens ascending inside an expert.
+ * Written: expert_off i32 [E+1] exclusive prefix sum of tokens per expert (expert_off[E] = nnz);
+ * row_token i32 [max_rows] token of each row; row_weight fp32 [max_rows] = probs[token, expert];
+ * tok_off i32 [T+1] exclusive prefix sum of cnt_tok; tok_rows i32 [max_rows] rows of each token in
+ * ascending expert order; nnz i32 [1].  Entries past nnz are left untouched.
+ * x_perm: dtype [max_rows,d] or NULL; when given, row r receives a copy of x[row_token[r], :]. */
+int32_t dsmoe_dispatch(dsmoe_ctx* ctx, const void* x, const float* probs, const uint64_t* mask, int32_t T,
+                       int32_t* expert_off, int32_t* row_token, float* row_weight, int32_t* tok_off,
+                       int32_t* tok_rows, int32_t* nnz, void* x_perm, void* stream);
+
+/* Per-expert SwiGLU FFN on the dispatched rows (the e_i(X) of Eq. 1):
+ * y_perm[r,:] = e_{expert(r)}(x[row_token[r],:]) for r < expert_off[E].
+ * Rows are read from x_perm when it is non-NULL, otherwise gathered from x through row_token.
+ * y_perm: dtype [max_rows,d] (rows < nnz written). */
+int32_t dsmoe_expert_ffn(dsmoe_ctx* ctx, const void* x, const void* x_perm, const int32_t* row_token,
+                         const int32_t* expert_off, const void* w_gate, const void* w_up,
+                         const void* w_down, void* y_perm, void* stream);
+
+/* Probability-weighted combine and un-permute (Eq. 1 second half; the "aggregation of outputs from
+ * various experts" of Sec. 4.4): out[t,:] = sum_j row_weight[r_j] * y_perm[r_j,:] over the rows
+ * r_j = tok_rows[tok_off[t] .. tok_off[t+1]) in that (ascending expert) order, fp32 accumulation.
+ * out: dtype [T,d] (written). */
+int32_t dsmoe_combine(dsmoe_ctx* ctx, const void* y_perm, const float* row_weight, const int32_t* tok_off,
+                      const int32_t* tok_rows, int32_t T, void* out, void* stream);
+
+/* Whole sparse-inference forward (Eq. 1): route, select, dispatch, expert FFN and combine in one call,
+ * with the intermediate routing objects kept in the workspace.  Same results as the five staged calls.
+ * out: dtype [T,d] (written). */
+int32_t dsmoe_sparse_fwd(dsmoe_ctx* ctx, const void* x, const void* w_r, const void* b_r,
+                         const void* w_gate, const void* w_up, const void* w_down, int32_t T,
+                         int32_t mode, int32_t k, float eps, void* out, void* stream);
+
+/* Copies the routing objects of the last dsmoe_sparse_fwd out of the workspace (any argument may be
+ * NULL): probs fp32 [T,E], mask u64 [T], expert_off i32 [E+1], row_token i32 [max_rows]. */
+int32_t dsmoe_sparse_fwd_routing(dsmoe_ctx* ctx, int32_t T, float* probs, uint64_t* mask,
+                                 int32_t* expert_off, int32_t* row_token, void* stream);
+
+/* Dense-training forward (Sec. 3.2 "Dense Training"): out[t,:] = sum_{j=1..E} S[t,j] * e_j(x[t,:]),
+ * every expert on every token.  `saved` (dsmoe_dense_saved_bytes(T) bytes, caller-owned, layout
+ * private) receives what the backward pass needs; NULL skips it.  probs: fp32 [T,E] or NULL. */
+int32_t dsmoe_dense_saved_bytes(const dsmoe_ctx* ctx, int32_t T, size_t* bytes /* host */);
+int32_t dsmoe_dense_fwd(dsmoe_ctx* ctx, const void* x, const void* w_r, const void* b_r,
+                        const void* w_gate, const void* w_up, const void* w_down, int32_t T, void* out,
+                        float* probs, void* saved, void* stream);
+
+/* Dense-training backward (Eq. 3: grad S = [e_1(X)..e_N(X)]^T grad O, grad e_j(X) = S_j grad O, then
+ * the chain rule through the experts, the softmax and the router).
+ * d_out: dtype [T,d].  scratch: dsmoe_dense_bwd_scratch_bytes(T) bytes of caller-owned device memory.
+ * Written (overwritten, not accumulated): dx dtype [T,d]; fp32 gradients dw_r [d,E], db_r [E]
+ * (NULL allowed), dw_gate [E,d,f], dw_up [E,d,f], dw_down [E,f,d]. */
+int32_t dsmoe_dense_bwd_scratch_bytes(const dsmoe_ctx* ctx, int32_t T, size_t* bytes /* host */);
+int32_t dsmoe_dense_bwd(dsmoe_ctx* ctx, const void* x, const void* w_r, const void* w_gate,
+                        const void* w_up, const void* w_down, const void* saved, const void* d_out,
+                        int32_t T, void* scratch, void* dx, float* dw_r, float* db_r, float* dw_gate,
+                        float* dw_up, float* dw_down, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DSMOE_H_ */

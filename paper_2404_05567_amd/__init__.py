@@ -1,0 +1,225 @@
+"""Thin Python binding of libdsmoe (the MI355X / gfx950 DS-MoE expert layer).
+
+Argument marshalling only: every step of the layer runs in the HIP kernels behind the C ABI declared in
+`include/dsmoe.h`.  PyTorch is used for device memory and streams.  There is no CPU fallback: if the
+shared library has not been built, importing the binding's functions raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from ctypes import POINTER, byref, c_char_p, c_float, c_int32, c_int64, c_size_t, c_void_p
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libdsmoe.so")
+
+F32, BF16 = 0, 1
+SEL_TOPK, SEL_THRESHOLD = 0, 1
+OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_CAPACITY, ERR_HIP, ERR_NOT_IMPL = 0, -1, -2, -3, -4, -5, -6
+
+EXPORTS = [
+    "dsmoe_create", "dsmoe_destroy", "dsmoe_last_error", "dsmoe_workspace_bytes", "dsmoe_set_workspace",
+    "dsmoe_poll_error", "dsmoe_route", "dsmoe_select", "dsmoe_dispatch", "dsmoe_expert_ffn", "dsmoe_combine",
+    "dsmoe_sparse_fwd", "dsmoe_sparse_fwd_routing", "dsmoe_dense_saved_bytes", "dsmoe_dense_fwd",
+    "dsmoe_dense_bwd_scratch_bytes", "dsmoe_dense_bwd",
+]
+
+
+class Desc(ctypes.Structure):
+    _fields_ = [("d_model", c_int32), ("d_ff", c_int32), ("n_experts", c_int32), ("dtype", c_int32),
+                ("max_tokens", c_int32), ("max_rows", c_int64)]
+
+
+class DsmoeError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__(f"libdsmoe status {code}: {msg}")
+        self.code = code
+
+
+_lib = None
+
+
+def load_library() -> ctypes.CDLL:
+    """Load libdsmoe.so (built in-tree by `paper_2404_05567_amd/build.py`); fails loudly if absent."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} is missing: run `python -m paper_2404_05567_amd.build` "
+                          "(or __graft_entry__.build()) first; there is no fallback path")
+    lib = ctypes.CDLL(LIB_PATH)
+    P = c_void_p
+    sig = {
+        "dsmoe_create": (c_int32, [POINTER(Desc), POINTER(c_void_p)]),
+        "dsmoe_destroy": (c_int32, [P]),
+        "dsmoe_last_error": (c_char_p, [P]),
+        "dsmoe_workspace_bytes": (c_int32, [P, POINTER(c_size_t)]),
+        "dsmoe_set_workspace": (c_int32, [P, P, c_size_t]),
+        "dsmoe_poll_error": (c_int32, [P, P]),
+        "dsmoe_route": (c_int32, [P, P, P, P, c_int32, P, P]),
+        "dsmoe_select": (c_int32, [P, P, c_int32, c_int32, c_int32, c_float, P, P, P]),
+        "dsmoe_dispatch": (c_int32, [P, P, P, P, c_int32, P, P, P, P, P, P, P, P]),
+        "dsmoe_expert_ffn": (c_int32, [P] * 10),
+        "dsmoe_combine": (c_int32, [P, P, P, P, P, c_int32, P, P]),
+        "dsmoe_sparse_fwd": (c_int32, [P, P, P, P, P, P, P, c_int32, c_int32, c_int32, c_float, P, P]),
+        "dsmoe_sparse_fwd_routing": (c_int32, [P, c_int32, P, P, P, P, P]),
+        "dsmoe_dense_saved_bytes": (c_int32, [P, c_int32, POINTER(c_size_t)]),
+        "dsmoe_dense_fwd": (c_int32, [P, P, P, P, P, P, P, c_int32, P, P, P, P]),
+        "dsmoe_dense_bwd_scratch_bytes": (c_int32, [P, c_int32, POINTER(c_size_t)]),
+        "dsmoe_dense_bwd": (c_int32, [P, P, P, P, P, P, P, P, c_int32, P, P, P, P, P, P, P, P]),
+    }
+    for name, (res, args) in sig.items():
+        fn = getattr(lib, name)
+        fn.restype, fn.argtypes = res, args
+    _lib = lib
+    return lib
+
+
+def _ptr(t):
+    """Device pointer of a torch tensor (None -> NULL)."""
+    if t is None:
+        return None
+    if not t.is_cuda or not t.is_contiguous():
+        raise ValueError("tensors handed to libdsmoe must be contiguous device tensors")
+    return c_void_p(t.data_ptr())
+
+
+def _stream():
+    import torch
+    return c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+class Layer:
+    """One `dsmoe_ctx` plus its workspace.  Method names and argument order mirror the C ABI."""
+
+    def __init__(self, d_model: int, d_ff: int, n_experts: int, dtype: str, max_tokens: int,
+                 max_rows: int | None = None, device="cuda:0"):
+        import torch
+        self.lib = load_library()
+        self.torch = torch
+        self.device = torch.device(device)
+        self.d, self.f, self.E = d_model, d_ff, n_experts
+        self.dtype_code = {"f32": F32, "bf16": BF16}[dtype]
+        self.tdtype = torch.float32 if dtype == "f32" else torch.bfloat16
+        self.max_tokens = max_tokens
+        self.max_rows = max_tokens * n_experts if max_rows is None else max_rows
+        desc = Desc(d_model, d_ff, n_experts, self.dtype_code, max_tokens, self.max_rows)
+        self.ctx = c_void_p()
+        rc = self.lib.dsmoe_create(byref(desc), byref(self.ctx))
+        if rc != OK:
+            raise DsmoeError(rc, "dsmoe_create rejected the descriptor")
+        nbytes = c_size_t()
+        self._check(self.lib.dsmoe_workspace_bytes(self.ctx, byref(nbytes)))
+        self.workspace_bytes = nbytes.value
+        with torch.cuda.device(self.device):
+            self.workspace = torch.empty(nbytes.value + 256, dtype=torch.uint8, device=self.device)
+            base = (self.workspace.data_ptr() + 255) // 256 * 256
+            self._check(self.lib.dsmoe_set_workspace(self.ctx, c_void_p(base), c_size_t(nbytes.value)))
+
+    def __del__(self):
+        try:
+            if getattr(self, "ctx", None):
+                self.lib.dsmoe_destroy(self.ctx)
+                self.ctx = None
+        except Exception:
+            pass
+
+    def _check(self, rc: int):
+        if rc != OK:
+            raise DsmoeError(rc, self.lib.dsmoe_last_error(self.ctx).decode())
+
+    def _empty(self, shape, dtype):
+        return self.torch.empty(shape, dtype=dtype, device=self.device)
+
+    # ---- staged calls ---------------------------------------------------------------------------
+    def route(self, x, w_r, b_r=None):
+        T = x.shape[0]
+        probs = self._empty((T, self.E), self.torch.float32)
+        self._check(self.lib.dsmoe_route(self.ctx, _ptr(x), _ptr(w_r), _ptr(b_r), T, _ptr(probs), _stream()))
+        return probs
+
+    def select(self, probs, mode: int, k: int = 0, eps: float = 0.0):
+        T = probs.shape[0]
+        mask = self._empty((T,), self.torch.int64)
+        cnt = self._empty((T,), self.torch.int32)
+        self._check(self.lib.dsmoe_select(self.ctx, _ptr(probs), T, mode, k, eps, _ptr(mask), _ptr(cnt), _stream()))
+        return mask, cnt
+
+    def dispatch(self, x, probs, mask, materialize: bool = False):
+        T = probs.shape[0]
+        t = self.torch
+        cap = max(self.max_rows, 1)
+        r = dict(expert_off=self._empty((self.E + 1,), t.int32), row_token=self._empty((cap,), t.int32),
+                 row_weight=self._empty((cap,), t.float32), tok_off=self._empty((T + 1,), t.int32),
+                 tok_rows=self._empty((cap,), t.int32), nnz=self._empty((4,), t.int32),
+                 x_perm=self._empty((cap, self.d), self.tdtype) if materialize else None)
+        self._check(self.lib.dsmoe_dispatch(self.ctx, _ptr(x), _ptr(probs), _ptr(mask), T, _ptr(r["expert_off"]),
+                                            _ptr(r["row_token"]), _ptr(r["row_weight"]), _ptr(r["tok_off"]),
+                                            _ptr(r["tok_rows"]), _ptr(r["nnz"]), _ptr(r["x_perm"]), _stream()))
+        return r
+
+    def expert_ffn(self, x, r, w_gate, w_up, w_down):
+        y = self._empty((max(self.max_rows, 1), self.d), self.tdtype)
+        self._check(self.lib.dsmoe_expert_ffn(self.ctx, _ptr(x), _ptr(r.get("x_perm")), _ptr(r["row_token"]),
+                                              _ptr(r["expert_off"]), _ptr(w_gate), _ptr(w_up), _ptr(w_down),
+                                              _ptr(y), _stream()))
+        return y
+
+    def combine(self, y_perm, r, T: int):
+        out = self._empty((T, self.d), self.tdtype)
+        self._check(self.lib.dsmoe_combine(self.ctx, _ptr(y_perm), _ptr(r["row_weight"]), _ptr(r["tok_off"]),
+                                           _ptr(r["tok_rows"]), T, _ptr(out), _stream()))
+        return out
+
+    # ---- fused calls ----------------------------------------------------------------------------
+    def sparse_fwd(self, x, w_r, b_r, w_gate, w_up, w_down, mode: int, k: int = 0, eps: float = 0.0, out=None):
+        T = x.shape[0]
+        if out is None:
+            out = self._empty((T, self.d), self.tdtype)
+        self._check(self.lib.dsmoe_sparse_fwd(self.ctx, _ptr(x), _ptr(w_r), _ptr(b_r), _ptr(w_gate), _ptr(w_up),
+                                              _ptr(w_down), T, mode, k, eps, _ptr(out), _stream()))
+        return out
+
+    def sparse_fwd_routing(self, T: int):
+        t = self.torch
+        probs = self._empty((T, self.E), t.float32)
+        mask = self._empty((T,), t.int64)
+        expert_off = self._empty((self.E + 1,), t.int32)
+        row_token = self._empty((max(self.max_rows, 1),), t.int32)
+        self._check(self.lib.dsmoe_sparse_fwd_routing(self.ctx, T, _ptr(probs), _ptr(mask), _ptr(expert_off),
+                                                      _ptr(row_token), _stream()))
+        return probs, mask, expert_off, row_token
+
+    def poll_error(self) -> int:
+        return self.lib.dsmoe_poll_error(self.ctx, _stream())
+
+    def dense_fwd(self, x, w_r, b_r, w_gate, w_up, w_down, want_probs=False, save=False):
+        T = x.shape[0]
+        t = self.torch
+        out = self._empty((T, self.d), self.tdtype)
+        probs = self._empty((T, self.E), t.float32) if want_probs else None
+        saved = None
+        if save:
+            n = c_size_t()
+            self._check(self.lib.dsmoe_dense_saved_bytes(self.ctx, T, byref(n)))
+            saved = self._empty((max(n.value, 16),), t.uint8)
+        self._check(self.lib.dsmoe_dense_fwd(self.ctx, _ptr(x), _ptr(w_r), _ptr(b_r), _ptr(w_gate), _ptr(w_up),
+                                             _ptr(w_down), T, _ptr(out), _ptr(probs), _ptr(saved), _stream()))
+        return out, probs, saved
+
+    def dense_bwd(self, x, w_r, w_gate, w_up, w_down, saved, d_out, with_bias_grad=False):
+        T = x.shape[0]
+        t = self.torch
+        n = c_size_t()
+        self._check(self.lib.dsmoe_dense_bwd_scratch_bytes(self.ctx, T, byref(n)))
+        scratch = self._empty((max(n.value, 16),), t.uint8)
+        g = dict(dx=self._empty((T, self.d), self.tdtype), dw_r=self._empty((self.d, self.E), t.float32),
+                 db_r=self._empty((self.E,), t.float32) if with_bias_grad else None,
+                 dw_gate=self._empty((self.E, self.d, self.f), t.float32),
+                 dw_up=self._empty((self.E, self.d, self.f), t.float32),
+                 dw_down=self._empty((self.E, self.f, self.d), t.float32))
+        self._check(self.lib.dsmoe_dense_bwd(self.ctx, _ptr(x), _ptr(w_r), _ptr(w_gate), _ptr(w_up), _ptr(w_down),
+                                             _ptr(saved), _ptr(d_out), T, _ptr(scratch), _ptr(g["dx"]),
+                                             _ptr(g["dw_r"]), _ptr(g["db_r"]), _ptr(g["dw_gate"]), _ptr(g["dw_up"]),
+                                             _ptr(g["dw_down"]), _stream()))
+        return g

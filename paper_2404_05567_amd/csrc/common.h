@@ -1,0 +1,85 @@
+// Internal declarations shared by the HIP sources of libdsmoe (not part of the C ABI).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "dsmoe.h"
+
+namespace dsmoe {
+
+typedef __bf16 bf16_t;
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+
+constexpr int kMaxExperts = 64;
+constexpr int kDispatchTokensPerBlock = 256;  // tokens handled by one block of the dispatch kernels
+
+// Workspace carve-up (byte offsets into the caller's buffer).
+struct WorkspaceLayout {
+  size_t err_flag;    // int32[4]: [0] deferred status
+  size_t blk_cnt;     // int32 [n_dispatch_blocks][E]   per-block expert histogram
+  size_t blk_tok;     // int32 [n_dispatch_blocks]      per-block number of (token, expert) pairs
+  size_t h;           // dtype [max_rows][f]            silu(G)*U rows between the two grouped GEMMs
+  // routing objects and permuted output owned by dsmoe_sparse_fwd
+  size_t probs;       // f32 [max_tokens][E]
+  size_t mask;        // u64 [max_tokens]
+  size_t cnt_tok;     // i32 [max_tokens]
+  size_t expert_off;  // i32 [E+1]
+  size_t row_token;   // i32 [max_rows]
+  size_t row_weight;  // f32 [max_rows]
+  size_t tok_off;     // i32 [max_tokens+1]
+  size_t tok_rows;    // i32 [max_rows]
+  size_t nnz;         // i32 [1]
+  size_t y_perm;      // dtype [max_rows][d]
+  size_t total;
+};
+
+}  // namespace dsmoe
+
+struct dsmoe_ctx {
+  dsmoe_desc desc;
+  size_t esize;  // bytes per dtype element
+  dsmoe::WorkspaceLayout ws;
+  char* workspace;
+  size_t workspace_bytes;
+  int n_cu;
+  char err[256];
+};
+
+namespace dsmoe {
+
+// ---- kernel launchers (each validates nothing: the C-ABI layer has done so) -------------------
+// router.hip
+hipError_t launch_route(const dsmoe_ctx* c, const void* x, const void* w_r, const void* b_r, int T,
+                        float* probs, int mode /* <0: no selection */, int k, float eps, uint64_t* mask,
+                        int32_t* cnt_tok, hipStream_t s);
+hipError_t launch_select(const dsmoe_ctx* c, const float* probs, int T, int mode, int k, float eps,
+                         uint64_t* mask, int32_t* cnt_tok, hipStream_t s);
+// dispatch.hip
+hipError_t launch_dispatch(const dsmoe_ctx* c, const void* x, const float* probs, const uint64_t* mask, int T,
+                           int32_t* expert_off, int32_t* row_token, float* row_weight, int32_t* tok_off,
+                           int32_t* tok_rows, int32_t* nnz, void* x_perm, hipStream_t s);
+// expert_ffn.hip
+hipError_t launch_expert_ffn(const dsmoe_ctx* c, const void* x, const void* x_perm, const int32_t* row_token,
+                             const int32_t* expert_off, const void* w_gate, const void* w_up,
+                             const void* w_down, void* y_perm, hipStream_t s);
+// combine.hip
+hipError_t launch_combine(const dsmoe_ctx* c, const void* y_perm, const float* row_weight,
+                          const int32_t* tok_off, const int32_t* tok_rows, int T, void* out, hipStream_t s);
+// dense.hip
+size_t dense_saved_bytes(const dsmoe_ctx* c, int T);
+size_t dense_bwd_scratch_bytes(const dsmoe_ctx* c, int T);
+hipError_t launch_dense_fwd(const dsmoe_ctx* c, const void* x, const void* w_r, const void* b_r,
+                            const void* w_gate, const void* w_up, const void* w_down, int T, void* out,
+                            float* probs, void* saved, hipStream_t s);
+hipError_t launch_dense_bwd(const dsmoe_ctx* c, const void* x, const void* w_r, const void* w_gate,
+                            const void* w_up, const void* w_down, const void* saved, const void* d_out, int T,
+                            void* scratch, void* dx, float* dw_r, float* db_r, float* dw_gate, float* dw_up,
+                            float* dw_down, hipStream_t s);
+
+}  // namespace dsmoe

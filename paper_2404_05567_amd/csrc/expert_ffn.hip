@@ -1,0 +1,185 @@
+// Grouped per-expert SwiGLU FFN on dispatched rows: the e_i(X) of Eq. 1 (paper Sec. 3.1), evaluated
+// only for the (token, expert) pairs kept by the selection (Sec. 3.2 "Sparse Inference").
+//
+//   kernel 1 (gate/up):  H[r,:] = silu(x_r W_gate[e]) * (x_r W_up[e])   rows r of expert e
+//   kernel 2 (down):     Y[r,:] = H[r,:] W_down[e]
+//
+// Both are persistent grids walking a tile list derived on the device from expert_off, so no host
+// synchronisation is needed to learn the data-dependent row counts.  Token rows are gathered
+// through row_token while staging the L operand (no permuted copy of X is required).
+#include <algorithm>
+
+#include "gemm_core.h"
+
+namespace dsmoe {
+
+// Maps the block to its next tile: tiles are dealt to the 8 XCDs in 8 contiguous chunks (workgroup
+// ids are distributed round-robin over XCDs), so an XCD's L2 sees consecutive tiles of few experts.
+struct TileWalker {
+  int total, per, slots, xcd, i;
+  __device__ __forceinline__ void init(int total_tiles) {
+    total = total_tiles;
+    per = (total + 7) >> 3;
+    slots = gridDim.x >> 3;
+    xcd = blockIdx.x & 7;
+    i = blockIdx.x >> 3;
+  }
+  __device__ __forceinline__ bool next(int& idx) {
+    if (i >= per) return false;
+    idx = xcd * per + i;
+    i += slots;
+    return idx < total;
+  }
+};
+
+__device__ __forceinline__ float silu_f(float g) { return g / (1.f + __expf(-g)); }
+
+template <typename T, int BM, int BN>
+__global__ void __launch_bounds__(kThreads, 2)
+gateup_kernel(const T* __restrict__ x, const T* __restrict__ x_perm, const int32_t* __restrict__ row_token,
+              const int32_t* __restrict__ expert_off, const T* __restrict__ w_gate, const T* __restrict__ w_up,
+              T* __restrict__ h, int d, int f, int E) {
+  typedef Tile<T, BM, BN, 2> TL;
+  extern __shared__ __align__(16) char smem[];
+  __shared__ GroupTiles gt;
+  build_group_tiles(gt, expert_off, E, BM);
+  const int n_tiles = (f + BN - 1) / BN;
+  TileWalker tw;
+  tw.init(gt.tile_off[E] * n_tiles);
+  int idx;
+  while (tw.next(idx)) {
+    const int nt_blk = idx % n_tiles, mg = idx / n_tiles;
+    const int e = find_group(gt, E, mg);
+    const int m0 = (mg - gt.tile_off[e]) * BM;
+    const int row0 = gt.row_off[e] + m0;
+    const int valid = min(BM, gt.row_off[e + 1] - row0);
+    const int n0 = nt_blk * BN;
+
+    SrcRows<T, BM> L;
+    L.seg_stride = 0;
+#pragma unroll
+    for (int i = 0; i < SrcRows<T, BM>::NV; ++i) {
+      const int r = min((int)(threadIdx.x >> 3) + 32 * i, valid - 1);
+      const T* src = x_perm ? x_perm + (size_t)(row0 + r) * d : x + (size_t)row_token[row0 + r] * d;
+      L.p[i] = reinterpret_cast<const char*>(src) + (threadIdx.x & 7) * 16;
+    }
+    SrcCols<T, BN> R[2];
+    R[0].base = reinterpret_cast<const char*>(w_gate + (size_t)e * d * f + n0);
+    R[1].base = reinterpret_cast<const char*>(w_up + (size_t)e * d * f + n0);
+#pragma unroll
+    for (int b = 0; b < 2; ++b) {
+      R[b].ld_bytes = (size_t)f * sizeof(T);
+      R[b].seg_stride = 0;
+      R[b].rows_valid = min(BN, f - n0);
+      R[b].k_valid = d;
+    }
+    typename TL::Acc acc;
+    TL::zero(acc);
+    TL::mainloop(acc, L, R, d / TL::BK, 1 << 30, smem);
+
+#pragma unroll
+    for (int mt = 0; mt < TL::MT; ++mt) {
+      const int m = TL::acc_m(mt);
+      if (m >= valid) continue;
+      T* hrow = h + (size_t)(row0 + m) * f + n0;
+#pragma unroll
+      for (int nt = 0; nt < TL::NT; ++nt)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const int n = TL::acc_n(nt, g);
+          if (n0 + n >= f) continue;
+          const f32x16& G = acc[0][nt][mt];
+          const f32x16& U = acc[1][nt][mt];
+          store4(hrow + n, silu_f(G[4 * g]) * U[4 * g], silu_f(G[4 * g + 1]) * U[4 * g + 1],
+                 silu_f(G[4 * g + 2]) * U[4 * g + 2], silu_f(G[4 * g + 3]) * U[4 * g + 3]);
+        }
+    }
+  }
+}
+
+template <typename T, int BM, int BN>
+__global__ void __launch_bounds__(kThreads, 2)
+down_kernel(const T* __restrict__ h, const int32_t* __restrict__ expert_off, const T* __restrict__ w_down,
+            T* __restrict__ y, int d, int f, int E) {
+  typedef Tile<T, BM, BN, 1> TL;
+  extern __shared__ __align__(16) char smem[];
+  __shared__ GroupTiles gt;
+  build_group_tiles(gt, expert_off, E, BM);
+  const int n_tiles = (d + BN - 1) / BN;
+  TileWalker tw;
+  tw.init(gt.tile_off[E] * n_tiles);
+  int idx;
+  while (tw.next(idx)) {
+    const int nt_blk = idx % n_tiles, mg = idx / n_tiles;
+    const int e = find_group(gt, E, mg);
+    const int m0 = (mg - gt.tile_off[e]) * BM;
+    const int row0 = gt.row_off[e] + m0;
+    const int valid = min(BM, gt.row_off[e + 1] - row0);
+    const int n0 = nt_blk * BN;
+
+    SrcRows<T, BM> L;
+    L.seg_stride = 0;
+#pragma unroll
+    for (int i = 0; i < SrcRows<T, BM>::NV; ++i) {
+      const int r = min((int)(threadIdx.x >> 3) + 32 * i, valid - 1);
+      L.p[i] = reinterpret_cast<const char*>(h + (size_t)(row0 + r) * f) + (threadIdx.x & 7) * 16;
+    }
+    SrcCols<T, BN> R[1];
+    R[0].base = reinterpret_cast<const char*>(w_down + (size_t)e * f * d + n0);
+    R[0].ld_bytes = (size_t)d * sizeof(T);
+    R[0].seg_stride = 0;
+    R[0].rows_valid = min(BN, d - n0);
+    R[0].k_valid = f;
+    typename TL::Acc acc;
+    TL::zero(acc);
+    TL::mainloop(acc, L, R, f / TL::BK, 1 << 30, smem);
+
+#pragma unroll
+    for (int mt = 0; mt < TL::MT; ++mt) {
+      const int m = TL::acc_m(mt);
+      if (m >= valid) continue;
+      T* yrow = y + (size_t)(row0 + m) * d + n0;
+#pragma unroll
+      for (int nt = 0; nt < TL::NT; ++nt)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const int n = TL::acc_n(nt, g);
+          if (n0 + n >= d) continue;
+          const f32x16& A = acc[0][nt][mt];
+          store4(yrow + n, A[4 * g], A[4 * g + 1], A[4 * g + 2], A[4 * g + 3]);
+        }
+    }
+  }
+}
+
+template <typename T>
+static hipError_t launch_ffn_t(const dsmoe_ctx* c, const void* x, const void* x_perm, const int32_t* row_token,
+                               const int32_t* expert_off, const void* w_gate, const void* w_up, const void* w_down,
+                               void* y_perm, hipStream_t s) {
+  constexpr int BM = 128, BN1 = 128, BN2 = 256;
+  const int d = c->desc.d_model, f = c->desc.d_ff, E = c->desc.n_experts;
+  T* h = reinterpret_cast<T*>(c->workspace + c->ws.h);
+  // upper bound of row tiles: every expert may add one ragged tile
+  const long max_mt = (c->desc.max_rows + BM - 1) / BM + E;
+  const long t1 = max_mt * ((f + BN1 - 1) / BN1), t2 = max_mt * ((d + BN2 - 1) / BN2);
+  const int full = c->n_cu * 2;
+  const int g1 = (int)((std::min<long>(t1, full) + 7) / 8 * 8), g2 = (int)((std::min<long>(t2, full) + 7) / 8 * 8);
+  constexpr int lds1 = Tile<T, BM, BN1, 2>::LDS_BYTES, lds2 = Tile<T, BM, BN2, 1>::LDS_BYTES;
+  gateup_kernel<T, BM, BN1><<<dim3(g1), dim3(kThreads), lds1, s>>>(
+      (const T*)x, (const T*)x_perm, row_token, expert_off, (const T*)w_gate, (const T*)w_up, h, d, f, E);
+  hipError_t err = hipGetLastError();
+  if (err != hipSuccess) return err;
+  down_kernel<T, BM, BN2><<<dim3(g2), dim3(kThreads), lds2, s>>>((const T*)h, expert_off, (const T*)w_down,
+                                                                 (T*)y_perm, d, f, E);
+  return hipGetLastError();
+}
+
+hipError_t launch_expert_ffn(const dsmoe_ctx* c, const void* x, const void* x_perm, const int32_t* row_token,
+                             const int32_t* expert_off, const void* w_gate, const void* w_up,
+                             const void* w_down, void* y_perm, hipStream_t s) {
+  if (c->desc.dtype == DSMOE_BF16)
+    return launch_ffn_t<bf16_t>(c, x, x_perm, row_token, expert_off, w_gate, w_up, w_down, y_perm, s);
+  return launch_ffn_t<float>(c, x, x_perm, row_token, expert_off, w_gate, w_up, w_down, y_perm, s);
+}
+
+}  // namespace dsmoe

@@ -1,0 +1,187 @@
+// Router of the MoE layer: S = softmax(h(X)) over all N experts (paper Eq. 1), fused with the
+// inference-time expert selection (top-K of Sec. 3.1, score threshold of Sec. 3.2 "Sparse Inference").
+//
+// One block owns 32 tokens.  The four waves split every 128-byte K slice of the token rows, read
+// their X fragments straight from global memory through a deep register ring (the kernel is bound
+// by the X read), and share the W_r slice that one SrcCols stage transposes into LDS.  Partial
+// logits are reduced across waves in a fixed order, then each wave finishes 8 tokens with one lane
+// per expert: max, exp, sum by butterfly reductions, and the selection as a ballot.
+#include "gemm_core.h"
+
+namespace dsmoe {
+
+constexpr int kRouterTokens = 32;   // tokens per block
+constexpr int kRouterRing = 16;     // K slices of X kept in flight per wave
+
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int s = 32; s > 0; s >>= 1) v = fmaxf(v, __shfl_xor(v, s, 64));
+  return v;
+}
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int s = 32; s > 0; s >>= 1) v += __shfl_xor(v, s, 64);
+  return v;
+}
+__device__ __forceinline__ unsigned long long wave_max_u64(unsigned long long v) {
+#pragma unroll
+  for (int s = 32; s > 0; s >>= 1) {
+    const unsigned long long o = __shfl_xor(v, s, 64);
+    v = o > v ? o : v;
+  }
+  return v;
+}
+
+// Selection for one token, one lane per expert (p < 0 on lanes that hold no expert).
+// mode < 0: no selection.  Ties go to the lower expert index; an empty threshold set keeps the arg-max.
+__device__ __forceinline__ unsigned long long select_wave(float p, int lane, int E, int mode, int k, float eps) {
+  const bool in = lane < E;
+  if (mode == DSMOE_SEL_THRESHOLD) {
+    unsigned long long m = __ballot(in && p > eps);
+    if (m == 0ull) {
+      const unsigned long long key =
+          in ? (((unsigned long long)__float_as_uint(p)) << 32) | (unsigned)(63 - lane) : 0ull;
+      m = 1ull << (63 - (int)(wave_max_u64(key) & 63ull));
+    }
+    return m;
+  }
+  int rank = 0;
+  for (int j = 0; j < E; ++j) {
+    const float pj = __shfl(p, j, 64);
+    rank += (pj > p || (pj == p && j < lane)) ? 1 : 0;
+  }
+  return __ballot(in && rank < k);
+}
+
+template <typename T, int EP>   // EP: experts padded to 32 or 64
+__global__ void __launch_bounds__(kThreads)
+route_kernel(const T* __restrict__ x, const T* __restrict__ w_r, const T* __restrict__ b_r, int T_tokens, int d, int E,
+             float* __restrict__ probs, int mode, int k, float eps, unsigned long long* __restrict__ mask,
+             int32_t* __restrict__ cnt_tok) {
+  constexpr int BK = ElemTraits<T>::BK;
+  constexpr int ET = EP / 32;
+  __shared__ __align__(16) char sW[2][EP * kLdsPitch];
+  __shared__ float sPart[4][kRouterTokens][EP + 1];
+
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int t0 = blockIdx.x * kRouterTokens;
+  const int nkt = d / BK;
+
+  // X fragment of this lane: token t0 + lane%32, bytes [wave*32 + (lane/32)*16, +16) of each K slice
+  const int trow = min(t0 + (lane & 31), T_tokens - 1);
+  const char* xp = reinterpret_cast<const char*>(x + (size_t)trow * d) + wave * 32 + (lane >> 5) * 16;
+  const char* fW = &sW[0][0] + (lane & 31) * kLdsPitch + wave * 32 + (lane >> 5) * 16;
+
+  SrcCols<T, EP> W;
+  W.base = reinterpret_cast<const char*>(w_r);
+  W.ld_bytes = (size_t)E * sizeof(T);
+  W.seg_stride = 0;
+  W.rows_valid = E;
+  W.k_valid = d;
+
+  f32x16 acc[ET];
+#pragma unroll
+  for (int et = 0; et < ET; ++et)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc[et][i] = 0.f;
+
+  u32x4 xr[kRouterRing];
+#pragma unroll
+  for (int j = 0; j < kRouterRing; ++j)
+    if (j < nkt) xr[j] = ldg16(xp + (size_t)j * kRowBytes);
+  u32x4 wr[SrcCols<T, EP>::NV];
+  W.load(wr, 0, 0);
+
+  for (int kt0 = 0; kt0 < nkt; kt0 += kRouterRing) {
+#pragma unroll
+    for (int j = 0; j < kRouterRing; ++j) {
+      const int kt = kt0 + j;
+      if (kt < nkt) {
+        W.store(wr, sW[kt & 1]);
+        if (kt + 1 < nkt) W.load(wr, 0, kt + 1);
+        __syncthreads();
+#pragma unroll
+        for (int et = 0; et < ET; ++et) {
+          const u32x4 wf =
+              *reinterpret_cast<const u32x4*>(fW + (kt & 1) * (EP * kLdsPitch) + et * 32 * kLdsPitch);
+          Mma<T>::run(acc[et], wf, xr[j]);
+        }
+        if (kt + kRouterRing < nkt) xr[j] = ldg16(xp + (size_t)(kt + kRouterRing) * kRowBytes);
+      }
+    }
+  }
+
+  // partial logits of this wave: lane owns token lane%32; register 4q+i <-> expert 8q + 4*(lane/32) + i
+#pragma unroll
+  for (int et = 0; et < ET; ++et)
+#pragma unroll
+    for (int i = 0; i < 16; ++i)
+      sPart[wave][lane & 31][et * 32 + (i >> 2) * 8 + (lane >> 5) * 4 + (i & 3)] = acc[et][i];
+  __syncthreads();
+
+  const float bias = (b_r != nullptr && lane < E) ? to_f32(b_r[lane]) : 0.f;
+  for (int tt = wave * 8; tt < wave * 8 + 8; ++tt) {
+    const int t = t0 + tt;
+    if (t >= T_tokens) break;
+    float z = -INFINITY;
+    if (lane < E) z = ((sPart[0][tt][lane] + sPart[1][tt][lane]) + (sPart[2][tt][lane] + sPart[3][tt][lane])) + bias;
+    const float zmax = wave_max(z);
+    const float ez = lane < E ? expf(z - zmax) : 0.f;
+    const float p = ez / wave_sum(ez);
+    if (lane < E) probs[(size_t)t * E + lane] = p;
+    if (mode >= 0) {
+      const unsigned long long m = select_wave(lane < E ? p : -1.f, lane, E, mode, k, eps);
+      if (lane == 0) {
+        mask[t] = m;
+        if (cnt_tok) cnt_tok[t] = __popcll(m);
+      }
+    }
+  }
+}
+
+__global__ void __launch_bounds__(kThreads)
+select_kernel(const float* __restrict__ probs, int T_tokens, int E, int mode, int k, float eps,
+              unsigned long long* __restrict__ mask, int32_t* __restrict__ cnt_tok) {
+  const int lane = threadIdx.x & 63;
+  const int t = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (t >= T_tokens) return;
+  const float p = lane < E ? probs[(size_t)t * E + lane] : -1.f;
+  const unsigned long long m = select_wave(p, lane, E, mode, k, eps);
+  if (lane == 0) {
+    mask[t] = m;
+    if (cnt_tok) cnt_tok[t] = __popcll(m);
+  }
+}
+
+template <typename T>
+static hipError_t launch_route_t(const dsmoe_ctx* c, const void* x, const void* w_r, const void* b_r, int T_tokens,
+                                 float* probs, int mode, int k, float eps, uint64_t* mask, int32_t* cnt_tok,
+                                 hipStream_t s) {
+  const int d = c->desc.d_model, E = c->desc.n_experts;
+  const int grid = (T_tokens + kRouterTokens - 1) / kRouterTokens;
+  if (E <= 32)
+    hipLaunchKernelGGL((route_kernel<T, 32>), dim3(grid), dim3(kThreads), 0, s, (const T*)x, (const T*)w_r,
+                       (const T*)b_r, T_tokens, d, E, probs, mode, k, eps, (unsigned long long*)mask, cnt_tok);
+  else
+    hipLaunchKernelGGL((route_kernel<T, 64>), dim3(grid), dim3(kThreads), 0, s, (const T*)x, (const T*)w_r,
+                       (const T*)b_r, T_tokens, d, E, probs, mode, k, eps, (unsigned long long*)mask, cnt_tok);
+  return hipGetLastError();
+}
+
+hipError_t launch_route(const dsmoe_ctx* c, const void* x, const void* w_r, const void* b_r, int T_tokens,
+                        float* probs, int mode, int k, float eps, uint64_t* mask, int32_t* cnt_tok, hipStream_t s) {
+  if (T_tokens == 0) return hipSuccess;
+  if (c->desc.dtype == DSMOE_BF16)
+    return launch_route_t<bf16_t>(c, x, w_r, b_r, T_tokens, probs, mode, k, eps, mask, cnt_tok, s);
+  return launch_route_t<float>(c, x, w_r, b_r, T_tokens, probs, mode, k, eps, mask, cnt_tok, s);
+}
+
+hipError_t launch_select(const dsmoe_ctx* c, const float* probs, int T_tokens, int mode, int k, float eps,
+                         uint64_t* mask, int32_t* cnt_tok, hipStream_t s) {
+  if (T_tokens == 0) return hipSuccess;
+  hipLaunchKernelGGL(select_kernel, dim3((T_tokens + 3) / 4), dim3(kThreads), 0, s, probs, T_tokens,
+                     c->desc.n_experts, mode, k, eps, (unsigned long long*)mask, cnt_tok);
+  return hipGetLastError();
+}
+
+}  // namespace dsmoe

@@ -42,5 +42,8 @@ def rel_err(got, ref):
     """max|got - ref| / max|ref| (the layer's parity metric)."""
     got = np.asarray(got, dtype=np.float64)
     ref = np.asarray(ref, dtype=np.float64)
+    assert got.shape == ref.shape, (got.shape, ref.shape)
+    if ref.size == 0:
+        return 0.0
     den = np.abs(ref).max()
     return float(np.abs(got - ref).max() / (den if den > 0 else 1.0))

@@ -1,0 +1,92 @@
+"""The C-ABI library loads, exports every symbol the header declares, and rejects bad arguments on the
+host before touching a device (no GPU needed)."""
+import ctypes
+import os
+import re
+from ctypes import byref, c_size_t, c_void_p
+
+import pytest
+
+import paper_2404_05567_amd as dsmoe
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(dsmoe.LIB_PATH):
+        from paper_2404_05567_amd import build
+        build.build(verbose=False)
+    return dsmoe.load_library()
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "dsmoe.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(dsmoe_[a-z_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = declared_symbols()
+    assert len(names) >= 15
+    for n in names:
+        assert hasattr(lib, n), n
+    assert sorted(dsmoe.EXPORTS) == names
+
+
+def make(lib, **kw):
+    d = dict(d_model=256, d_ff=64, n_experts=8, dtype=dsmoe.F32, max_tokens=128, max_rows=1024)
+    d.update(kw)
+    ctx = c_void_p()
+    rc = lib.dsmoe_create(byref(dsmoe.Desc(**d)), byref(ctx))
+    return rc, ctx
+
+
+def test_create_validates_the_descriptor(lib):
+    rc, ctx = make(lib)
+    assert rc == dsmoe.OK and ctx.value
+    n = c_size_t()
+    assert lib.dsmoe_workspace_bytes(ctx, byref(n)) == dsmoe.OK and n.value > 0
+    assert lib.dsmoe_destroy(ctx) == dsmoe.OK
+    assert make(lib, n_experts=128)[0] == dsmoe.ERR_UNSUPPORTED
+    assert make(lib, n_experts=12)[0] == dsmoe.ERR_UNSUPPORTED
+    assert make(lib, d_model=250)[0] == dsmoe.ERR_UNSUPPORTED
+    assert make(lib, d_ff=40)[0] == dsmoe.ERR_UNSUPPORTED
+    assert make(lib, dtype=7)[0] == dsmoe.ERR_UNSUPPORTED
+    assert make(lib, d_model=0)[0] == dsmoe.ERR_INVALID_ARG
+    assert make(lib, max_rows=128 * 8 + 1)[0] == dsmoe.ERR_INVALID_ARG
+    assert lib.dsmoe_create(None, byref(c_void_p())) == dsmoe.ERR_INVALID_ARG
+
+
+def test_calls_reject_bad_arguments_before_any_device_work(lib):
+    rc, ctx = make(lib)
+    assert rc == dsmoe.OK
+    fake = c_void_p(0x1000)     # aligned, never dereferenced on these paths
+    odd = c_void_p(0x1004)
+    s = None
+    assert lib.dsmoe_route(ctx, None, fake, None, 4, fake, s) == dsmoe.ERR_INVALID_ARG
+    assert b"null pointer" in lib.dsmoe_last_error(ctx)
+    assert lib.dsmoe_route(ctx, odd, fake, None, 4, fake, s) == dsmoe.ERR_INVALID_ARG
+    assert b"aligned" in lib.dsmoe_last_error(ctx)
+    assert lib.dsmoe_route(ctx, fake, fake, None, -1, fake, s) == dsmoe.ERR_INVALID_ARG
+    assert lib.dsmoe_route(ctx, fake, fake, None, 129, fake, s) == dsmoe.ERR_INVALID_ARG
+    assert lib.dsmoe_select(ctx, fake, 4, dsmoe.SEL_TOPK, 0, 0.0, fake, None, s) == dsmoe.ERR_INVALID_ARG
+    assert lib.dsmoe_select(ctx, fake, 4, dsmoe.SEL_TOPK, 9, 0.0, fake, None, s) == dsmoe.ERR_INVALID_ARG
+    assert lib.dsmoe_select(ctx, fake, 4, dsmoe.SEL_THRESHOLD, 0, -0.5, fake, None, s) == dsmoe.ERR_INVALID_ARG
+    assert lib.dsmoe_select(ctx, fake, 4, dsmoe.SEL_THRESHOLD, 0, float("nan"), fake, None, s) == dsmoe.ERR_INVALID_ARG
+    assert lib.dsmoe_select(ctx, fake, 4, 5, 1, 0.0, fake, None, s) == dsmoe.ERR_INVALID_ARG
+    # calls that need the workspace refuse to run without one
+    assert lib.dsmoe_sparse_fwd(ctx, fake, fake, None, fake, fake, fake, 4, dsmoe.SEL_TOPK, 2, 0.0, fake, s) \
+        == dsmoe.ERR_WORKSPACE
+    assert lib.dsmoe_expert_ffn(ctx, fake, None, fake, fake, fake, fake, fake, fake, s) == dsmoe.ERR_WORKSPACE
+    assert lib.dsmoe_set_workspace(ctx, None, 1 << 20) == dsmoe.ERR_INVALID_ARG
+    assert lib.dsmoe_set_workspace(ctx, c_void_p(0x1010), 1 << 30) == dsmoe.ERR_INVALID_ARG
+    assert lib.dsmoe_set_workspace(ctx, fake, 16) == dsmoe.ERR_WORKSPACE
+    assert lib.dsmoe_destroy(ctx) == dsmoe.OK
+
+
+def test_binding_fails_loudly_without_the_library(monkeypatch, tmp_path):
+    monkeypatch.setattr(dsmoe, "_lib", None)
+    monkeypatch.setattr(dsmoe, "LIB_PATH", str(tmp_path / "libdsmoe.so"))
+    with pytest.raises(ImportError):
+        dsmoe.load_library()

@@ -1,0 +1,296 @@
+"""GPU parity of the sparse-inference forward (Eq. 1) against the CPU checker, through the C ABI.
+
+Bars: routing objects (selected sets, per-expert counts, dispatch permutation) bit-exact; outputs
+within max|gpu - ref| / max|ref| <= 1e-5 (fp32) or 2e-2 (bf16 storage, fp32 accumulation).
+"""
+import sys
+
+import numpy as np
+import pytest
+
+import dsmoe_inputs as gen
+from oracle import dsmoe_oracle as orc
+from tests import helpers
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"f32": 1e-5, "bf16": 2e-2}
+
+
+def say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+@pytest.fixture(scope="module")
+def torch():
+    import torch
+    assert torch.cuda.is_available()
+    return torch
+
+
+@pytest.fixture(scope="module")
+def dsmoe():
+    import paper_2404_05567_amd as m
+    m.load_library()      # raises if the HIP library is missing: there is no fallback
+    return m
+
+
+def dev(torch, a, dtype):
+    if a is None:
+        return None
+    t = torch.from_numpy(np.ascontiguousarray(a)).to("cuda:0")
+    return t.to(torch.bfloat16) if dtype == "bf16" else t
+
+
+def weights_to_dev(torch, inp):
+    dt = inp.cfg.dtype
+    return {k: dev(torch, getattr(inp, k), dt) for k in ("x", "w_r", "b_r", "w_gate", "w_up", "w_down")}
+
+
+def mode_code(dsmoe, mode):
+    return dsmoe.SEL_TOPK if mode == "topk" else dsmoe.SEL_THRESHOLD
+
+
+def mask_to_bool(mask_i64, E):
+    m = mask_i64.cpu().numpy().view(np.uint64)
+    return ((m[:, None] >> np.arange(E, dtype=np.uint64)[None, :]) & np.uint64(1)).astype(bool)
+
+
+def run_staged_and_check(torch, dsmoe, inp, mode, k, eps, max_rows=None, materialize=False):
+    """Every staged C-ABI call against the matching checker function; returns the GPU output."""
+    cfg = inp.cfg
+    T, E, tol = inp.x.shape[0], cfg.E, TOL[cfg.dtype]
+    say(f"[case] {cfg.name} T={T} d={cfg.d} E={E} f={cfg.f} {cfg.dtype} mode={mode} k={k} eps={eps} "
+        f"materialize={materialize}")
+    w = weights_to_dev(torch, inp)
+    layer = dsmoe.Layer(cfg.d, cfg.f, E, cfg.dtype, max_tokens=max(T, 1), max_rows=max_rows)
+
+    S_ref = orc.route(inp.x, inp.w_r, inp.b_r)
+    M_ref = orc.select(S_ref, mode, k, eps)
+    r_ref = orc.dispatch(M_ref, S_ref)
+
+    # route
+    probs = layer.route(w["x"], w["w_r"], w["b_r"])
+    torch.cuda.synchronize()
+    S_gpu = probs.cpu().numpy()
+    assert helpers.rel_err(S_gpu, S_ref) <= 1e-5
+    np.testing.assert_allclose(S_gpu.sum(axis=1), 1.0, atol=1e-5)
+
+    # select: on the GPU's own fp32 probabilities, checker decides on the same fp32 values
+    mask, cnt = layer.select(probs, mode_code(dsmoe, mode), k, eps)
+    M_same = orc.select(S_gpu, mode, k, np.float32(eps))
+    M_gpu = mask_to_bool(mask, E)
+    np.testing.assert_array_equal(M_gpu, M_same)
+    np.testing.assert_array_equal(cnt.cpu().numpy(), M_same.sum(axis=1))
+    # margin-conditioned inputs: the sets also equal the fp64 decision
+    np.testing.assert_array_equal(M_gpu, M_ref)
+
+    # dispatch
+    r = layer.dispatch(w["x"], probs, mask, materialize=materialize)
+    assert layer.poll_error() == dsmoe.OK
+    r_same = orc.dispatch(M_gpu, S_gpu)
+    nnz = int(r["nnz"][0].item())
+    assert nnz == r_same.nnz == r_ref.nnz
+    np.testing.assert_array_equal(r["expert_off"].cpu().numpy(), r_same.expert_off)
+    np.testing.assert_array_equal(r["row_token"].cpu().numpy()[:nnz], r_same.row_token)
+    np.testing.assert_array_equal(r["tok_off"].cpu().numpy(), r_same.tok_off)
+    np.testing.assert_array_equal(r["tok_rows"].cpu().numpy()[:nnz], r_same.tok_rows)
+    np.testing.assert_array_equal(r["row_weight"].cpu().numpy()[:nnz], r_same.row_weight)
+    np.testing.assert_array_equal(r["row_token"].cpu().numpy()[:nnz], r_ref.row_token)
+    if materialize:
+        xp = r["x_perm"][:nnz].float().cpu().numpy()
+        np.testing.assert_array_equal(xp, inp.x[r_same.row_token])
+
+    # expert FFN on the dispatched rows
+    y = layer.expert_ffn(w["x"], r, w["w_gate"], w["w_up"], w["w_down"])
+    torch.cuda.synchronize()
+    Y_ref = orc.expert_outputs_permuted(inp.x, r_ref, inp.w_gate, inp.w_up, inp.w_down)
+    y_gpu = y[:nnz].float().cpu().numpy()
+    if nnz:
+        assert helpers.rel_err(y_gpu, Y_ref) <= tol
+
+    # combine
+    out = layer.combine(y, r, T)
+    torch.cuda.synchronize()
+    O_ref, _, _ = orc.sparse_forward(inp.x, inp.w_r, inp.b_r, inp.w_gate, inp.w_up, inp.w_down, mode, k, eps)
+    o_gpu = out.float().cpu().numpy()
+    if T:
+        assert helpers.rel_err(o_gpu, O_ref) <= tol
+        # the combine alone, on the GPU's own rows, in fp64
+        O_cmb = orc.combine(y_gpu.astype(np.float64), r_same, T)
+        assert helpers.rel_err(o_gpu, O_cmb) <= (1e-6 if cfg.dtype == "f32" else 6e-3)
+
+    # fused call gives the same routing and (bitwise) the same output
+    out2 = layer.sparse_fwd(w["x"], w["w_r"], w["b_r"], w["w_gate"], w["w_up"], w["w_down"],
+                            mode_code(dsmoe, mode), k, eps)
+    assert layer.poll_error() == dsmoe.OK
+    p2, m2, eo2, rt2 = layer.sparse_fwd_routing(T)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(mask_to_bool(m2, E), M_ref)
+    np.testing.assert_array_equal(eo2.cpu().numpy(), r_ref.expert_off)
+    np.testing.assert_array_equal(rt2.cpu().numpy()[:nnz], r_ref.row_token)
+    assert torch.equal(out2, out)
+    return o_gpu
+
+
+def conditioned(cfg, mode, k, eps, variant=0):
+    inp = gen.make_layer(cfg, variant)
+    helpers.condition_margins(inp, mode, k, eps)
+    return inp
+
+
+# --------------------------------------------------------------------------------------------------
+def test_c1_tiny_fp32_topk2(torch, dsmoe):
+    cfg = gen.CONFIGS["c1"]
+    run_staged_and_check(torch, dsmoe, conditioned(cfg, "topk", 2, 0.0), "topk", 2, 0.0)
+
+
+def test_c1_threshold_and_materialised_permutation(torch, dsmoe):
+    cfg = gen.CONFIGS["c1"].with_(router_std=0.1)
+    run_staged_and_check(torch, dsmoe, conditioned(cfg, "threshold", 0, 0.1), "threshold", 0, 0.1, materialize=True)
+
+
+def test_c1_dense_limits_k_equals_E_and_eps_zero(torch, dsmoe):
+    cfg = gen.CONFIGS["c1"]
+    inp = gen.make_layer(cfg, 0)
+    o1 = run_staged_and_check(torch, dsmoe, inp, "topk", cfg.E, 0.0)
+    o2 = run_staged_and_check(torch, dsmoe, inp, "threshold", 0, 0.0)
+    D, _, _ = orc.dense_forward(inp.x, inp.w_r, inp.b_r, inp.w_gate, inp.w_up, inp.w_down)
+    assert helpers.rel_err(o1, D) <= 1e-5 and helpers.rel_err(o2, D) <= 1e-5
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("mode,k,eps", [("topk", 3, 0.0), ("threshold", 0, 0.05)])
+def test_ragged_multi_tile(torch, dsmoe, dtype, mode, k, eps):
+    # T not a multiple of any tile, d_ff with a ragged column tile, several row tiles per expert
+    cfg = gen.LayerConfig("ragged", 11, T=777, d=320, E=16, f=192, dtype=dtype, mode=mode, k=k, eps=eps,
+                          router_std=0.08)
+    run_staged_and_check(torch, dsmoe, conditioned(cfg, mode, k, eps), mode, k, eps)
+
+
+def test_skewed_router_bias_empty_and_hot_experts(torch, dsmoe):
+    cfg = gen.LayerConfig("skew", 12, T=500, d=256, E=24, f=128, dtype="bf16", mode="threshold", eps=0.04,
+                          router_std=0.05, zipf_s=2.0)
+    inp = conditioned(cfg, "threshold", 0, 0.04)
+    S = orc.route(inp.x, inp.w_r, inp.b_r)
+    cnt = orc.select_threshold(S, 0.04).sum(axis=0)
+    assert cnt.max() > 400 and cnt.min() == 0          # one expert takes nearly every token, some none
+    run_staged_and_check(torch, dsmoe, inp, "threshold", 0, 0.04)
+
+
+def test_one_hot_router_sends_everything_to_one_expert(torch, dsmoe):
+    cfg = gen.LayerConfig("onehot", 13, T=200, d=128, E=8, f=64, dtype="f32", mode="topk", k=1, router_std=0.0)
+    inp = gen.make_layer(cfg, 0)
+    inp.b_r = np.zeros(8, dtype=np.float32)
+    inp.b_r[5] = 60.0
+    o = run_staged_and_check(torch, dsmoe, inp, "topk", 1, 0.0)
+    ref = orc.expert_ffn(inp.x, inp.w_gate[5], inp.w_up[5], inp.w_down[5])
+    assert helpers.rel_err(o, ref) <= 1e-5
+
+
+def test_exact_ties_from_duplicated_router_columns(torch, dsmoe):
+    cfg = gen.LayerConfig("ties", 14, T=256, d=128, E=8, f=64, dtype="bf16", mode="topk", k=2, router_std=0.1)
+    inp = gen.make_layer(cfg, 0)
+    inp.w_r[:, 6] = inp.w_r[:, 1]
+    inp.w_r[:, 3] = inp.w_r[:, 1]
+    w = weights_to_dev(torch, inp)
+    layer = dsmoe.Layer(cfg.d, cfg.f, cfg.E, cfg.dtype, max_tokens=cfg.T)
+    probs = layer.route(w["x"], w["w_r"], None)
+    S = probs.cpu().numpy()
+    assert np.array_equal(S[:, 1], S[:, 3]) and np.array_equal(S[:, 1], S[:, 6])
+    for k in (1, 2, 3):
+        mask, _ = layer.select(probs, dsmoe.SEL_TOPK, k, 0.0)
+        np.testing.assert_array_equal(mask_to_bool(mask, cfg.E), orc.select_topk(S, k))
+    # threshold fallback with ties: eps above every probability -> arg-max, lowest index
+    mask, cnt = layer.select(probs, dsmoe.SEL_THRESHOLD, 0, 0.999)
+    np.testing.assert_array_equal(mask_to_bool(mask, cfg.E), orc.select_threshold(S, np.float32(0.999)))
+    assert (cnt.cpu().numpy() == 1).all()
+
+
+@pytest.mark.parametrize("T", [0, 1, 8, 32, 128])
+@pytest.mark.parametrize("mode,k,eps", [("topk", 4, 0.0), ("threshold", 0, 0.02)])
+def test_c3_decode_sizes(torch, dsmoe, T, mode, k, eps):
+    cfg = gen.CONFIGS["c3"].with_(T=T, E=32)
+    inp = gen.make_layer(cfg, T)
+    if T:
+        helpers.condition_margins(inp, mode, k, eps)
+    run_staged_and_check(torch, dsmoe, inp, mode, k, eps, max_rows=T * 32)
+
+
+def test_capacity_overflow_is_reported_and_harmless(torch, dsmoe):
+    cfg = gen.CONFIGS["c1"]
+    inp = gen.make_layer(cfg, 0)
+    w = weights_to_dev(torch, inp)
+    layer = dsmoe.Layer(cfg.d, cfg.f, cfg.E, cfg.dtype, max_tokens=cfg.T, max_rows=200)   # needs 256 rows
+    out = layer.sparse_fwd(w["x"], w["w_r"], None, w["w_gate"], w["w_up"], w["w_down"], dsmoe.SEL_TOPK, 2, 0.0)
+    assert layer.poll_error() == dsmoe.ERR_CAPACITY
+    assert layer.poll_error() == dsmoe.OK                      # the flag is cleared by the poll
+    _, _, eo, _ = layer.sparse_fwd_routing(cfg.T)
+    assert int(eo.abs().sum().item()) == 0                     # empty routing was published
+    assert float(out.abs().max().item()) == 0.0                # combine of nothing
+    # a call that fits still works afterwards
+    out = layer.sparse_fwd(w["x"], w["w_r"], None, w["w_gate"], w["w_up"], w["w_down"], dsmoe.SEL_TOPK, 1, 0.0)
+    assert layer.poll_error() == dsmoe.OK
+    O, _, _ = orc.sparse_forward(inp.x, inp.w_r, None, inp.w_gate, inp.w_up, inp.w_down, "topk", 1)
+    assert helpers.rel_err(out.float().cpu().numpy(), O) <= 1e-5
+
+
+def test_repeated_calls_are_bitwise_identical(torch, dsmoe):
+    cfg = gen.LayerConfig("det", 15, T=1000, d=256, E=16, f=128, dtype="bf16", mode="threshold", eps=0.05,
+                          router_std=0.08)
+    inp = gen.make_layer(cfg, 0)
+    w = weights_to_dev(torch, inp)
+    layer = dsmoe.Layer(cfg.d, cfg.f, cfg.E, cfg.dtype, max_tokens=cfg.T)
+    outs = [layer.sparse_fwd(w["x"], w["w_r"], None, w["w_gate"], w["w_up"], w["w_down"],
+                             dsmoe.SEL_THRESHOLD, 0, 0.05).clone() for _ in range(3)]
+    assert torch.equal(outs[0], outs[1]) and torch.equal(outs[0], outs[2])
+
+
+# --------------------------------------------------------------------------------------------------
+# full benchmark sizes, in the launch configuration bench.py times (dsmoe_sparse_fwd)
+# --------------------------------------------------------------------------------------------------
+def full_size_check(torch, dsmoe, name, n_sample, max_rows):
+    cfg = gen.CONFIGS[name]
+    say(f"[case] full-size {name}: generating inputs")
+    inp = conditioned(cfg, cfg.mode, cfg.k, cfg.eps)
+    T, E = cfg.T, cfg.E
+    S_ref = orc.route(inp.x, inp.w_r, inp.b_r)
+    M_ref = orc.select(S_ref, cfg.mode, cfg.k, cfg.eps)
+    r_ref = orc.dispatch(M_ref, S_ref)
+    say(f"[case] full-size {name}: nnz={r_ref.nnz} mean active={r_ref.nnz / T:.2f} "
+        f"rows/expert min={r_ref.cnt_exp.min()} max={r_ref.cnt_exp.max()}")
+    assert r_ref.nnz <= max_rows
+    w = weights_to_dev(torch, inp)
+    layer = dsmoe.Layer(cfg.d, cfg.f, E, cfg.dtype, max_tokens=T, max_rows=max_rows)
+    out = layer.sparse_fwd(w["x"], w["w_r"], w["b_r"], w["w_gate"], w["w_up"], w["w_down"],
+                           mode_code(dsmoe, cfg.mode), cfg.k, cfg.eps)
+    assert layer.poll_error() == dsmoe.OK
+    probs, mask, eo, rt = layer.sparse_fwd_routing(T)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(mask_to_bool(mask, E), M_ref)
+    np.testing.assert_array_equal(eo.cpu().numpy(), r_ref.expert_off)
+    np.testing.assert_array_equal(rt.cpu().numpy()[:r_ref.nnz], r_ref.row_token)
+    assert helpers.rel_err(probs.cpu().numpy(), S_ref) <= 1e-5
+    # sampled output rows (each token's output depends on no other token)
+    g = np.random.default_rng(cfg.index)
+    tokens = np.sort(g.choice(T, size=n_sample, replace=False))
+    tokens[0], tokens[-1] = 0, T - 1
+    O_ref, _, _ = orc.sparse_forward(inp.x, inp.w_r, inp.b_r, inp.w_gate, inp.w_up, inp.w_down, cfg.mode,
+                                     cfg.k, cfg.eps, tokens=tokens)
+    o = out.float().cpu().numpy()
+    err = helpers.rel_err(o[tokens], O_ref)
+    say(f"[case] full-size {name}: sampled rel err {err:.3e}")
+    assert err <= TOL[cfg.dtype]
+    assert np.isfinite(o).all()
+    return r_ref
+
+
+def test_c2_full_size_sparse_prefill(torch, dsmoe):
+    r = full_size_check(torch, dsmoe, "c2", n_sample=96, max_rows=4096 * 16)
+    assert 0.30 < r.nnz / (4096 * 32) < 0.42
+
+
+def test_c5_full_size_skewed_prefill(torch, dsmoe):
+    r = full_size_check(torch, dsmoe, "c5", n_sample=48, max_rows=16384 * 24)
+    assert r.cnt_exp.max() > 10 * r.cnt_exp.min()
