@@ -149,6 +149,16 @@ int32_t dsmoe_dense_bwd(dsmoe_ctx* ctx, const void* x, const void* w_r, const vo
                         int32_t T, void* scratch, void* dx, float* dw_r, float* db_r, float* dw_gate,
                         float* dw_up, float* dw_down, void* stream);
 
+/* Kernel timing for benchmarks (not part of the layer's definition).  While enabled, every call that
+ * runs the expert FFN (dsmoe_expert_ffn, dsmoe_sparse_fwd) brackets its two grouped-GEMM kernels with
+ * HIP events recorded on the call's stream, for at most max_calls calls.  dsmoe_profile_read waits for
+ * the recorded events, returns the number of calls and the summed durations in milliseconds of the
+ * gate/up kernel and of the down kernel (host pointers), and starts a new series.
+ * max_calls = 0 disables timing and releases the events. */
+int32_t dsmoe_profile_enable(dsmoe_ctx* ctx, int32_t max_calls);
+int32_t dsmoe_profile_read(dsmoe_ctx* ctx, int32_t* n_calls /* host */, float* gateup_ms /* host */,
+                           float* down_ms /* host */);
+
 #ifdef __cplusplus
 }
 #endif

@@ -21,7 +21,7 @@ EXPORTS = [
     "dsmoe_create", "dsmoe_destroy", "dsmoe_last_error", "dsmoe_workspace_bytes", "dsmoe_set_workspace",
     "dsmoe_poll_error", "dsmoe_route", "dsmoe_select", "dsmoe_dispatch", "dsmoe_expert_ffn", "dsmoe_combine",
     "dsmoe_sparse_fwd", "dsmoe_sparse_fwd_routing", "dsmoe_dense_saved_bytes", "dsmoe_dense_fwd",
-    "dsmoe_dense_bwd_scratch_bytes", "dsmoe_dense_bwd",
+    "dsmoe_dense_bwd_scratch_bytes", "dsmoe_dense_bwd", "dsmoe_profile_enable", "dsmoe_profile_read",
 ]
 
 
@@ -67,6 +67,8 @@ def load_library() -> ctypes.CDLL:
         "dsmoe_dense_fwd": (c_int32, [P, P, P, P, P, P, P, c_int32, P, P, P, P]),
         "dsmoe_dense_bwd_scratch_bytes": (c_int32, [P, c_int32, POINTER(c_size_t)]),
         "dsmoe_dense_bwd": (c_int32, [P, P, P, P, P, P, P, P, c_int32, P, P, P, P, P, P, P, P]),
+        "dsmoe_profile_enable": (c_int32, [P, c_int32]),
+        "dsmoe_profile_read": (c_int32, [P, POINTER(c_int32), POINTER(c_float), POINTER(c_float)]),
     }
     for name, (res, args) in sig.items():
         fn = getattr(lib, name)
@@ -189,6 +191,15 @@ class Layer:
         self._check(self.lib.dsmoe_sparse_fwd_routing(self.ctx, T, _ptr(probs), _ptr(mask), _ptr(expert_off),
                                                       _ptr(row_token), _stream()))
         return probs, mask, expert_off, row_token
+
+    def profile_enable(self, max_calls: int):
+        self._check(self.lib.dsmoe_profile_enable(self.ctx, max_calls))
+
+    def profile_read(self):
+        """(calls, summed gate/up kernel ms, summed down kernel ms) since the last read."""
+        n, a, b = c_int32(), c_float(), c_float()
+        self._check(self.lib.dsmoe_profile_read(self.ctx, byref(n), byref(a), byref(b)))
+        return n.value, a.value, b.value
 
     def poll_error(self) -> int:
         return self.lib.dsmoe_poll_error(self.ctx, _stream())

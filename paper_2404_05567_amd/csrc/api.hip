@@ -126,7 +126,51 @@ int32_t dsmoe_create(const dsmoe_desc* desc, dsmoe_ctx** out) {
   return DSMOE_OK;
 }
 
+static void release_events(dsmoe_ctx* c) {
+  if (c->prof.ev) {
+    for (int i = 0; i < 3 * c->prof.max_calls; ++i) (void)hipEventDestroy(c->prof.ev[i]);
+    delete[] c->prof.ev;
+  }
+  c->prof = dsmoe_profile();
+}
+
+int32_t dsmoe_profile_enable(dsmoe_ctx* c, int32_t max_calls) {
+  if (!c || max_calls < 0 || max_calls > (1 << 20)) return DSMOE_ERR_INVALID_ARG;
+  release_events(c);
+  if (max_calls == 0) return DSMOE_OK;
+  c->prof.ev = new (std::nothrow) hipEvent_t[3 * (size_t)max_calls];
+  if (!c->prof.ev) return fail(c, DSMOE_ERR_INVALID_ARG, "out of host memory");
+  for (int i = 0; i < 3 * max_calls; ++i) {
+    hipError_t e = hipEventCreate(&c->prof.ev[i]);
+    if (e != hipSuccess) {
+      for (int j = 0; j < i; ++j) (void)hipEventDestroy(c->prof.ev[j]);
+      delete[] c->prof.ev;
+      c->prof = dsmoe_profile();
+      return hip_fail(c, e, "hipEventCreate");
+    }
+  }
+  c->prof.max_calls = max_calls;
+  return DSMOE_OK;
+}
+
+int32_t dsmoe_profile_read(dsmoe_ctx* c, int32_t* n_calls, float* gateup_ms, float* down_ms) {
+  if (!c || !n_calls || !gateup_ms || !down_ms) return DSMOE_ERR_INVALID_ARG;
+  *n_calls = 0; *gateup_ms = 0.f; *down_ms = 0.f;
+  for (int i = 0; i < c->prof.n; ++i) {
+    hipEvent_t* ev = c->prof.ev + 3 * i;
+    float a = 0.f, b = 0.f;
+    HIP_TRY(c, hipEventSynchronize(ev[2]));
+    HIP_TRY(c, hipEventElapsedTime(&a, ev[0], ev[1]));
+    HIP_TRY(c, hipEventElapsedTime(&b, ev[1], ev[2]));
+    *gateup_ms += a; *down_ms += b;
+  }
+  *n_calls = c->prof.n;
+  c->prof.n = 0;
+  return DSMOE_OK;
+}
+
 int32_t dsmoe_destroy(dsmoe_ctx* ctx) {
+  if (ctx) release_events(ctx);
   delete ctx;
   return DSMOE_OK;
 }

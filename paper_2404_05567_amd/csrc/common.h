@@ -41,8 +41,14 @@ struct WorkspaceLayout {
 
 }  // namespace dsmoe
 
+struct dsmoe_profile {
+  int max_calls = 0, n = 0;
+  hipEvent_t* ev = nullptr;   // 3 events per call: before gate/up, between, after down
+};
+
 struct dsmoe_ctx {
   dsmoe_desc desc;
+  mutable dsmoe_profile prof;
   size_t esize;  // bytes per dtype element
   dsmoe::WorkspaceLayout ws;
   char* workspace;

@@ -165,13 +165,18 @@ static hipError_t launch_ffn_t(const dsmoe_ctx* c, const void* x, const void* x_
   const int full = c->n_cu * 2;
   const int g1 = (int)((std::min<long>(t1, full) + 7) / 8 * 8), g2 = (int)((std::min<long>(t2, full) + 7) / 8 * 8);
   constexpr int lds1 = Tile<T, BM, BN1, 2>::LDS_BYTES, lds2 = Tile<T, BM, BN2, 1>::LDS_BYTES;
+  hipEvent_t* ev = (c->prof.ev && c->prof.n < c->prof.max_calls) ? c->prof.ev + 3 * c->prof.n++ : nullptr;
+  if (ev) (void)hipEventRecord(ev[0], s);
   gateup_kernel<T, BM, BN1><<<dim3(g1), dim3(kThreads), lds1, s>>>(
       (const T*)x, (const T*)x_perm, row_token, expert_off, (const T*)w_gate, (const T*)w_up, h, d, f, E);
   hipError_t err = hipGetLastError();
   if (err != hipSuccess) return err;
+  if (ev) (void)hipEventRecord(ev[1], s);
   down_kernel<T, BM, BN2><<<dim3(g2), dim3(kThreads), lds2, s>>>((const T*)h, expert_off, (const T*)w_down,
                                                                  (T*)y_perm, d, f, E);
-  return hipGetLastError();
+  err = hipGetLastError();
+  if (ev) (void)hipEventRecord(ev[2], s);
+  return err;
 }
 
 hipError_t launch_expert_ffn(const dsmoe_ctx* c, const void* x, const void* x_perm, const int32_t* row_token,
