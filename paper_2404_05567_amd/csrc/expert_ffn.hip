@@ -9,7 +9,7 @@
 // through row_token while staging the L operand (no permuted copy of X is required).
 #include <algorithm>
 
-#include "gemm_core.h"
+#include "gemm_bf16.h"
 
 namespace dsmoe {
 
@@ -152,6 +152,150 @@ down_kernel(const T* __restrict__ h, const int32_t* __restrict__ expert_off, con
   }
 }
 
+// ---- bf16: 256-row tiles, 8 waves, transposing LDS reads of the weights ------------------------------
+template <int BM>
+__global__ void __launch_bounds__(kThreads2)
+gateup_bf16_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ x_perm, const int32_t* __restrict__ row_token,
+                   const int32_t* __restrict__ expert_off, const bf16_t* __restrict__ w_gate,
+                   const bf16_t* __restrict__ w_up, bf16_t* __restrict__ h, int d, int f, int E) {
+  constexpr int BNS = 128;                         // columns per source (gate, up) and block
+  typedef Tile2<BM, 2 * BNS, 2, 4> TL;
+  extern __shared__ __align__(16) char smem[];
+  __shared__ GroupTiles gt;
+  build_group_tiles(gt, expert_off, E, BM);
+  const int n_tiles = (f + BNS - 1) / BNS;
+  TileWalker tw;
+  tw.init(gt.tile_off[E] * n_tiles);
+  int idx;
+  while (tw.next(idx)) {
+    const int nt_blk = idx % n_tiles, mg = idx / n_tiles;
+    const int e = find_group(gt, E, mg);
+    const int row0 = gt.row_off[e] + (mg - gt.tile_off[e]) * BM;
+    const int valid = min(BM, gt.row_off[e + 1] - row0);
+    const int n0 = nt_blk * BNS;
+
+    LRows2<BM> L;
+    L.seg_stride = 0;
+#pragma unroll
+    for (int i = 0; i < LRows2<BM>::NV; ++i) {
+      const int r = min((int)(threadIdx.x >> 3) + 64 * i, valid - 1);
+      const bf16_t* src = x_perm ? x_perm + (size_t)(row0 + r) * d : x + (size_t)row_token[row0 + r] * d;
+      L.p[i] = reinterpret_cast<const char*>(src) + (threadIdx.x & 7) * 16;
+    }
+    RCols2<2 * BNS, 2> R;
+    const bf16_t* const base[2] = {w_gate + (size_t)e * d * f + n0, w_up + (size_t)e * d * f + n0};
+    R.init(base, f, min(BNS, f - n0), d);
+    typename TL::Acc acc;
+    TL::zero(acc);
+    TL::mainloop(acc, L, R, d / TL::BK, 1 << 30, smem);
+
+    const int ncol0 = n0 + TL::wave_n() * 32;      // the wave's 64-column slice is [gate 32 | up 32]
+#pragma unroll
+    for (int mt = 0; mt < TL::MT; ++mt) {
+      const int m = TL::acc_m(mt);
+      if (m >= valid) continue;
+      bf16_t* hrow = h + (size_t)(row0 + m) * f;
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const int n = ncol0 + TL::acc_n_local(0, g);
+        if (n >= f) continue;
+        const f32x16& G = acc[0][mt];
+        const f32x16& U = acc[1][mt];
+        store4(hrow + n, silu_f(G[4 * g]) * U[4 * g], silu_f(G[4 * g + 1]) * U[4 * g + 1],
+               silu_f(G[4 * g + 2]) * U[4 * g + 2], silu_f(G[4 * g + 3]) * U[4 * g + 3]);
+      }
+    }
+  }
+}
+
+template <int BM>
+__global__ void __launch_bounds__(kThreads2)
+down_bf16_kernel(const bf16_t* __restrict__ h, const int32_t* __restrict__ expert_off,
+                 const bf16_t* __restrict__ w_down, bf16_t* __restrict__ y, int d, int f, int E) {
+  constexpr int BN = 256;
+  typedef Tile2<BM, BN, 2, 4> TL;
+  extern __shared__ __align__(16) char smem[];
+  __shared__ GroupTiles gt;
+  build_group_tiles(gt, expert_off, E, BM);
+  const int n_tiles = (d + BN - 1) / BN;
+  TileWalker tw;
+  tw.init(gt.tile_off[E] * n_tiles);
+  int idx;
+  while (tw.next(idx)) {
+    const int nt_blk = idx % n_tiles, mg = idx / n_tiles;
+    const int e = find_group(gt, E, mg);
+    const int row0 = gt.row_off[e] + (mg - gt.tile_off[e]) * BM;
+    const int valid = min(BM, gt.row_off[e + 1] - row0);
+    const int n0 = nt_blk * BN;
+
+    LRows2<BM> L;
+    L.seg_stride = 0;
+#pragma unroll
+    for (int i = 0; i < LRows2<BM>::NV; ++i) {
+      const int r = min((int)(threadIdx.x >> 3) + 64 * i, valid - 1);
+      L.p[i] = reinterpret_cast<const char*>(h + (size_t)(row0 + r) * f) + (threadIdx.x & 7) * 16;
+    }
+    RCols2<BN, 1> R;
+    const bf16_t* const base[1] = {w_down + (size_t)e * f * d + n0};
+    R.init(base, d, min(BN, d - n0), f);
+    typename TL::Acc acc;
+    TL::zero(acc);
+    TL::mainloop(acc, L, R, f / TL::BK, 1 << 30, smem);
+
+    const int ncol0 = n0 + TL::wave_n() * TL::WN;
+#pragma unroll
+    for (int mt = 0; mt < TL::MT; ++mt) {
+      const int m = TL::acc_m(mt);
+      if (m >= valid) continue;
+      bf16_t* yrow = y + (size_t)(row0 + m) * d;
+#pragma unroll
+      for (int nt = 0; nt < TL::NT; ++nt)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const int n = ncol0 + TL::acc_n_local(nt, g);
+          if (n >= d) continue;
+          const f32x16& A = acc[nt][mt];
+          store4(yrow + n, A[4 * g], A[4 * g + 1], A[4 * g + 2], A[4 * g + 3]);
+        }
+    }
+  }
+}
+
+static hipError_t launch_ffn_bf16(const dsmoe_ctx* c, const void* x, const void* x_perm, const int32_t* row_token,
+                                  const int32_t* expert_off, const void* w_gate, const void* w_up,
+                                  const void* w_down, void* y_perm, hipStream_t s) {
+  constexpr int BM = 256;
+  typedef Tile2<BM, 256, 2, 4> TL;
+  const int d = c->desc.d_model, f = c->desc.d_ff, E = c->desc.n_experts;
+  bf16_t* h = reinterpret_cast<bf16_t*>(c->workspace + c->ws.h);
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e1 = hipFuncSetAttribute(reinterpret_cast<const void*>(&gateup_bf16_kernel<BM>),
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, TL::LDS_BYTES);
+    hipError_t e2 = hipFuncSetAttribute(reinterpret_cast<const void*>(&down_bf16_kernel<BM>),
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, TL::LDS_BYTES);
+    if (e1 != hipSuccess) return e1;
+    if (e2 != hipSuccess) return e2;
+    attr_set = true;
+  }
+  const long max_mt = (c->desc.max_rows + BM - 1) / BM + E;
+  const long t1 = max_mt * ((f + 127) / 128), t2 = max_mt * ((d + 255) / 256);
+  const int g1 = (int)((std::min<long>(t1, c->n_cu) + 7) / 8 * 8), g2 = (int)((std::min<long>(t2, c->n_cu) + 7) / 8 * 8);
+  hipEvent_t* ev = (c->prof.ev && c->prof.n < c->prof.max_calls) ? c->prof.ev + 3 * c->prof.n++ : nullptr;
+  if (ev) (void)hipEventRecord(ev[0], s);
+  gateup_bf16_kernel<BM><<<dim3(g1), dim3(kThreads2), TL::LDS_BYTES, s>>>(
+      (const bf16_t*)x, (const bf16_t*)x_perm, row_token, expert_off, (const bf16_t*)w_gate, (const bf16_t*)w_up, h,
+      d, f, E);
+  hipError_t err = hipGetLastError();
+  if (err != hipSuccess) return err;
+  if (ev) (void)hipEventRecord(ev[1], s);
+  down_bf16_kernel<BM><<<dim3(g2), dim3(kThreads2), TL::LDS_BYTES, s>>>(h, expert_off, (const bf16_t*)w_down,
+                                                                        (bf16_t*)y_perm, d, f, E);
+  err = hipGetLastError();
+  if (ev) (void)hipEventRecord(ev[2], s);
+  return err;
+}
+
 template <typename T>
 static hipError_t launch_ffn_t(const dsmoe_ctx* c, const void* x, const void* x_perm, const int32_t* row_token,
                                const int32_t* expert_off, const void* w_gate, const void* w_up, const void* w_down,
@@ -183,7 +327,7 @@ hipError_t launch_expert_ffn(const dsmoe_ctx* c, const void* x, const void* x_pe
                              const int32_t* expert_off, const void* w_gate, const void* w_up,
                              const void* w_down, void* y_perm, hipStream_t s) {
   if (c->desc.dtype == DSMOE_BF16)
-    return launch_ffn_t<bf16_t>(c, x, x_perm, row_token, expert_off, w_gate, w_up, w_down, y_perm, s);
+    return launch_ffn_bf16(c, x, x_perm, row_token, expert_off, w_gate, w_up, w_down, y_perm, s);
   return launch_ffn_t<float>(c, x, x_perm, row_token, expert_off, w_gate, w_up, w_down, y_perm, s);
 }
 
