@@ -159,7 +159,7 @@ gateup_bf16_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ x_pe
                    const int32_t* __restrict__ expert_off, const bf16_t* __restrict__ w_gate,
                    const bf16_t* __restrict__ w_up, bf16_t* __restrict__ h, int d, int f, int E) {
   constexpr int BNS = 128;                         // columns per source (gate, up) and block
-  typedef Tile2<BM, 2 * BNS, 2, 4> TL;
+  typedef Tile2<BM, 2 * BNS, 2, 4, 2> TL;
   extern __shared__ __align__(16) char smem[];
   __shared__ GroupTiles gt;
   build_group_tiles(gt, expert_off, E, BM);
@@ -178,9 +178,9 @@ gateup_bf16_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ x_pe
     L.seg_stride = 0;
 #pragma unroll
     for (int i = 0; i < LRows2<BM>::NV; ++i) {
-      const int r = min((int)(threadIdx.x >> 3) + 64 * i, valid - 1);
+      const int r = min((int)(threadIdx.x >> 2) + 128 * i, valid - 1);
       const bf16_t* src = x_perm ? x_perm + (size_t)(row0 + r) * d : x + (size_t)row_token[row0 + r] * d;
-      L.p[i] = reinterpret_cast<const char*>(src) + (threadIdx.x & 7) * 16;
+      L.p[i] = reinterpret_cast<const char*>(src) + (threadIdx.x & 3) * 16;
     }
     RCols2<2 * BNS, 2> R;
     const bf16_t* const base[2] = {w_gate + (size_t)e * d * f + n0, w_up + (size_t)e * d * f + n0};
@@ -189,7 +189,6 @@ gateup_bf16_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ x_pe
     TL::zero(acc);
     TL::mainloop(acc, L, R, d / TL::BK, 1 << 30, smem);
 
-    const int ncol0 = n0 + TL::wave_n() * 32;      // the wave's 64-column slice is [gate 32 | up 32]
 #pragma unroll
     for (int mt = 0; mt < TL::MT; ++mt) {
       const int m = TL::acc_m(mt);
@@ -197,7 +196,7 @@ gateup_bf16_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ x_pe
       bf16_t* hrow = h + (size_t)(row0 + m) * f;
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
-        const int n = ncol0 + TL::acc_n_local(0, g);
+        const int n = n0 + TL::acc_n(0, g);   // column tile 0 holds gate, tile 1 the same columns of up
         if (n >= f) continue;
         const f32x16& G = acc[0][mt];
         const f32x16& U = acc[1][mt];
@@ -232,8 +231,8 @@ down_bf16_kernel(const bf16_t* __restrict__ h, const int32_t* __restrict__ exper
     L.seg_stride = 0;
 #pragma unroll
     for (int i = 0; i < LRows2<BM>::NV; ++i) {
-      const int r = min((int)(threadIdx.x >> 3) + 64 * i, valid - 1);
-      L.p[i] = reinterpret_cast<const char*>(h + (size_t)(row0 + r) * f) + (threadIdx.x & 7) * 16;
+      const int r = min((int)(threadIdx.x >> 2) + 128 * i, valid - 1);
+      L.p[i] = reinterpret_cast<const char*>(h + (size_t)(row0 + r) * f) + (threadIdx.x & 3) * 16;
     }
     RCols2<BN, 1> R;
     const bf16_t* const base[1] = {w_down + (size_t)e * f * d + n0};
@@ -242,7 +241,6 @@ down_bf16_kernel(const bf16_t* __restrict__ h, const int32_t* __restrict__ exper
     TL::zero(acc);
     TL::mainloop(acc, L, R, f / TL::BK, 1 << 30, smem);
 
-    const int ncol0 = n0 + TL::wave_n() * TL::WN;
 #pragma unroll
     for (int mt = 0; mt < TL::MT; ++mt) {
       const int m = TL::acc_m(mt);
@@ -252,7 +250,7 @@ down_bf16_kernel(const bf16_t* __restrict__ h, const int32_t* __restrict__ exper
       for (int nt = 0; nt < TL::NT; ++nt)
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
-          const int n = ncol0 + TL::acc_n_local(nt, g);
+          const int n = n0 + TL::acc_n(nt, g);
           if (n >= d) continue;
           const f32x16& A = acc[nt][mt];
           store4(yrow + n, A[4 * g], A[4 * g + 1], A[4 * g + 2], A[4 * g + 3]);

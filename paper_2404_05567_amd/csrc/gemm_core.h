@@ -32,7 +32,15 @@ template <> struct ElemTraits<bf16_t> {
   static constexpr int BK = 64;
 };
 
-__device__ __forceinline__ u32x4 ldg16(const void* p) { return *reinterpret_cast<const u32x4*>(p); }
+// 16-byte load through the GLOBAL address space.  Pointers that reach the loaders through structs or
+// selects lose their address space; a generic (flat) load would also tie up the LDS counter and force
+// full waits, which serialises the software pipeline.
+typedef __attribute__((address_space(1))) const u32x4 global_u32x4;
+typedef __attribute__((address_space(1))) u32x4 global_u32x4_w;
+typedef __attribute__((address_space(1))) u32x2 global_u32x2_w;
+__device__ __forceinline__ u32x4 ldg16(const void* p) { return *(global_u32x4*)(p); }
+__device__ __forceinline__ void stg16(void* p, u32x4 v) { *(global_u32x4_w*)(p) = v; }
+__device__ __forceinline__ void stg8(void* p, u32x2 v) { *(global_u32x2_w*)(p) = v; }
 
 // ---- operand sources ---------------------------------------------------------------------------
 
@@ -226,7 +234,7 @@ struct Tile {
 // ---- output helpers ----------------------------------------------------------------------------
 __device__ __forceinline__ void store4(float* p, float a, float b, float c, float d) {
   f32x4 v = {a, b, c, d};
-  *reinterpret_cast<f32x4*>(p) = v;
+  stg16(p, __builtin_bit_cast(u32x4, v));
 }
 __device__ __forceinline__ unsigned pack_bf16x2(float lo, float hi) {
   typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
@@ -235,7 +243,7 @@ __device__ __forceinline__ unsigned pack_bf16x2(float lo, float hi) {
 }
 __device__ __forceinline__ void store4(bf16_t* p, float a, float b, float c, float d) {
   u32x2 v = {pack_bf16x2(a, b), pack_bf16x2(c, d)};
-  *reinterpret_cast<u32x2*>(p) = v;
+  stg8(p, v);
 }
 __device__ __forceinline__ float to_f32(float v) { return v; }
 __device__ __forceinline__ float to_f32(bf16_t v) { return (float)v; }
