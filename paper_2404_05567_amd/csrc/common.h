@@ -74,7 +74,9 @@ hipError_t launch_dispatch(const dsmoe_ctx* c, const void* x, const float* probs
 hipError_t launch_expert_ffn(const dsmoe_ctx* c, const void* x, const void* x_perm, const int32_t* row_token,
                              const int32_t* expert_off, const void* w_gate, const void* w_up,
                              const void* w_down, void* y_perm, hipStream_t s);
-// combine.hip
+hipError_t launch_down_dense(const dsmoe_ctx* c, const void* h, int T, int k_total, const void* w, void* out,
+                             hipStream_t s);
+// dispatch.hip (combine)
 hipError_t launch_combine(const dsmoe_ctx* c, const void* y_perm, const float* row_weight,
                           const int32_t* tok_off, const int32_t* tok_rows, int T, void* out, hipStream_t s);
 // dense.hip

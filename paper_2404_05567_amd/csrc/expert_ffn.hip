@@ -13,27 +13,6 @@
 
 namespace dsmoe {
 
-// Maps the block to its next tile: tiles are dealt to the 8 XCDs in 8 contiguous chunks (workgroup
-// ids are distributed round-robin over XCDs), so an XCD's L2 sees consecutive tiles of few experts.
-struct TileWalker {
-  int total, per, slots, xcd, i;
-  __device__ __forceinline__ void init(int total_tiles) {
-    total = total_tiles;
-    per = (total + 7) >> 3;
-    slots = gridDim.x >> 3;
-    xcd = blockIdx.x & 7;
-    i = blockIdx.x >> 3;
-  }
-  __device__ __forceinline__ bool next(int& idx) {
-    if (i >= per) return false;
-    idx = xcd * per + i;
-    i += slots;
-    return idx < total;
-  }
-};
-
-__device__ __forceinline__ float silu_f(float g) { return g / (1.f + __expf(-g)); }
-
 template <typename T, int BM, int BN>
 __global__ void __launch_bounds__(kThreads, 2)
 gateup_kernel(const T* __restrict__ x, const T* __restrict__ x_perm, const int32_t* __restrict__ row_token,
@@ -100,11 +79,11 @@ gateup_kernel(const T* __restrict__ x, const T* __restrict__ x_perm, const int32
 template <typename T, int BM, int BN>
 __global__ void __launch_bounds__(kThreads, 2)
 down_kernel(const T* __restrict__ h, const int32_t* __restrict__ expert_off, const T* __restrict__ w_down,
-            T* __restrict__ y, int d, int f, int E) {
+            T* __restrict__ y, int d, int f, int E, int uniform_rows) {
   typedef Tile<T, BM, BN, 1> TL;
   extern __shared__ __align__(16) char smem[];
   __shared__ GroupTiles gt;
-  build_group_tiles(gt, expert_off, E, BM);
+  build_group_tiles(gt, expert_off, E, BM, uniform_rows);
   const int n_tiles = (d + BN - 1) / BN;
   TileWalker tw;
   tw.init(gt.tile_off[E] * n_tiles);
@@ -210,12 +189,12 @@ gateup_bf16_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ x_pe
 template <int BM>
 __global__ void __launch_bounds__(kThreads2)
 down_bf16_kernel(const bf16_t* __restrict__ h, const int32_t* __restrict__ expert_off,
-                 const bf16_t* __restrict__ w_down, bf16_t* __restrict__ y, int d, int f, int E) {
+                 const bf16_t* __restrict__ w_down, bf16_t* __restrict__ y, int d, int f, int E, int uniform_rows) {
   constexpr int BN = 256;
   typedef Tile2<BM, BN, 2, 4> TL;
   extern __shared__ __align__(16) char smem[];
   __shared__ GroupTiles gt;
-  build_group_tiles(gt, expert_off, E, BM);
+  build_group_tiles(gt, expert_off, E, BM, uniform_rows);
   const int n_tiles = (d + BN - 1) / BN;
   TileWalker tw;
   tw.init(gt.tile_off[E] * n_tiles);
@@ -259,6 +238,21 @@ down_bf16_kernel(const bf16_t* __restrict__ h, const int32_t* __restrict__ exper
   }
 }
 
+// kernels whose dynamic LDS exceeds the default limit need the attribute once per process
+static hipError_t ffn_bf16_attrs() {
+  static bool attr_set = false;
+  if (attr_set) return hipSuccess;
+  typedef Tile2<256, 256, 2, 4> TL;
+  hipError_t e1 = hipFuncSetAttribute(reinterpret_cast<const void*>(&gateup_bf16_kernel<256>),
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, TL::LDS_BYTES);
+  hipError_t e2 = hipFuncSetAttribute(reinterpret_cast<const void*>(&down_bf16_kernel<256>),
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, TL::LDS_BYTES);
+  if (e1 != hipSuccess) return e1;
+  if (e2 != hipSuccess) return e2;
+  attr_set = true;
+  return hipSuccess;
+}
+
 static hipError_t launch_ffn_bf16(const dsmoe_ctx* c, const void* x, const void* x_perm, const int32_t* row_token,
                                   const int32_t* expert_off, const void* w_gate, const void* w_up,
                                   const void* w_down, void* y_perm, hipStream_t s) {
@@ -266,16 +260,7 @@ static hipError_t launch_ffn_bf16(const dsmoe_ctx* c, const void* x, const void*
   typedef Tile2<BM, 256, 2, 4> TL;
   const int d = c->desc.d_model, f = c->desc.d_ff, E = c->desc.n_experts;
   bf16_t* h = reinterpret_cast<bf16_t*>(c->workspace + c->ws.h);
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e1 = hipFuncSetAttribute(reinterpret_cast<const void*>(&gateup_bf16_kernel<BM>),
-                                        hipFuncAttributeMaxDynamicSharedMemorySize, TL::LDS_BYTES);
-    hipError_t e2 = hipFuncSetAttribute(reinterpret_cast<const void*>(&down_bf16_kernel<BM>),
-                                        hipFuncAttributeMaxDynamicSharedMemorySize, TL::LDS_BYTES);
-    if (e1 != hipSuccess) return e1;
-    if (e2 != hipSuccess) return e2;
-    attr_set = true;
-  }
+  if (hipError_t e = ffn_bf16_attrs()) return e;
   const long max_mt = (c->desc.max_rows + BM - 1) / BM + E;
   const long t1 = max_mt * ((f + 127) / 128), t2 = max_mt * ((d + 255) / 256);
   const int g1 = (int)((std::min<long>(t1, c->n_cu) + 7) / 8 * 8), g2 = (int)((std::min<long>(t2, c->n_cu) + 7) / 8 * 8);
@@ -288,7 +273,7 @@ static hipError_t launch_ffn_bf16(const dsmoe_ctx* c, const void* x, const void*
   if (err != hipSuccess) return err;
   if (ev) (void)hipEventRecord(ev[1], s);
   down_bf16_kernel<BM><<<dim3(g2), dim3(kThreads2), TL::LDS_BYTES, s>>>(h, expert_off, (const bf16_t*)w_down,
-                                                                        (bf16_t*)y_perm, d, f, E);
+                                                                        (bf16_t*)y_perm, d, f, E, 0);
   err = hipGetLastError();
   if (ev) (void)hipEventRecord(ev[2], s);
   return err;
@@ -315,10 +300,32 @@ static hipError_t launch_ffn_t(const dsmoe_ctx* c, const void* x, const void* x_
   if (err != hipSuccess) return err;
   if (ev) (void)hipEventRecord(ev[1], s);
   down_kernel<T, BM, BN2><<<dim3(g2), dim3(kThreads), lds2, s>>>((const T*)h, expert_off, (const T*)w_down,
-                                                                 (T*)y_perm, d, f, E);
+                                                                 (T*)y_perm, d, f, E, 0);
   err = hipGetLastError();
   if (ev) (void)hipEventRecord(ev[2], s);
   return err;
+}
+
+// out[t,:] = h[t,:] W for ONE group of T rows: h is [T, k_total], w is [k_total, d].  Used by the dense
+// layer, whose down projection over all experts is one product over the concatenated hidden width.
+hipError_t launch_down_dense(const dsmoe_ctx* c, const void* h, int T, int k_total, const void* w, void* out,
+                             hipStream_t s) {
+  const int d = c->desc.d_model;
+  if (c->desc.dtype == DSMOE_BF16) {
+    if (hipError_t e = ffn_bf16_attrs()) return e;
+    typedef Tile2<256, 256, 2, 4> TL;
+    const long tiles = (long)((T + 255) / 256) * ((d + 255) / 256);
+    const int g = (int)((std::min<long>(tiles, c->n_cu) + 7) / 8 * 8);
+    down_bf16_kernel<256><<<dim3(g), dim3(kThreads2), TL::LDS_BYTES, s>>>((const bf16_t*)h, nullptr, (const bf16_t*)w,
+                                                                          (bf16_t*)out, d, k_total, 1, T);
+  } else {
+    constexpr int BM = 128, BN = 256;
+    const long tiles = (long)((T + BM - 1) / BM) * ((d + BN - 1) / BN);
+    const int g = (int)((std::min<long>(tiles, c->n_cu * 2) + 7) / 8 * 8);
+    down_kernel<float, BM, BN><<<dim3(g), dim3(kThreads), Tile<float, BM, BN, 1>::LDS_BYTES, s>>>(
+        (const float*)h, nullptr, (const float*)w, (float*)out, d, k_total, 1, T);
+  }
+  return hipGetLastError();
 }
 
 hipError_t launch_expert_ffn(const dsmoe_ctx* c, const void* x, const void* x_perm, const int32_t* row_token,

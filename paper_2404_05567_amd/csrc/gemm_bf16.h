@@ -34,9 +34,12 @@ __device__ __forceinline__ u32x2 lds_read_tr16(const char* p) {
   return __builtin_bit_cast(u32x2, v);
 }
 
-// Token-side source: rows k-contiguous in memory; thread t stages rows t/4 + 128 i, 16-byte column t%4.
+// Operand whose rows are k-contiguous in memory (token activations, or a weight used transposed);
+// thread t stages rows t/4 + 128 i, 16-byte column t%4.  Usable on either side of the product.
 template <int ROWS>
 struct LRows2 {
+  static constexpr bool kKMajor = false;             // LDS tile is [row][k]
+  static constexpr int LDS = ROWS * kLPitch2;
   static constexpr int NV = ROWS / 128;
   const char* p[NV];   // row base + (t%4)*16, K segment 0
   size_t seg_stride;   // bytes between K segments
@@ -52,12 +55,15 @@ struct LRows2 {
   }
 };
 
-// Weight-side source: NSRC matrices stored [k][n] (n contiguous), each contributing BN / NSRC columns
+// Operand stored [k][n] with n contiguous (a weight matrix, or X^T / dY for the weight gradients);
+// usable on either side of the product.  NSRC matrices each contribute BN / NSRC columns
 // of the tile; source s occupies LDS columns [s * BN / NSRC, (s + 1) * BN / NSRC).  Columns past the
 // end of the matrix are read from a clamped (valid) address and never reach a stored output.
 // KTAIL: zero-fill k >= k_valid (needed only when K is not a multiple of 32).
 template <int BN, int NSRC, bool KTAIL = false>
 struct RCols2 {
+  static constexpr bool kKMajor = true;               // LDS tile is [k][n]
+  static constexpr int LDS = kBK2 * (BN * 2 + 64);
   static constexpr int CH = BN / 8;                   // 16-byte chunks per k row
   static constexpr int NV = kBK2 * CH / kThreads2;    // chunks per thread
   static constexpr int KSTEP = kThreads2 / CH;        // k rows between a thread's chunks
@@ -118,7 +124,9 @@ struct Interleave {
 };
 
 // NSRC = 2: the wave's NT = 2 column tiles are the same 32 columns of source 0 (gate) and source 1 (up).
-template <int BM_, int BN_, int WGM_, int WGN_, int NSRC_ = 1>
+// L_KMAJOR / R_KMAJOR: LDS layout of the token-side / weight-side tile ([k][col] read with the
+// transposing load, or [row][k] read with 16-byte loads); they must match the source types used.
+template <int BM_, int BN_, int WGM_, int WGN_, int NSRC_ = 1, bool L_KMAJOR = false, bool R_KMAJOR = true>
 struct Tile2 {
   static constexpr int BM = BM_, BN = BN_, WGM = WGM_, WGN = WGN_, NSRC = NSRC_;
   static_assert(WGM * WGN == 8, "8 waves");
@@ -126,14 +134,16 @@ struct Tile2 {
   static constexpr int WM = BM / WGM, WN = BN / WGN;
   static constexpr int MT = WM / 32, NT = WN / 32;
   static_assert(NSRC == 1 || NT == NSRC, "one column tile per source");
-  static constexpr int R_PITCH = BN * 2 + 64;
-  static constexpr int LDS_L = BM * kLPitch2, LDS_R = BK * R_PITCH, STAGE = LDS_L + LDS_R;
+  static constexpr int L_PITCH = L_KMAJOR ? BM * 2 + 64 : kLPitch2;
+  static constexpr int R_PITCH = R_KMAJOR ? BN * 2 + 64 : kLPitch2;
+  static constexpr int LDS_L = L_KMAJOR ? BK * L_PITCH : BM * L_PITCH;
+  static constexpr int LDS_R = R_KMAJOR ? BK * R_PITCH : BN * R_PITCH;
+  static constexpr int STAGE = LDS_L + LDS_R;
   static constexpr int LDS_BYTES = 2 * STAGE;
   // LDS column of the wave's first column, and distance between its column tiles
   static constexpr int WCOL = NSRC == 1 ? WN : 32, NT_COLS = NSRC == 1 ? 32 : BN / NSRC;
-  static constexpr int NFR = MT + 2 * NT;          // LDS reads per 16-wide K slice
+  static constexpr int NFR = (L_KMAJOR ? 2 : 1) * MT + (R_KMAJOR ? 2 : 1) * NT;   // LDS reads per 16-wide K slice
   typedef f32x16 Acc[NT][MT];
-  struct Frag { u32x4 x[MT]; u32x4 w[NT]; };
 
   static __device__ __forceinline__ void zero(Acc& acc) {
 #pragma unroll
@@ -144,72 +154,62 @@ struct Tile2 {
         for (int i = 0; i < 16; ++i) acc[nt][mt][i] = 0.f;
   }
 
-  static __device__ __forceinline__ const char* frag_l(const char* stage) {
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    return stage + ((wave / WGN) * WM + (lane & 31)) * kLPitch2 + (lane >> 5) * 16;
+  // lane base address inside a tile for 32-wide fragment `first` (in rows / columns of the tile)
+  template <bool KMAJOR>
+  static __device__ __forceinline__ const char* frag_base(const char* tile, int pitch, int first) {
+    const int lane = threadIdx.x & 63, r = lane & 15;
+    if (KMAJOR)   // transposing read: lane r of a 16-lane group addresses [k0 + r/4][n0 + 4*(r%4)]
+      return tile + ((lane >> 5) * 8 + (r >> 2)) * pitch + (first + ((lane >> 4) & 1) * 16 + (r & 3) * 4) * 2;
+    return tile + (first + (lane & 31)) * pitch + (lane >> 5) * 16;
   }
-  // transposing read: lane r of a 16-lane group addresses [k0 + r/4][n0 + 4*(r%4)]
-  static __device__ __forceinline__ const char* frag_r(const char* stage) {
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, r = lane & 15;
-    return stage + LDS_L + ((lane >> 5) * 8 + (r >> 2)) * R_PITCH +
-           ((wave % WGN) * WCOL + ((lane >> 4) & 1) * 16 + (r & 3) * 4) * 2;
-  }
-  static __device__ __forceinline__ void read_frag(Frag& f, const char* fL, const char* fR, int ks) {
-#pragma unroll
-    for (int mt = 0; mt < MT; ++mt) f.x[mt] = *reinterpret_cast<const u32x4*>(fL + mt * 32 * kLPitch2 + ks * 32);
-#pragma unroll
-    for (int nt = 0; nt < NT; ++nt) {
-      const u32x2 lo = lds_read_tr16(fR + (ks * 16) * R_PITCH + nt * NT_COLS * 2);
-      const u32x2 hi = lds_read_tr16(fR + (ks * 16 + 4) * R_PITCH + nt * NT_COLS * 2);
-      f.w[nt] = u32x4{lo.x, lo.y, hi.x, hi.y};
+  // fragment of 32 rows/columns starting `off` after the lane base, K slice ks (16 wide)
+  template <bool KMAJOR>
+  static __device__ __forceinline__ u32x4 read_frag(const char* base, int pitch, int off, int ks) {
+    if (KMAJOR) {
+      const u32x2 lo = lds_read_tr16(base + (ks * 16) * pitch + off * 2);
+      const u32x2 hi = lds_read_tr16(base + (ks * 16 + 4) * pitch + off * 2);
+      return u32x4{lo.x, lo.y, hi.x, hi.y};
     }
-  }
-  static __device__ __forceinline__ void mma(Acc& acc, const Frag& f) {
-#pragma unroll
-    for (int nt = 0; nt < NT; ++nt)
-#pragma unroll
-      for (int mt = 0; mt < MT; ++mt) Mma<bf16_t>::run(acc[nt][mt], f.w[nt], f.x[mt]);
+    return *reinterpret_cast<const u32x4*>(base + off * pitch + ks * 32);
   }
 
-  // MFMA work of one K step (two 16-wide slices) on LDS stage `cur` for the first NMT 32-row groups
-  // of the wave, the fragment reads of the second slice interleaved with the MFMAs of the first.
-  template <int NMT>
-  static __device__ __forceinline__ void compute_n(Acc& acc, const char* cur) {
-    constexpr int NMMA = NMT * NT, NRD = NMT + 2 * NT;
-    const char* fL = frag_l(cur);
-    const char* fR = frag_r(cur);
-    u32x4 xa[NMT], xb[NMT], wa[NT], wb[NT];
+  // MFMA work of one K step (two 16-wide slices) on LDS stage `cur`, the fragment reads of the second
+  // slice interleaved with the MFMAs of the first.
+  static __device__ __forceinline__ void compute(Acc& acc, const char* cur) {
+    constexpr int NMMA = MT * NT;
+    const int wave = threadIdx.x >> 6;
+    const char* fL = frag_base<L_KMAJOR>(cur, L_PITCH, (wave / WGN) * WM);
+    const char* fR = frag_base<R_KMAJOR>(cur + LDS_L, R_PITCH, (wave % WGN) * WCOL);
+    u32x4 xa[MT], xb[MT], wa[NT], wb[NT];
 #pragma unroll
-    for (int ks = 0; ks < 2; ++ks) {
-      u32x4(&x)[NMT] = ks ? xb : xa;
-      u32x4(&w)[NT] = ks ? wb : wa;
+    for (int mt = 0; mt < MT; ++mt) xa[mt] = read_frag<L_KMAJOR>(fL, L_PITCH, mt * 32, 0);
 #pragma unroll
-      for (int mt = 0; mt < NMT; ++mt) x[mt] = *reinterpret_cast<const u32x4*>(fL + mt * 32 * kLPitch2 + ks * 32);
+    for (int nt = 0; nt < NT; ++nt) wa[nt] = read_frag<R_KMAJOR>(fR, R_PITCH, nt * NT_COLS, 0);
 #pragma unroll
-      for (int nt = 0; nt < NT; ++nt) {
-        const u32x2 lo = lds_read_tr16(fR + (ks * 16) * R_PITCH + nt * NT_COLS * 2);
-        const u32x2 hi = lds_read_tr16(fR + (ks * 16 + 4) * R_PITCH + nt * NT_COLS * 2);
-        w[nt] = u32x4{lo.x, lo.y, hi.x, hi.y};
-      }
-    }
+    for (int mt = 0; mt < MT; ++mt) xb[mt] = read_frag<L_KMAJOR>(fL, L_PITCH, mt * 32, 1);
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) wb[nt] = read_frag<R_KMAJOR>(fR, R_PITCH, nt * NT_COLS, 1);
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
-      for (int mt = 0; mt < NMT; ++mt) Mma<bf16_t>::run(acc[nt][mt], wa[nt], xa[mt]);
+      for (int mt = 0; mt < MT; ++mt) Mma<bf16_t>::run(acc[nt][mt], wa[nt], xa[mt]);
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
-      for (int mt = 0; mt < NMT; ++mt) Mma<bf16_t>::run(acc[nt][mt], wb[nt], xb[mt]);
-    sched_group<kSgDsRd, NRD>();
-    Interleave<0, NMMA, NRD, kSgDsRd>::run();
+      for (int mt = 0; mt < MT; ++mt) Mma<bf16_t>::run(acc[nt][mt], wb[nt], xb[mt]);
+    sched_group<kSgDsRd, NFR>();
+    Interleave<0, NMMA, NFR, kSgDsRd>::run();
     sched_group<kSgMfma, NMMA>();
   }
+
   // acc += L * R over nkt K steps; K may be split in segments of seg_tiles steps (see the sources).
   // Step t is loaded into register slot t % 3 while step t - 4 is computed, written to LDS stage
   // t & 1 while step t - 1 is computed, and consumed one barrier later.
   template <typename LSrc, typename RSrc>
   static __device__ __forceinline__ void mainloop(Acc& acc, const LSrc& L, const RSrc& R, int nkt, int seg_tiles,
                                                   char* smem) {
+    static_assert(LSrc::kKMajor == L_KMAJOR && RSrc::kKMajor == R_KMAJOR, "source / tile layout mismatch");
+    static_assert(LSrc::LDS == LDS_L && RSrc::LDS == LDS_R, "source / tile size mismatch");
     u32x4 lr[kRegStages][LSrc::NV], rr[kRegStages][RSrc::NV];
     int seg = 0, kin = 0, next = 0;   // K position / index of the next step to load
     // Loads are issued unconditionally (steps past the end re-read the last one): the compiler can
@@ -231,7 +231,7 @@ struct Tile2 {
       L.store(a, nxt);                                  // step kt + 1 (a harmless re-store at the end)
       R.store(b, nxt + LDS_L);
       load_next(a, b);                                  // step kt + 4 into the slot just drained
-      compute_n<MT>(acc, smem + (kt & 1) * STAGE);
+      compute(acc, smem + (kt & 1) * STAGE);
       __syncthreads();
     };
     // three steps per trip with fixed register slots and no exits inside the loop body

@@ -253,10 +253,16 @@ struct GroupTiles {
   int tile_off[kMaxExperts + 1];   // exclusive prefix sum of ceil(cnt_e / BM)
   int row_off[kMaxExperts + 1];
 };
-__device__ __forceinline__ void build_group_tiles(GroupTiles& g, const int32_t* __restrict__ expert_off, int E, int BM) {
+// expert_off == nullptr: every group has uniform_rows rows (dense layer: all tokens in every expert).
+__device__ __forceinline__ void build_group_tiles(GroupTiles& g, const int32_t* __restrict__ expert_off, int E, int BM,
+                                                  int uniform_rows = 0) {
   if (threadIdx.x < 64) {
     const int e = threadIdx.x;
-    const int lo = e < E ? expert_off[e] : 0, hi = e < E ? expert_off[e + 1] : 0;
+    int lo = 0, hi = 0;
+    if (e < E) {
+      lo = expert_off ? expert_off[e] : e * uniform_rows;
+      hi = expert_off ? expert_off[e + 1] : (e + 1) * uniform_rows;
+    }
     int t = (hi - lo + BM - 1) / BM;
 #pragma unroll
     for (int s = 1; s < 64; s <<= 1) {
@@ -278,5 +284,26 @@ __device__ __forceinline__ int find_group(const GroupTiles& g, int E, int tile) 
   }
   return lo;
 }
+
+// Maps the block to its next tile: tiles are dealt to the 8 XCDs in 8 contiguous chunks (workgroup
+// ids are distributed round-robin over XCDs), so an XCD's L2 sees consecutive tiles of few experts.
+struct TileWalker {
+  int total, per, slots, xcd, i;
+  __device__ __forceinline__ void init(int total_tiles) {
+    total = total_tiles;
+    per = (total + 7) >> 3;
+    slots = gridDim.x >> 3;
+    xcd = blockIdx.x & 7;
+    i = blockIdx.x >> 3;
+  }
+  __device__ __forceinline__ bool next(int& idx) {
+    if (i >= per) return false;
+    idx = xcd * per + i;
+    i += slots;
+    return idx < total;
+  }
+};
+
+__device__ __forceinline__ float silu_f(float g) { return g / (1.f + __expf(-g)); }
 
 }  // namespace dsmoe
