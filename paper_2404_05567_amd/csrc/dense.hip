@@ -1,19 +1,491 @@
-// Dense-training forward and backward (paper Sec. 3.2 "Dense Training", Eq. 3).
-#include "gemm_core.h"
+// Dense-training forward and backward of the MoE layer (paper Sec. 3.2 "Dense Training", Eq. 3):
+// every expert runs on every token, O = sum_j S_j e_j(X), and the gradient flows through all of them.
+//
+// Forward      G_j = X W_gate[j], U_j = X W_up[j]              (kernel dense_gateup, grouped over j)
+//              Ht[:, j] = S_j * silu(G_j) * U_j                (its epilogue; G, U, Ht kept for backward)
+//              O = Ht [W_down[0]; ...; W_down[N-1]]             (one product over the concatenated width)
+// Backward     Eq. 3: grad e_j(X) = S_j dO and grad S_j = <e_j(X), dO>.  With D_j = dO W_down[j]^T the
+//              second is grad S_j = sum_c H_j[:, c] D_j[:, c] (H_j = silu(G_j) U_j), so the retained
+//              expert outputs e_j(X) of the paper's formulation are never materialised.
+//              dH_j = S_j D_j, dU_j = dH_j silu(G_j), dG_j = dH_j U_j silu'(G_j)    (kernel dense_bwd_dh)
+//              dW_down[j] = Ht_j^T dO                                               (kernel dense_bwd_dwdown)
+//              dW_gate[j] = X^T dG_j, dW_up[j] = X^T dU_j                           (kernel dense_bwd_dwgu)
+//              dZ = S (dS - sum_k S_k dS_k)   (softmax), dW_r = X^T dZ, db_r = sum_t dZ
+//              dX = sum_j dU_j W_up[j]^T + dG_j W_gate[j]^T + dZ W_r^T              (kernel dense_bwd_dx)
+// All reductions have a fixed order: results are bitwise reproducible.
+#include <algorithm>
+
+#include "gemm.h"
 
 namespace dsmoe {
 
-size_t dense_saved_bytes(const dsmoe_ctx* c, int T) { (void)c; (void)T; return 0; }
-size_t dense_bwd_scratch_bytes(const dsmoe_ctx* c, int T) { (void)c; (void)T; return 0; }
+namespace {
 
-hipError_t launch_dense_fwd(const dsmoe_ctx*, const void*, const void*, const void*, const void*, const void*,
-                            const void*, int, void*, float*, void*, hipStream_t) {
-  return hipErrorNotSupported;
+size_t al256(size_t v) { return (v + 255) / 256 * 256; }
+
+template <typename T> struct DenseTiles;
+template <> struct DenseTiles<float> { static constexpr int BM = 128, BN1 = 128, BN2 = 128; };
+template <> struct DenseTiles<bf16_t> { static constexpr int BM = 256, BN1 = 256, BN2 = 128; };
+
+struct SavedLayout { size_t S, G, U, Ht, total; };
+SavedLayout saved_layout(const dsmoe_ctx* c, int T) {
+  const size_t n = (size_t)T * c->desc.n_experts, nf = n * c->desc.d_ff * c->esize;
+  SavedLayout l;
+  size_t o = 0;
+  l.S = o; o = al256(o + n * 4);
+  l.G = o; o = al256(o + nf);
+  l.U = o; o = al256(o + nf);
+  l.Ht = o; o = al256(o + nf);
+  l.total = o;
+  return l;
 }
-hipError_t launch_dense_bwd(const dsmoe_ctx*, const void*, const void*, const void*, const void*, const void*,
-                            const void*, const void*, int, void*, void*, float*, float*, float*, float*, float*,
-                            hipStream_t) {
-  return hipErrorNotSupported;
+
+constexpr int kWrTokens = 512;   // tokens per block of the router weight-gradient kernel
+
+struct ScratchLayout { size_t dU, dG, dS_part, dZ, dWr_part, dbr_part, total; int ntb, nsplit; };
+ScratchLayout scratch_layout(const dsmoe_ctx* c, int T) {
+  const size_t E = c->desc.n_experts, n = (size_t)T * E, nf = n * c->desc.d_ff * c->esize;
+  const int bn1 = c->desc.dtype == DSMOE_BF16 ? DenseTiles<bf16_t>::BN1 : DenseTiles<float>::BN1;
+  ScratchLayout l;
+  l.ntb = (c->desc.d_ff + bn1 - 1) / bn1;
+  l.nsplit = std::max(1, (T + kWrTokens - 1) / kWrTokens);
+  size_t o = 0;
+  l.dU = o; o = al256(o + nf);
+  l.dG = o; o = al256(o + nf);
+  l.dS_part = o; o = al256(o + n * l.ntb * 4);
+  l.dZ = o; o = al256(o + n * 4);
+  l.dWr_part = o; o = al256(o + (size_t)l.nsplit * c->desc.d_model * E * 4);
+  l.dbr_part = o; o = al256(o + (size_t)l.nsplit * E * 4);
+  l.total = o;
+  return l;
+}
+
+__device__ __forceinline__ float sigmoid_f(float g) { return 1.f / (1.f + __expf(-g)); }
+
+template <typename T> __device__ __forceinline__ void load4(const T* p, float (&v)[4]);
+template <> __device__ __forceinline__ void load4<float>(const float* p, float (&v)[4]) {
+  const f32x4 q = __builtin_bit_cast(f32x4, ldg16(p));
+  v[0] = q.x; v[1] = q.y; v[2] = q.z; v[3] = q.w;
+}
+template <> __device__ __forceinline__ void load4<bf16_t>(const bf16_t* p, float (&v)[4]) {
+  typedef __attribute__((address_space(1))) const u32x2 g_u32x2;
+  const u32x2 q = *(g_u32x2*)(p);
+  v[0] = __uint_as_float(q.x << 16); v[1] = __uint_as_float(q.x & 0xffff0000u);
+  v[2] = __uint_as_float(q.y << 16); v[3] = __uint_as_float(q.y & 0xffff0000u);
+}
+
+// ---- forward: gate / up products of every expert on every token --------------------------------------
+template <typename T>
+__global__ void __launch_bounds__((Gemm<T, DenseTiles<T>::BM, DenseTiles<T>::BN2, 2, false, true>::THREADS))
+dense_gateup_kernel(const T* __restrict__ x, const T* __restrict__ w_gate, const T* __restrict__ w_up,
+                    const float* __restrict__ S, T* __restrict__ G, T* __restrict__ U, T* __restrict__ Ht, int Tn,
+                    int d, int f, int E) {
+  typedef Gemm<T, DenseTiles<T>::BM, DenseTiles<T>::BN2, 2, false, true> GM;
+  extern __shared__ __align__(16) char smem[];
+  const int n_mt = (Tn + GM::BM - 1) / GM::BM, n_nt = (f + GM::BN - 1) / GM::BN;
+  const size_t EF = (size_t)E * f;
+  TileWalker tw;
+  tw.init(E * n_mt * n_nt);
+  int idx;
+  while (tw.next(idx)) {
+    const int nt = idx % n_nt, mt = (idx / n_nt) % n_mt, e = idx / (n_nt * n_mt);
+    const int t0 = mt * GM::BM, n0 = nt * GM::BN;
+    typename GM::LSrc L;
+    GM::l_rows(L, min(GM::BM, Tn - t0), 0, [&](int r) { return x + (size_t)(t0 + r) * d; });
+    typename GM::RSrc R;
+    const T* const base[2] = {w_gate + (size_t)e * d * f + n0, w_up + (size_t)e * d * f + n0};
+    GM::r_cols(R, base, f, f - n0, d);
+    typename GM::Acc acc;
+    GM::zero(acc);
+    GM::mainloop(acc, L, R, d / GM::BK, 1 << 30, smem);
+    GM::for_each_quad(acc, [&](int m, int n, const float (&v)[2][4]) {
+      const int t = t0 + m, col = n0 + n;
+      if (t >= Tn || col >= f) return;
+      const float s = S[(size_t)t * E + e];
+      const size_t o = (size_t)t * EF + (size_t)e * f + col;
+      if (G != nullptr) {
+        store4(G + o, v[0][0], v[0][1], v[0][2], v[0][3]);
+        store4(U + o, v[1][0], v[1][1], v[1][2], v[1][3]);
+      }
+      store4(Ht + o, s * silu_f(v[0][0]) * v[1][0], s * silu_f(v[0][1]) * v[1][1], s * silu_f(v[0][2]) * v[1][2],
+             s * silu_f(v[0][3]) * v[1][3]);
+    });
+  }
+}
+
+// ---- backward: D_j = dO W_down[j]^T, then the SwiGLU backward and the score-gradient partial sums -----
+template <typename T>
+__global__ void __launch_bounds__((Gemm<T, DenseTiles<T>::BM, DenseTiles<T>::BN1, 1, false, false>::THREADS))
+dense_bwd_dh_kernel(const T* __restrict__ d_out, const T* __restrict__ w_down, const float* __restrict__ S,
+                    const T* __restrict__ G, const T* __restrict__ U, T* __restrict__ dU, T* __restrict__ dG,
+                    float* __restrict__ dS_part, int Tn, int d, int f, int E) {
+  typedef Gemm<T, DenseTiles<T>::BM, DenseTiles<T>::BN1, 1, false, false> GM;
+  extern __shared__ __align__(16) char smem[];
+  __shared__ float red[GM::WAVES_N][GM::BM];
+  const int n_mt = (Tn + GM::BM - 1) / GM::BM, n_nt = (f + GM::BN - 1) / GM::BN;
+  const size_t EF = (size_t)E * f;
+  const int lane = threadIdx.x & 63;
+  TileWalker tw;
+  tw.init(E * n_mt * n_nt);
+  int idx;
+  while (tw.next(idx)) {
+    const int nt = idx % n_nt, mt = (idx / n_nt) % n_mt, e = idx / (n_nt * n_mt);
+    const int t0 = mt * GM::BM, n0 = nt * GM::BN;
+    typename GM::LSrc L;
+    GM::l_rows(L, min(GM::BM, Tn - t0), 0, [&](int r) { return d_out + (size_t)(t0 + r) * d; });
+    typename GM::RSrc R;
+    GM::r_rows(R, min(GM::BN, f - n0), 0, [&](int r) { return w_down + ((size_t)e * f + n0 + r) * d; });
+    typename GM::Acc acc;
+    GM::zero(acc);
+    GM::mainloop(acc, L, R, d / GM::BK, 1 << 30, smem);
+
+    // a lane's quads of one 32-row group share the token; for_each_quad walks the row groups in order
+    float part = 0.f;
+    int cur_m = -1;
+    auto flush = [&]() {
+      if (cur_m < 0) return;
+      const float p = part + __shfl_xor(part, 32, 64);
+      if (lane < 32) red[GM::wave_n()][cur_m] = p;
+    };
+    GM::for_each_quad(acc, [&](int m, int n, const float (&v)[1][4]) {
+      if (m != cur_m) { flush(); cur_m = m; part = 0.f; }
+      const int t = t0 + m, col = n0 + n;
+      if (t >= Tn || col >= f) return;
+      const float s = S[(size_t)t * E + e];
+      const size_t o = (size_t)t * EF + (size_t)e * f + col;
+      float g[4], u[4], du[4], dg[4];
+      load4(G + o, g);
+      load4(U + o, u);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const float sg = sigmoid_f(g[i]), sl = g[i] * sg;
+        part = fmaf(sl * u[i], v[0][i], part);
+        const float dh = s * v[0][i];
+        du[i] = dh * sl;
+        dg[i] = dh * u[i] * (sg * (1.f + g[i] * (1.f - sg)));
+      }
+      store4(dU + o, du[0], du[1], du[2], du[3]);
+      store4(dG + o, dg[0], dg[1], dg[2], dg[3]);
+    });
+    flush();
+    __syncthreads();
+    for (int m = threadIdx.x; m < GM::BM; m += GM::THREADS) {
+      const int t = t0 + m;
+      if (t >= Tn) continue;
+      float p = red[0][m];
+#pragma unroll
+      for (int w = 1; w < GM::WAVES_N; ++w) p += red[w][m];
+      dS_part[((size_t)t * E + e) * n_nt + nt] = p;
+    }
+    // the next tile's main loop passes barriers before `red` is written again
+  }
+}
+
+// ---- backward: dW_down[j] = Ht_j^T dO (contraction over tokens) ------------------------------------------
+template <typename T>
+__global__ void __launch_bounds__((Gemm<T, DenseTiles<T>::BM, DenseTiles<T>::BN1, 1, true, true, true>::THREADS))
+dense_bwd_dwdown_kernel(const T* __restrict__ Ht, const T* __restrict__ d_out, float* __restrict__ dw_down, int Tn,
+                        int d, int f, int E) {
+  typedef Gemm<T, DenseTiles<T>::BM, DenseTiles<T>::BN1, 1, true, true, true> GM;
+  extern __shared__ __align__(16) char smem[];
+  const int n_mt = (f + GM::BM - 1) / GM::BM, n_nt = (d + GM::BN - 1) / GM::BN;
+  const size_t EF = (size_t)E * f;
+  TileWalker tw;
+  tw.init(E * n_mt * n_nt);
+  int idx;
+  while (tw.next(idx)) {
+    const int nt = idx % n_nt, mt = (idx / n_nt) % n_mt, e = idx / (n_nt * n_mt);
+    const int m0 = mt * GM::BM, n0 = nt * GM::BN;
+    typename GM::LSrc L;
+    GM::l_cols(L, Ht + (size_t)e * f + m0, EF, f - m0, Tn);
+    typename GM::RSrc R;
+    const T* const base[1] = {d_out + n0};
+    GM::r_cols(R, base, d, d - n0, Tn);
+    typename GM::Acc acc;
+    GM::zero(acc);
+    GM::mainloop(acc, L, R, (Tn + GM::BK - 1) / GM::BK, 1 << 30, smem);
+    GM::for_each_quad(acc, [&](int m, int n, const float (&v)[1][4]) {
+      if (m0 + m >= f || n0 + n >= d) return;
+      store4(dw_down + ((size_t)e * f + m0 + m) * d + n0 + n, v[0][0], v[0][1], v[0][2], v[0][3]);
+    });
+  }
+}
+
+// ---- backward: dW_gate[j] = X^T dG_j, dW_up[j] = X^T dU_j ---------------------------------------------
+template <typename T>
+__global__ void __launch_bounds__((Gemm<T, DenseTiles<T>::BM, DenseTiles<T>::BN2, 2, true, true, true>::THREADS))
+dense_bwd_dwgu_kernel(const T* __restrict__ x, const T* __restrict__ dG, const T* __restrict__ dU,
+                      float* __restrict__ dw_gate, float* __restrict__ dw_up, int Tn, int d, int f, int E) {
+  typedef Gemm<T, DenseTiles<T>::BM, DenseTiles<T>::BN2, 2, true, true, true> GM;
+  extern __shared__ __align__(16) char smem[];
+  const int n_mt = (d + GM::BM - 1) / GM::BM, n_nt = (f + GM::BN - 1) / GM::BN;
+  const size_t EF = (size_t)E * f;
+  TileWalker tw;
+  tw.init(E * n_mt * n_nt);
+  int idx;
+  while (tw.next(idx)) {
+    const int nt = idx % n_nt, mt = (idx / n_nt) % n_mt, e = idx / (n_nt * n_mt);
+    const int m0 = mt * GM::BM, n0 = nt * GM::BN;
+    typename GM::LSrc L;
+    GM::l_cols(L, x + m0, d, d - m0, Tn);
+    typename GM::RSrc R;
+    const T* const base[2] = {dG + (size_t)e * f + n0, dU + (size_t)e * f + n0};
+    GM::r_cols(R, base, EF, f - n0, Tn);
+    typename GM::Acc acc;
+    GM::zero(acc);
+    GM::mainloop(acc, L, R, (Tn + GM::BK - 1) / GM::BK, 1 << 30, smem);
+    GM::for_each_quad(acc, [&](int m, int n, const float (&v)[2][4]) {
+      if (m0 + m >= d || n0 + n >= f) return;
+      const size_t o = ((size_t)e * d + m0 + m) * f + n0 + n;
+      store4(dw_gate + o, v[0][0], v[0][1], v[0][2], v[0][3]);
+      store4(dw_up + o, v[1][0], v[1][1], v[1][2], v[1][3]);
+    });
+  }
+}
+
+// ---- backward: dX = sum_j dU_j W_up[j]^T + dG_j W_gate[j]^T + dZ W_r^T -----------------------------------
+template <typename T>
+__global__ void __launch_bounds__((Gemm<T, DenseTiles<T>::BM, DenseTiles<T>::BN1, 1, false, false>::THREADS))
+dense_bwd_dx_kernel(const T* __restrict__ dU, const T* __restrict__ dG, const T* __restrict__ w_up,
+                    const T* __restrict__ w_gate, const float* __restrict__ dZ, const T* __restrict__ w_r,
+                    T* __restrict__ dx, int Tn, int d, int f, int E) {
+  typedef Gemm<T, DenseTiles<T>::BM, DenseTiles<T>::BN1, 1, false, false> GM;
+  extern __shared__ __align__(16) char smem[];
+  const int n_mt = (Tn + GM::BM - 1) / GM::BM, n_nt = (d + GM::BN - 1) / GM::BN;
+  const size_t EF = (size_t)E * f;
+  TileWalker tw;
+  tw.init(n_mt * n_nt);
+  int idx;
+  while (tw.next(idx)) {
+    const int nt = idx % n_nt, mt = idx / n_nt;
+    const int t0 = mt * GM::BM, n0 = nt * GM::BN;
+    typename GM::Acc acc;
+    GM::zero(acc);
+#pragma unroll 1
+    for (int half = 0; half < 2; ++half) {
+      const T* a = half ? dG : dU;
+      const T* w = half ? w_gate : w_up;
+      // K runs over (expert, hidden unit): one segment of f per expert on both sides
+      typename GM::LSrc L;
+      GM::l_rows(L, min(GM::BM, Tn - t0), (size_t)f * sizeof(T), [&](int r) { return a + (size_t)(t0 + r) * EF; });
+      typename GM::RSrc R;
+      GM::r_rows(R, min(GM::BN, d - n0), (size_t)d * f * sizeof(T), [&](int r) { return w + (size_t)(n0 + r) * f; });
+      GM::mainloop(acc, L, R, (int)(EF / GM::BK), f / GM::BK, smem);
+    }
+    GM::for_each_quad(acc, [&](int m, int n, const float (&v)[1][4]) {
+      const int t = t0 + m, col = n0 + n;
+      if (t >= Tn || col >= d) return;
+      float o[4] = {v[0][0], v[0][1], v[0][2], v[0][3]};
+      const float* z = dZ + (size_t)t * E;
+      for (int e = 0; e < E; ++e) {
+        const float ze = z[e];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) o[i] = fmaf(ze, to_f32(w_r[(size_t)(col + i) * E + e]), o[i]);
+      }
+      store4(dx + (size_t)t * d + col, o[0], o[1], o[2], o[3]);
+    });
+  }
+}
+
+// ---- softmax backward: dZ = S (dS - sum_k S_k dS_k), one wave per token, one lane per expert -------------
+__global__ void __launch_bounds__(kThreads)
+dense_softmax_bwd_kernel(const float* __restrict__ S, const float* __restrict__ dS_part, int ntb, int Tn, int E,
+                         float* __restrict__ dZ) {
+  const int lane = threadIdx.x & 63;
+  const int t = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (t >= Tn) return;
+  float s = 0.f, ds = 0.f;
+  if (lane < E) {
+    s = S[(size_t)t * E + lane];
+    for (int j = 0; j < ntb; ++j) ds += dS_part[((size_t)t * E + lane) * ntb + j];
+  }
+  float dot = s * ds;
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) dot += __shfl_xor(dot, o, 64);
+  if (lane < E) dZ[(size_t)t * E + lane] = s * (ds - dot);
+}
+
+// ---- router weight gradient: partial dW_r = X^T dZ and db_r = sum_t dZ over a slab of tokens ---------------
+// grid (d / 64, n_split); thread (i = tid % 64, expert group tid / 64) accumulates E/4 experts.
+template <typename T>
+__global__ void __launch_bounds__(kThreads)
+dense_router_dw_kernel(const T* __restrict__ x, const float* __restrict__ dZ, int Tn, int d, int E,
+                       float* __restrict__ dWr_part, float* __restrict__ dbr_part) {
+  __shared__ float sX[64][65];
+  __shared__ float sZ[64][kMaxExperts];
+  const int i0 = blockIdx.x * 64, il = threadIdx.x & 63, eg = threadIdx.x >> 6, ept = E / 4;
+  const int tb = blockIdx.y * kWrTokens, te = min(Tn, tb + kWrTokens);
+  float acc[kMaxExperts / 4];
+#pragma unroll
+  for (int j = 0; j < kMaxExperts / 4; ++j) acc[j] = 0.f;
+  float bsum = 0.f;
+  for (int c0 = tb; c0 < te; c0 += 64) {
+    __syncthreads();
+    for (int q = threadIdx.x; q < 64 * 64; q += kThreads) {
+      const int tt = q >> 6, ii = q & 63;
+      sX[tt][ii] = c0 + tt < te ? to_f32(x[(size_t)(c0 + tt) * d + i0 + ii]) : 0.f;
+    }
+    for (int q = threadIdx.x; q < 64 * E; q += kThreads) {
+      const int tt = q / E, ee = q % E;
+      sZ[tt][ee] = c0 + tt < te ? dZ[(size_t)(c0 + tt) * E + ee] : 0.f;
+    }
+    __syncthreads();
+    for (int tt = 0; tt < 64; ++tt) {
+      const float xv = sX[tt][il];
+#pragma unroll
+      for (int j = 0; j < kMaxExperts / 4; ++j)
+        if (j < ept) acc[j] = fmaf(xv, sZ[tt][eg * ept + j], acc[j]);
+    }
+    if (blockIdx.x == 0 && threadIdx.x < E)
+      for (int tt = 0; tt < 64; ++tt) bsum += sZ[tt][threadIdx.x];
+  }
+  float* out = dWr_part + (size_t)blockIdx.y * d * E;
+#pragma unroll
+  for (int j = 0; j < kMaxExperts / 4; ++j)
+    if (j < ept) out[(size_t)(i0 + il) * E + eg * ept + j] = acc[j];
+  if (blockIdx.x == 0 && threadIdx.x < E) dbr_part[(size_t)blockIdx.y * E + threadIdx.x] = bsum;
+}
+
+__global__ void __launch_bounds__(kThreads)
+dense_router_dw_reduce_kernel(const float* __restrict__ dWr_part, const float* __restrict__ dbr_part, int nsplit,
+                              int n, int E, float* __restrict__ dw_r, float* __restrict__ db_r) {
+  const int i = blockIdx.x * kThreads + threadIdx.x;
+  if (i < n) {
+    float s = 0.f;
+    for (int k = 0; k < nsplit; ++k) s += dWr_part[(size_t)k * n + i];
+    dw_r[i] = s;
+  }
+  if (db_r != nullptr && i < E) {
+    float s = 0.f;
+    for (int k = 0; k < nsplit; ++k) s += dbr_part[(size_t)k * E + i];
+    db_r[i] = s;
+  }
+}
+
+template <typename K>
+hipError_t set_lds(K kernel, int bytes) {
+  if (bytes <= 48 * 1024) return hipSuccess;
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+}
+
+int grid_for(const dsmoe_ctx* c, long tiles, int blocks_per_cu) {
+  const long full = (long)c->n_cu * blocks_per_cu;
+  return (int)((std::min(tiles, full) + 7) / 8 * 8);
+}
+
+template <typename T>
+hipError_t dense_fwd_t(const dsmoe_ctx* c, const void* x, const void* w_gate, const void* w_up, const void* w_down,
+                       int Tn, const float* S, T* G, T* U, T* Ht, void* out, hipStream_t s) {
+  typedef Gemm<T, DenseTiles<T>::BM, DenseTiles<T>::BN2, 2, false, true> GM;
+  const int d = c->desc.d_model, f = c->desc.d_ff, E = c->desc.n_experts;
+  constexpr int bpc = sizeof(T) == 4 ? 2 : 1;
+  static bool attrs = false;
+  if (!attrs) {
+    if (hipError_t e = set_lds(dense_gateup_kernel<T>, GM::LDS_BYTES)) return e;
+    attrs = true;
+  }
+  const long tiles = (long)E * ((Tn + GM::BM - 1) / GM::BM) * ((f + GM::BN - 1) / GM::BN);
+  dense_gateup_kernel<T><<<dim3(grid_for(c, tiles, bpc)), dim3(GM::THREADS), GM::LDS_BYTES, s>>>(
+      (const T*)x, (const T*)w_gate, (const T*)w_up, S, G, U, Ht, Tn, d, f, E);
+  if (hipError_t e = hipGetLastError()) return e;
+  return launch_down_dense(c, Ht, Tn, E * f, w_down, out, s);
+}
+
+template <typename T>
+hipError_t dense_bwd_t(const dsmoe_ctx* c, const void* x, const void* w_r, const void* w_gate, const void* w_up,
+                       const void* w_down, const char* saved, const void* d_out, int Tn, char* scratch, void* dx,
+                       float* dw_r, float* db_r, float* dw_gate, float* dw_up, float* dw_down, hipStream_t s) {
+  typedef DenseTiles<T> DT;
+  typedef Gemm<T, DT::BM, DT::BN1, 1, false, false> GRR;
+  typedef Gemm<T, DT::BM, DT::BN1, 1, true, true, true> GCC1;
+  typedef Gemm<T, DT::BM, DT::BN2, 2, true, true, true> GCC2;
+  const int d = c->desc.d_model, f = c->desc.d_ff, E = c->desc.n_experts;
+  constexpr int bpc = sizeof(T) == 4 ? 2 : 1;
+  const SavedLayout sv = saved_layout(c, Tn);
+  const ScratchLayout sc = scratch_layout(c, Tn);
+  const float* S = reinterpret_cast<const float*>(saved + sv.S);
+  const T* G = reinterpret_cast<const T*>(saved + sv.G);
+  const T* U = reinterpret_cast<const T*>(saved + sv.U);
+  const T* Ht = reinterpret_cast<const T*>(saved + sv.Ht);
+  T* dU = reinterpret_cast<T*>(scratch + sc.dU);
+  T* dG = reinterpret_cast<T*>(scratch + sc.dG);
+  float* dS_part = reinterpret_cast<float*>(scratch + sc.dS_part);
+  float* dZ = reinterpret_cast<float*>(scratch + sc.dZ);
+  float* dWr_part = reinterpret_cast<float*>(scratch + sc.dWr_part);
+  float* dbr_part = reinterpret_cast<float*>(scratch + sc.dbr_part);
+  auto cdiv = [](long a, long b) { return (a + b - 1) / b; };
+
+  static bool attrs = false;
+  if (!attrs) {
+    if (hipError_t e = set_lds(dense_bwd_dh_kernel<T>, GRR::LDS_BYTES)) return e;
+    if (hipError_t e = set_lds(dense_bwd_dx_kernel<T>, GRR::LDS_BYTES)) return e;
+    if (hipError_t e = set_lds(dense_bwd_dwdown_kernel<T>, GCC1::LDS_BYTES)) return e;
+    if (hipError_t e = set_lds(dense_bwd_dwgu_kernel<T>, GCC2::LDS_BYTES)) return e;
+    attrs = true;
+  }
+
+  long tiles = E * cdiv(Tn, DT::BM) * cdiv(f, DT::BN1);
+  dense_bwd_dh_kernel<T><<<dim3(grid_for(c, tiles, bpc)), dim3(GRR::THREADS), GRR::LDS_BYTES, s>>>(
+      (const T*)d_out, (const T*)w_down, S, G, U, dU, dG, dS_part, Tn, d, f, E);
+  if (hipError_t e = hipGetLastError()) return e;
+
+  dense_softmax_bwd_kernel<<<dim3((Tn + 3) / 4), dim3(kThreads), 0, s>>>(S, dS_part, sc.ntb, Tn, E, dZ);
+  if (hipError_t e = hipGetLastError()) return e;
+
+  dense_router_dw_kernel<T><<<dim3(d / 64, sc.nsplit), dim3(kThreads), 0, s>>>((const T*)x, dZ, Tn, d, E, dWr_part,
+                                                                              dbr_part);
+  if (hipError_t e = hipGetLastError()) return e;
+  dense_router_dw_reduce_kernel<<<dim3((d * E + kThreads - 1) / kThreads), dim3(kThreads), 0, s>>>(
+      dWr_part, dbr_part, sc.nsplit, d * E, E, dw_r, db_r);
+  if (hipError_t e = hipGetLastError()) return e;
+
+  tiles = E * cdiv(f, DT::BM) * cdiv(d, DT::BN1);
+  dense_bwd_dwdown_kernel<T><<<dim3(grid_for(c, tiles, bpc)), dim3(GCC1::THREADS), GCC1::LDS_BYTES, s>>>(
+      Ht, (const T*)d_out, dw_down, Tn, d, f, E);
+  if (hipError_t e = hipGetLastError()) return e;
+
+  tiles = E * cdiv(d, DT::BM) * cdiv(f, DT::BN2);
+  dense_bwd_dwgu_kernel<T><<<dim3(grid_for(c, tiles, bpc)), dim3(GCC2::THREADS), GCC2::LDS_BYTES, s>>>(
+      (const T*)x, dG, dU, dw_gate, dw_up, Tn, d, f, E);
+  if (hipError_t e = hipGetLastError()) return e;
+
+  tiles = cdiv(Tn, DT::BM) * cdiv(d, DT::BN1);
+  dense_bwd_dx_kernel<T><<<dim3(grid_for(c, tiles, bpc)), dim3(GRR::THREADS), GRR::LDS_BYTES, s>>>(
+      dU, dG, (const T*)w_up, (const T*)w_gate, dZ, (const T*)w_r, (T*)dx, Tn, d, f, E);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+size_t dense_saved_bytes(const dsmoe_ctx* c, int T) { return saved_layout(c, T).total; }
+size_t dense_bwd_scratch_bytes(const dsmoe_ctx* c, int T) { return scratch_layout(c, T).total; }
+
+hipError_t launch_dense_fwd(const dsmoe_ctx* c, const void* x, const void* w_r, const void* b_r, const void* w_gate,
+                            const void* w_up, const void* w_down, int T, void* out, float* probs, void* saved,
+                            hipStream_t s) {
+  const int E = c->desc.n_experts;
+  char* sv = static_cast<char*>(saved);
+  const SavedLayout l = saved_layout(c, T);
+  float* S = sv ? reinterpret_cast<float*>(sv + l.S) : (probs ? probs : reinterpret_cast<float*>(c->workspace + c->ws.probs));
+  if (hipError_t e = launch_route(c, x, w_r, b_r, T, S, -1, 0, 0.f, nullptr, nullptr, s)) return e;
+  if (probs != nullptr && probs != S)
+    if (hipError_t e = hipMemcpyAsync(probs, S, (size_t)T * E * 4, hipMemcpyDeviceToDevice, s)) return e;
+  void* G = sv ? sv + l.G : nullptr;
+  void* U = sv ? sv + l.U : nullptr;
+  void* Ht = sv ? sv + l.Ht : c->workspace + c->ws.h;
+  if (c->desc.dtype == DSMOE_BF16)
+    return dense_fwd_t<bf16_t>(c, x, w_gate, w_up, w_down, T, S, (bf16_t*)G, (bf16_t*)U, (bf16_t*)Ht, out, s);
+  return dense_fwd_t<float>(c, x, w_gate, w_up, w_down, T, S, (float*)G, (float*)U, (float*)Ht, out, s);
+}
+
+hipError_t launch_dense_bwd(const dsmoe_ctx* c, const void* x, const void* w_r, const void* w_gate, const void* w_up,
+                            const void* w_down, const void* saved, const void* d_out, int T, void* scratch, void* dx,
+                            float* dw_r, float* db_r, float* dw_gate, float* dw_up, float* dw_down, hipStream_t s) {
+  if (c->desc.dtype == DSMOE_BF16)
+    return dense_bwd_t<bf16_t>(c, x, w_r, w_gate, w_up, w_down, (const char*)saved, d_out, T, (char*)scratch, dx, dw_r,
+                               db_r, dw_gate, dw_up, dw_down, s);
+  return dense_bwd_t<float>(c, x, w_r, w_gate, w_up, w_down, (const char*)saved, d_out, T, (char*)scratch, dx, dw_r,
+                            db_r, dw_gate, dw_up, dw_down, s);
 }
 
 }  // namespace dsmoe

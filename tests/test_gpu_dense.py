@@ -1,0 +1,209 @@
+"""GPU parity of the dense-training forward and backward (Sec. 3.2 "Dense Training", Eq. 3) against the
+CPU checker, through the C ABI.
+
+Bar: every output tensor (O, the scores, and each gradient separately) within
+max|gpu - ref| / max|ref| <= 1e-5 (fp32) or 2e-2 (bf16 storage, fp32 accumulation).
+"""
+import sys
+
+import numpy as np
+import pytest
+
+import dsmoe_inputs as gen
+from oracle import dsmoe_oracle as orc
+from tests import helpers
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"f32": 1e-5, "bf16": 2e-2}
+
+
+def say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+@pytest.fixture(scope="module")
+def torch():
+    import torch
+    assert torch.cuda.is_available()
+    return torch
+
+
+@pytest.fixture(scope="module")
+def dsmoe():
+    import paper_2404_05567_amd as m
+    m.load_library()      # raises if the HIP library is missing: there is no fallback
+    return m
+
+
+def dev(torch, a, dtype):
+    if a is None:
+        return None
+    t = torch.from_numpy(np.ascontiguousarray(a)).to("cuda:0")
+    return t.to(torch.bfloat16) if dtype == "bf16" else t
+
+
+def to_dev(torch, inp):
+    dt = inp.cfg.dtype
+    return {k: dev(torch, getattr(inp, k), dt) for k in ("x", "w_r", "b_r", "w_gate", "w_up", "w_down", "d_out")}
+
+
+def host(t):
+    return t.float().cpu().numpy()
+
+
+def check_dense(torch, dsmoe, cfg, bias=False, variant=0):
+    T, E, tol = cfg.T, cfg.E, TOL[cfg.dtype]
+    say(f"[case] dense {cfg.name} T={T} d={cfg.d} E={E} f={cfg.f} {cfg.dtype} bias={bias}")
+    inp = gen.make_layer(cfg, variant, with_grad=True)
+    if bias and inp.b_r is None:
+        g = np.random.default_rng(cfg.index)
+        inp.b_r = gen.round_to_bf16(g.standard_normal(E).astype(np.float32) * 0.5) if cfg.dtype == "bf16" \
+            else (g.standard_normal(E) * 0.5).astype(np.float32)
+    w = to_dev(torch, inp)
+    layer = dsmoe.Layer(cfg.d, cfg.f, E, cfg.dtype, max_tokens=max(T, 1))
+
+    O_ref, S_ref, _ = orc.dense_forward(inp.x, inp.w_r, inp.b_r, inp.w_gate, inp.w_up, inp.w_down)
+    gr = orc.dense_backward(inp.x, inp.w_r, inp.b_r, inp.w_gate, inp.w_up, inp.w_down, inp.d_out)
+
+    out, probs, saved = layer.dense_fwd(w["x"], w["w_r"], w["b_r"], w["w_gate"], w["w_up"], w["w_down"],
+                                        want_probs=True, save=True)
+    torch.cuda.synchronize()
+    assert helpers.rel_err(host(probs), S_ref) <= 1e-5
+    err = helpers.rel_err(host(out), O_ref)
+    say(f"  forward rel err {err:.3e}")
+    assert err <= tol
+
+    # inference-only forward (nothing saved) gives the same output
+    out2, _, _ = layer.dense_fwd(w["x"], w["w_r"], w["b_r"], w["w_gate"], w["w_up"], w["w_down"])
+    torch.cuda.synchronize()
+    assert torch.equal(out, out2)
+
+    g = layer.dense_bwd(w["x"], w["w_r"], w["w_gate"], w["w_up"], w["w_down"], saved, w["d_out"],
+                        with_bias_grad=bias)
+    torch.cuda.synchronize()
+    refs = dict(dx=gr.dX, dw_r=gr.dW_r, dw_gate=gr.dW_gate, dw_up=gr.dW_up, dw_down=gr.dW_down)
+    if bias:
+        refs["db_r"] = gr.db_r
+    for name, ref in refs.items():
+        e = helpers.rel_err(host(g[name]), ref)
+        say(f"  {name} rel err {e:.3e}")
+        assert e <= tol, name
+    return layer, w, saved, g
+
+
+def test_c1_dense_forward_and_backward_fp32(torch, dsmoe):
+    check_dense(torch, dsmoe, gen.CONFIGS["c1"])
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_ragged_shapes_with_router_bias(torch, dsmoe, dtype):
+    # T below / not a multiple of any tile or K step, ragged column tiles, several tiles per expert
+    for T, d, E, f in [(77, 192, 8, 64), (333, 320, 16, 192)]:
+        cfg = gen.LayerConfig("dense_ragged", 21, T=T, d=d, E=E, f=f, dtype=dtype, mode="topk", k=1,
+                              router_std=0.08)
+        check_dense(torch, dsmoe, cfg, bias=True)
+
+
+def test_bf16_multi_tile(torch, dsmoe):
+    cfg = gen.LayerConfig("dense_mid", 22, T=1000, d=512, E=8, f=512, dtype="bf16", mode="topk", k=1,
+                          router_std=1.5 / np.sqrt(512))
+    check_dense(torch, dsmoe, cfg)
+
+
+def test_sixty_four_experts(torch, dsmoe):
+    cfg = gen.LayerConfig("dense_e64", 23, T=200, d=256, E=64, f=64, dtype="bf16", mode="topk", k=1,
+                          router_std=0.1)
+    check_dense(torch, dsmoe, cfg, bias=True)
+
+
+def test_repeated_backward_is_bitwise_identical(torch, dsmoe):
+    cfg = gen.LayerConfig("dense_det", 24, T=600, d=256, E=8, f=128, dtype="bf16", mode="topk", k=1,
+                          router_std=0.1)
+    layer, w, saved, g1 = check_dense(torch, dsmoe, cfg)
+    g2 = layer.dense_bwd(w["x"], w["w_r"], w["w_gate"], w["w_up"], w["w_down"], saved, w["d_out"])
+    torch.cuda.synchronize()
+    for k in ("dx", "dw_r", "dw_gate", "dw_up", "dw_down"):
+        assert torch.equal(g1[k], g2[k]), k
+
+
+def test_no_tokens(torch, dsmoe):
+    cfg = gen.CONFIGS["c1"]
+    inp = gen.make_layer(cfg.with_(T=0), 0, with_grad=True)
+    w = to_dev(torch, inp)
+    layer = dsmoe.Layer(cfg.d, cfg.f, cfg.E, cfg.dtype, max_tokens=8)
+    out, _, saved = layer.dense_fwd(w["x"], w["w_r"], None, w["w_gate"], w["w_up"], w["w_down"], save=True)
+    assert out.shape[0] == 0
+    g = layer.dense_bwd(w["x"], w["w_r"], w["w_gate"], w["w_up"], w["w_down"], saved, w["d_out"], with_bias_grad=True)
+    torch.cuda.synchronize()
+    for k in ("dw_r", "db_r", "dw_gate", "dw_up", "dw_down"):
+        assert float(g[k].abs().max().item()) == 0.0
+
+
+def test_forward_without_saved_needs_room_in_the_workspace(torch, dsmoe):
+    cfg = gen.CONFIGS["c1"]
+    inp = gen.make_layer(cfg, 0)
+    w = to_dev(torch, gen.make_layer(cfg, 0, with_grad=True))
+    layer = dsmoe.Layer(cfg.d, cfg.f, cfg.E, cfg.dtype, max_tokens=cfg.T, max_rows=cfg.T * 2)
+    with pytest.raises(dsmoe.DsmoeError) as ei:
+        layer.dense_fwd(w["x"], w["w_r"], None, w["w_gate"], w["w_up"], w["w_down"])
+    assert ei.value.code == dsmoe.ERR_WORKSPACE
+    out, _, _ = layer.dense_fwd(w["x"], w["w_r"], None, w["w_gate"], w["w_up"], w["w_down"], save=True)
+    torch.cuda.synchronize()
+    O_ref, _, _ = orc.dense_forward(inp.x, inp.w_r, None, inp.w_gate, inp.w_up, inp.w_down)
+    assert helpers.rel_err(host(out), O_ref) <= 1e-5
+
+
+# --------------------------------------------------------------------------------------------------
+# full training size, in the launch configuration bench.py times
+# --------------------------------------------------------------------------------------------------
+def test_c4_full_size_dense_training(torch, dsmoe):
+    cfg = gen.CONFIGS["c4"]
+    T, E, tol = cfg.T, cfg.E, TOL["bf16"]
+    say("[case] full-size c4: generating inputs")
+    inp = gen.make_layer(cfg, 0, with_grad=True)
+    w = to_dev(torch, inp)
+    layer = dsmoe.Layer(cfg.d, cfg.f, E, cfg.dtype, max_tokens=T, max_rows=T)
+    out, probs, saved = layer.dense_fwd(w["x"], w["w_r"], None, w["w_gate"], w["w_up"], w["w_down"],
+                                        want_probs=True, save=True)
+    g = layer.dense_bwd(w["x"], w["w_r"], w["w_gate"], w["w_up"], w["w_down"], saved, w["d_out"])
+    torch.cuda.synchronize()
+    say("[case] full-size c4: GPU done, checker running")
+
+    # scores, score gradients and the router weight gradient for every token, a slab of tokens at a time
+    S_ref = orc.route(inp.x, inp.w_r, None)
+    assert helpers.rel_err(host(probs), S_ref) <= 1e-5
+    dW_r = np.zeros((cfg.d, E))
+    for lo in range(0, T, 1024):
+        tok = np.arange(lo, min(T, lo + 1024))
+        _, _, Y = orc.dense_forward(inp.x, inp.w_r, None, inp.w_gate, inp.w_up, inp.w_down, tokens=tok)
+        dZ = orc.softmax_backward(S_ref[tok], orc.grad_scores(Y, inp.d_out[tok]))
+        dW_r += inp.x[tok].astype(np.float64).T @ dZ
+    e = helpers.rel_err(host(g["dw_r"]), dW_r)
+    say(f"  dw_r rel err {e:.3e}")
+    assert e <= tol
+
+    # token-wise outputs on sampled tokens (a token's O and dX depend on no other token)
+    rs = np.random.default_rng(4)
+    tok = np.sort(rs.choice(T, size=64, replace=False))
+    tok[0], tok[-1] = 0, T - 1
+    O_ref, _, _ = orc.dense_forward(inp.x, inp.w_r, None, inp.w_gate, inp.w_up, inp.w_down, tokens=tok)
+    e = helpers.rel_err(host(out)[tok], O_ref)
+    say(f"  forward (sampled tokens) rel err {e:.3e}")
+    assert e <= tol
+    gs = orc.dense_backward(inp.x[tok], inp.w_r, None, inp.w_gate, inp.w_up, inp.w_down, inp.d_out[tok])
+    e = helpers.rel_err(host(g["dx"])[tok], gs.dX)
+    say(f"  dx (sampled tokens) rel err {e:.3e}")
+    assert e <= tol
+
+    # expert weight gradients of sampled experts over all tokens
+    for j in (0, 13, E - 1):
+        _, dWg, dWu, dWd = orc.expert_backward(inp.x, S_ref[:, j], inp.w_gate[j], inp.w_up[j], inp.w_down[j],
+                                               inp.d_out)
+        for name, ref in (("dw_gate", dWg), ("dw_up", dWu), ("dw_down", dWd)):
+            e = helpers.rel_err(host(g[name][j]), ref)
+            say(f"  {name}[{j}] rel err {e:.3e}")
+            assert e <= tol
+    for k in ("dx", "dw_r", "dw_gate", "dw_up", "dw_down"):
+        assert bool(torch.isfinite(g[k].float()).all()), k
