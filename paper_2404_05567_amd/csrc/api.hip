@@ -1,5 +1,6 @@
 // C-ABI entry points of libdsmoe: argument validation, workspace carve-up and kernel sequencing.
 // All arithmetic lives in the kernels; nothing here touches tensor data on the host.
+#include <algorithm>
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
@@ -50,6 +51,10 @@ WorkspaceLayout make_layout(const dsmoe_desc& d, size_t esize) {
   w.tok_rows = take(rows * 4);
   w.nnz = take(4);
   w.y_perm = take(rows * d.d_model * esize);
+  const size_t dec_rows = d.dtype == DSMOE_BF16 ? (size_t)std::min<int64_t>(d.max_tokens, kDecodeMaxTokens) * E : 0;
+  w.dec_info = take(32);
+  w.dec_p1 = take(dec_rows * 2 * d.d_ff * 4);
+  w.dec_p2 = take(dec_rows * d.d_model * 4);
   w.total = o;
   return w;
 }
@@ -297,6 +302,11 @@ int32_t dsmoe_sparse_fwd(dsmoe_ctx* c, const void* x, const void* w_r, const voi
   int32_t* nnz = reinterpret_cast<int32_t*>(w + c->ws.nnz);
   void* y_perm = w + c->ws.y_perm;
   HIP_TRY(c, launch_route(c, x, w_r, b_r, T, probs, mode, k, eps, mask, cnt_tok, s));
+  if (c->desc.dtype == DSMOE_BF16 && T <= kDecodeMaxTokens) {
+    // decode-sized batch: weight-streaming kernels that derive the dispatch from the masks themselves
+    HIP_TRY(c, launch_decode_fwd(c, x, w_gate, w_up, w_down, T, out, s));
+    return DSMOE_OK;
+  }
   HIP_TRY(c, launch_dispatch(c, x, probs, mask, T, expert_off, row_token, row_weight, tok_off, tok_rows, nnz,
                              nullptr, s));
   if (c->desc.max_rows > 0)

@@ -18,6 +18,7 @@ typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 
 constexpr int kMaxExperts = 64;
 constexpr int kDispatchTokensPerBlock = 256;  // tokens handled by one block of the dispatch kernels
+constexpr int kDecodeMaxTokens = 128;         // largest batch served by the weight-streaming (decode) path
 
 // Workspace carve-up (byte offsets into the caller's buffer).
 struct WorkspaceLayout {
@@ -36,6 +37,10 @@ struct WorkspaceLayout {
   size_t tok_rows;    // i32 [max_rows]
   size_t nnz;         // i32 [1]
   size_t y_perm;      // dtype [max_rows][d]
+  // weight-streaming (decode) path, bf16 only
+  size_t dec_info;    // i32 [8]: rows, active experts, K split of gate/up, K split of down
+  size_t dec_p1;      // f32 [decode_row_cap][2 f]      K-chunk partial sums of gate | up
+  size_t dec_p2;      // f32 [decode_row_cap][d]        K-chunk partial sums of the down projection
   size_t total;
 };
 
@@ -59,6 +64,11 @@ struct dsmoe_ctx {
 
 namespace dsmoe {
 
+// rows of K-chunk partial sums the decode path may keep (K split times dispatched rows)
+inline int decode_row_cap(const dsmoe_ctx* c) {
+  return (c->desc.max_tokens < kDecodeMaxTokens ? c->desc.max_tokens : kDecodeMaxTokens) * c->desc.n_experts;
+}
+
 // ---- kernel launchers (each validates nothing: the C-ABI layer has done so) -------------------
 // router.hip
 hipError_t launch_route(const dsmoe_ctx* c, const void* x, const void* w_r, const void* b_r, int T,
@@ -79,6 +89,10 @@ hipError_t launch_down_dense(const dsmoe_ctx* c, const void* h, int T, int k_tot
 // dispatch.hip (combine)
 hipError_t launch_combine(const dsmoe_ctx* c, const void* y_perm, const float* row_weight,
                           const int32_t* tok_off, const int32_t* tok_rows, int T, void* out, hipStream_t s);
+// decode.hip: expert FFN + combine of dsmoe_sparse_fwd for at most kDecodeMaxTokens bf16 tokens, from the
+// probabilities and masks the router left in the workspace; also publishes the routing objects there
+hipError_t launch_decode_fwd(const dsmoe_ctx* c, const void* x, const void* w_gate, const void* w_up,
+                             const void* w_down, int T, void* out, hipStream_t s);
 // dense.hip
 size_t dense_saved_bytes(const dsmoe_ctx* c, int T);
 size_t dense_bwd_scratch_bytes(const dsmoe_ctx* c, int T);

@@ -1,0 +1,327 @@
+// Sparse-inference forward for decode-sized batches (at most 128 tokens): the expert FFN of Eq. 1 is then
+// bound by reading the selected experts' weights once from HBM, not by arithmetic (paper Sec. 4.4 calls
+// the decoding phase I/O-bound), so the kernels here are laid out to keep every CU streaming weights:
+//
+//   * no dispatch kernels: every block derives the routing (tokens per expert, row offsets) from the
+//     selection bitmasks of the <= 128 tokens itself; block 0 also publishes the usual routing objects;
+//   * a work item is (active expert, column slice, K chunk).  The K split is chosen on the device from the
+//     number of active experts so that there are at least as many items as blocks even when one token
+//     activates four experts; K chunks leave fp32 partial sums that the consumer adds in a fixed order
+//     (no atomics: results are bitwise reproducible);
+//   * gate/up partials -> H = silu(G) * U (small elementwise kernel) -> down partials -> weighted combine.
+#include <algorithm>
+
+#include "gemm_bf16.h"
+
+namespace dsmoe {
+
+namespace {
+
+constexpr int kDecT = kDecodeMaxTokens;
+
+struct DecodePlan {
+  int cnt[kMaxExperts];        // tokens per expert
+  int cnt_w0[kMaxExperts];     // ... of which among tokens 0..63
+  int off[kMaxExperts + 1];    // exclusive prefix sum of cnt (all zero after a capacity overflow)
+  int act[kMaxExperts];        // active experts, ascending
+  int U, nnz, ks1, ks2;        // active experts, rows, K split of the gate/up and of the down products
+};
+
+// K split: the smallest power of two that gives at least `blocks` items, limited by the partial-sum
+// buffer (ks * nnz <= row_cap rows) and by the K steps available (ks must divide ksteps).
+__device__ __forceinline__ int choose_ksplit(int U, int slices, int blocks, int nnz, int row_cap, int ksteps) {
+  int ks = 1;
+  while (U * slices * ks < blocks && 2 * ks * nnz <= row_cap && ksteps % (2 * ks) == 0 && ksteps / (2 * ks) >= 2)
+    ks *= 2;
+  return ks;
+}
+
+// Called by every thread of the block.  m: selection mask of token threadIdx.x (0 beyond T or for
+// threads >= 128).
+__device__ __forceinline__ void build_plan(DecodePlan& p, unsigned long long m, int E, int blocks, long long max_rows,
+                                           int row_cap, int ns1, int ns2, int d, int f) {
+  __shared__ int sW[2][kMaxExperts];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  if (wave < 2) {
+    int mine = 0;
+    for (int e = 0; e < E; ++e) {
+      const int c = __popcll(__ballot((m >> e) & 1ull));
+      if (lane == e) mine = c;
+    }
+    sW[wave][lane] = mine;
+  }
+  __syncthreads();
+  if (wave == 0) {
+    const int c = lane < E ? sW[0][lane] + sW[1][lane] : 0;
+    int incl = c;
+#pragma unroll
+    for (int s = 1; s < 64; s <<= 1) {
+      const int o = __shfl_up(incl, s, 64);
+      if (lane >= s) incl += o;
+    }
+    const int nnz = __shfl(incl, 63, 64);
+    const bool overflow = (long long)nnz > max_rows;
+    const unsigned long long actm = overflow ? 0ull : __ballot(c > 0);
+    p.cnt[lane] = overflow ? 0 : c;
+    p.cnt_w0[lane] = lane < E ? sW[0][lane] : 0;
+    p.off[lane] = overflow ? 0 : incl - c;
+    if (c > 0 && !overflow) p.act[__popcll(actm & ((1ull << lane) - 1ull))] = lane;
+    if (lane == 0) {
+      const int U = __popcll(actm), n = overflow ? 0 : nnz;
+      p.off[64] = n;
+      p.U = U;
+      p.nnz = overflow ? -1 : nnz;
+      p.ks1 = choose_ksplit(U, ns1, blocks, n, row_cap, d / kBK2);
+      p.ks2 = choose_ksplit(U, ns2, blocks, n, row_cap, f / kBK2);
+    }
+  }
+  __syncthreads();
+}
+
+// ---- gate / up: partial G, U over one K chunk ----------------------------------------------------------
+__global__ void __launch_bounds__(kThreads2)
+decode_gateup_kernel(const bf16_t* __restrict__ x, const unsigned long long* __restrict__ mask,
+                     const float* __restrict__ probs, const bf16_t* __restrict__ w_gate,
+                     const bf16_t* __restrict__ w_up, float* __restrict__ P1, int T, int d, int f, int E,
+                     long long max_rows, int row_cap, int32_t* __restrict__ info, int32_t* __restrict__ expert_off,
+                     int32_t* __restrict__ row_token, float* __restrict__ row_weight, int32_t* __restrict__ tok_off,
+                     int32_t* __restrict__ tok_rows, int32_t* __restrict__ nnz_out, int32_t* __restrict__ err_flag) {
+  constexpr int BNS = 128;                       // columns of gate and of up per item
+  typedef Tile2<kDecT, 2 * BNS, 2, 4, 2> TL;
+  extern __shared__ __align__(16) char smem[];
+  __shared__ DecodePlan plan;
+  __shared__ int toks[kDecT];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int ns1 = (f + BNS - 1) / BNS, ns2 = (d + 255) / 256;
+  const unsigned long long m = (int)threadIdx.x < T ? mask[threadIdx.x] : 0ull;
+  build_plan(plan, m, E, gridDim.x, max_rows, row_cap, ns1, ns2, d, f);
+  const bool overflow = plan.nnz < 0;
+
+  if (blockIdx.x == 0) {   // publish the routing objects of this call
+    if ((int)threadIdx.x <= E) expert_off[threadIdx.x] = threadIdx.x == E ? plan.off[64] : plan.off[threadIdx.x];
+    if (threadIdx.x == 0) {
+      nnz_out[0] = overflow ? 0 : plan.nnz;
+      info[0] = overflow ? 0 : plan.nnz; info[1] = plan.U; info[2] = plan.ks1; info[3] = plan.ks2;
+      if (overflow) err_flag[0] = DSMOE_ERR_CAPACITY;
+    }
+    __shared__ int sTok0;
+    const int cnt = __popcll(m);
+    int incl = cnt;
+#pragma unroll
+    for (int s = 1; s < 64; s <<= 1) {
+      const int o = __shfl_up(incl, s, 64);
+      if (lane >= s) incl += o;
+    }
+    if (threadIdx.x == 63) sTok0 = incl;
+    __syncthreads();
+    if (wave < 2) {
+      const int t = threadIdx.x;
+      const int tbase = overflow ? 0 : incl - cnt + (wave == 1 ? sTok0 : 0);
+      if (t < T) tok_off[t] = tbase;
+      if (t == T - 1) tok_off[T] = overflow ? 0 : plan.nnz;
+      const unsigned long long lt = (1ull << lane) - 1ull;
+      for (int e = 0; e < E; ++e) {
+        const unsigned long long bits = __ballot((m >> e) & 1ull);
+        if (((m >> e) & 1ull) && !overflow) {
+          const int row = plan.off[e] + __popcll(bits & lt) + (wave == 1 ? plan.cnt_w0[e] : 0);
+          row_token[row] = t;
+          row_weight[row] = probs[(size_t)t * E + e];
+          tok_rows[tbase + __popcll(m & ((1ull << e) - 1ull))] = row;
+        }
+      }
+    }
+  }
+
+  const int items = plan.U * ns1 * plan.ks1;
+  const int kc = d / plan.ks1;                   // K elements per chunk
+  for (int item = blockIdx.x; item < items; item += gridDim.x) {
+    const int c = item % plan.ks1, j = (item / plan.ks1) % ns1, e = plan.act[item / (plan.ks1 * ns1)];
+    const int Me = plan.cnt[e], n0 = j * BNS;
+    __syncthreads();                             // the previous item no longer reads toks
+    if (wave < 2) {
+      const unsigned long long bits = __ballot((m >> e) & 1ull);
+      if ((m >> e) & 1ull)
+        toks[__popcll(bits & ((1ull << lane) - 1ull)) + (wave == 1 ? plan.cnt_w0[e] : 0)] = threadIdx.x;
+    }
+    __syncthreads();
+    LRows2<kDecT> L;
+    L.seg_stride = 0;
+    {
+      const int r = min((int)(threadIdx.x >> 2), Me - 1);
+      L.p[0] = reinterpret_cast<const char*>(x + (size_t)toks[r] * d + (size_t)c * kc) + (threadIdx.x & 3) * 16;
+    }
+    RCols2<2 * BNS, 2> R;
+    const size_t wo = (size_t)e * d * f + (size_t)c * kc * f + n0;
+    const bf16_t* const base[2] = {w_gate + wo, w_up + wo};
+    R.init(base, f, min(BNS, f - n0), kc);
+    typename TL::Acc acc;
+    TL::zero(acc);
+    TL::mainloop(acc, L, R, kc / kBK2, 1 << 30, smem);
+#pragma unroll
+    for (int mt = 0; mt < TL::MT; ++mt) {
+      const int mrow = TL::acc_m(mt);
+      if (mrow >= Me) continue;
+      float* prow = P1 + ((size_t)c * plan.nnz + plan.off[e] + mrow) * (2 * (size_t)f);
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const int n = n0 + TL::acc_n(0, g);
+        if (n >= f) continue;
+        const f32x16& G = acc[0][mt];
+        const f32x16& Uv = acc[1][mt];
+        store4(prow + n, G[4 * g], G[4 * g + 1], G[4 * g + 2], G[4 * g + 3]);
+        store4(prow + f + n, Uv[4 * g], Uv[4 * g + 1], Uv[4 * g + 2], Uv[4 * g + 3]);
+      }
+    }
+  }
+}
+
+// ---- H = silu(sum of gate partials) * (sum of up partials), bf16 ------------------------------------------
+__global__ void __launch_bounds__(kThreads)
+decode_act_kernel(const float* __restrict__ P1, const int32_t* __restrict__ info, bf16_t* __restrict__ H, int f) {
+  const int nnz = info[0], ks1 = info[2];
+  const int qpr = f / 4;                          // column quads per row
+  const long total = (long)nnz * qpr;
+  for (long q = (long)blockIdx.x * kThreads + threadIdx.x; q < total; q += (long)gridDim.x * kThreads) {
+    const int row = (int)(q / qpr), col = (int)(q % qpr) * 4;
+    f32x4 g = {0.f, 0.f, 0.f, 0.f}, u = g;
+    for (int c = 0; c < ks1; ++c) {
+      const float* p = P1 + ((size_t)c * nnz + row) * (2 * (size_t)f) + col;
+      g += __builtin_bit_cast(f32x4, ldg16(p));
+      u += __builtin_bit_cast(f32x4, ldg16(p + f));
+    }
+    store4(H + (size_t)row * f + col, silu_f(g.x) * u.x, silu_f(g.y) * u.y, silu_f(g.z) * u.z, silu_f(g.w) * u.w);
+  }
+}
+
+// ---- down: partial Y over one chunk of the hidden width -------------------------------------------------
+__global__ void __launch_bounds__(kThreads2)
+decode_down_kernel(const bf16_t* __restrict__ H, const int32_t* __restrict__ info,
+                   const int32_t* __restrict__ expert_off, const bf16_t* __restrict__ w_down,
+                   float* __restrict__ P2, int d, int f, int E) {
+  constexpr int BN = 256;
+  typedef Tile2<kDecT, BN, 2, 4> TL;
+  extern __shared__ __align__(16) char smem[];
+  __shared__ int sOff[kMaxExperts + 1], sAct[kMaxExperts];
+  __shared__ int sU;
+  if (threadIdx.x < 64) {
+    const int e = threadIdx.x;
+    const int lo = e < E ? expert_off[e] : 0, hi = e < E ? expert_off[e + 1] : 0;
+    const unsigned long long actm = __ballot(hi > lo);
+    sOff[e] = lo;
+    if (e == E - 1) sOff[E] = hi;
+    if (hi > lo) sAct[__popcll(actm & ((1ull << e) - 1ull))] = e;
+    if (e == 0) sU = __popcll(actm);
+  }
+  __syncthreads();
+  const int nnz = info[0], ks2 = info[3];
+  const int ns2 = (d + BN - 1) / BN;
+  const int items = sU * ns2 * ks2;
+  const int kc = f / ks2;
+  for (int item = blockIdx.x; item < items; item += gridDim.x) {
+    const int c = item % ks2, j = (item / ks2) % ns2, e = sAct[item / (ks2 * ns2)];
+    const int row0 = sOff[e], Me = sOff[e + 1] - row0, n0 = j * BN;
+    LRows2<kDecT> L;
+    L.seg_stride = 0;
+    {
+      const int r = min((int)(threadIdx.x >> 2), Me - 1);
+      L.p[0] = reinterpret_cast<const char*>(H + (size_t)(row0 + r) * f + (size_t)c * kc) + (threadIdx.x & 3) * 16;
+    }
+    RCols2<BN, 1> R;
+    const bf16_t* const base[1] = {w_down + (size_t)e * f * d + (size_t)c * kc * d + n0};
+    R.init(base, d, min(BN, d - n0), kc);
+    typename TL::Acc acc;
+    TL::zero(acc);
+    TL::mainloop(acc, L, R, kc / kBK2, 1 << 30, smem);
+#pragma unroll
+    for (int mt = 0; mt < TL::MT; ++mt) {
+      const int mrow = TL::acc_m(mt);
+      if (mrow >= Me) continue;
+      float* prow = P2 + ((size_t)c * nnz + row0 + mrow) * (size_t)d;
+#pragma unroll
+      for (int nt = 0; nt < TL::NT; ++nt)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const int n = n0 + TL::acc_n(nt, g);
+          if (n >= d) continue;
+          const f32x16& A = acc[nt][mt];
+          store4(prow + n, A[4 * g], A[4 * g + 1], A[4 * g + 2], A[4 * g + 3]);
+        }
+    }
+  }
+}
+
+// ---- combine: out[t,:] = sum over the token's rows (ascending expert) of weight * (sum of down partials) ----
+__global__ void __launch_bounds__(kThreads)
+decode_combine_kernel(const float* __restrict__ P2, const int32_t* __restrict__ info,
+                      const float* __restrict__ row_weight, const int32_t* __restrict__ tok_off,
+                      const int32_t* __restrict__ tok_rows, int d, bf16_t* __restrict__ out) {
+  const int t = blockIdx.x;
+  const int nnz = info[0], ks2 = info[3];
+  const int lo = tok_off[t], hi = tok_off[t + 1];
+  for (int c0 = threadIdx.x * 4; c0 < d; c0 += kThreads * 4) {
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+    for (int j = lo; j < hi; ++j) {
+      const int row = tok_rows[j];
+      const float w = row_weight[row];
+      f32x4 y = {0.f, 0.f, 0.f, 0.f};
+      for (int c = 0; c < ks2; ++c)
+        y += __builtin_bit_cast(f32x4, ldg16(P2 + ((size_t)c * nnz + row) * (size_t)d + c0));
+      acc.x = fmaf(w, y.x, acc.x);
+      acc.y = fmaf(w, y.y, acc.y);
+      acc.z = fmaf(w, y.z, acc.z);
+      acc.w = fmaf(w, y.w, acc.w);
+    }
+    store4(out + (size_t)t * d + c0, acc.x, acc.y, acc.z, acc.w);
+  }
+}
+
+}  // namespace
+
+hipError_t launch_decode_fwd(const dsmoe_ctx* c, const void* x, const void* w_gate, const void* w_up,
+                             const void* w_down, int T, void* out, hipStream_t s) {
+  typedef Tile2<kDecT, 256, 2, 4, 2> TL1;
+  typedef Tile2<kDecT, 256, 2, 4> TL2;
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e1 = hipFuncSetAttribute(reinterpret_cast<const void*>(&decode_gateup_kernel),
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, TL1::LDS_BYTES);
+    hipError_t e2 = hipFuncSetAttribute(reinterpret_cast<const void*>(&decode_down_kernel),
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, TL2::LDS_BYTES);
+    if (e1 != hipSuccess) return e1;
+    if (e2 != hipSuccess) return e2;
+    attr_set = true;
+  }
+  const int d = c->desc.d_model, f = c->desc.d_ff, E = c->desc.n_experts;
+  char* w = c->workspace;
+  const float* probs = reinterpret_cast<const float*>(w + c->ws.probs);
+  const unsigned long long* mask = reinterpret_cast<const unsigned long long*>(w + c->ws.mask);
+  int32_t* info = reinterpret_cast<int32_t*>(w + c->ws.dec_info);
+  float* P1 = reinterpret_cast<float*>(w + c->ws.dec_p1);
+  float* P2 = reinterpret_cast<float*>(w + c->ws.dec_p2);
+  bf16_t* H = reinterpret_cast<bf16_t*>(w + c->ws.h);
+  int32_t* expert_off = reinterpret_cast<int32_t*>(w + c->ws.expert_off);
+  int32_t* row_token = reinterpret_cast<int32_t*>(w + c->ws.row_token);
+  float* row_weight = reinterpret_cast<float*>(w + c->ws.row_weight);
+  int32_t* tok_off = reinterpret_cast<int32_t*>(w + c->ws.tok_off);
+  int32_t* tok_rows = reinterpret_cast<int32_t*>(w + c->ws.tok_rows);
+  int32_t* nnz = reinterpret_cast<int32_t*>(w + c->ws.nnz);
+  int32_t* err_flag = reinterpret_cast<int32_t*>(w + c->ws.err_flag);
+  const int grid = (c->n_cu + 7) / 8 * 8;
+  const int row_cap = decode_row_cap(c);
+
+  decode_gateup_kernel<<<dim3(grid), dim3(kThreads2), TL1::LDS_BYTES, s>>>(
+      (const bf16_t*)x, mask, probs, (const bf16_t*)w_gate, (const bf16_t*)w_up, P1, T, d, f, E,
+      (long long)c->desc.max_rows, row_cap, info, expert_off, row_token, row_weight, tok_off, tok_rows, nnz, err_flag);
+  if (hipError_t e = hipGetLastError()) return e;
+  const long quads = (long)std::min<long long>(c->desc.max_rows, (long long)T * E) * (f / 4);
+  const int g_act = (int)std::max<long>(1, std::min<long>((quads + kThreads - 1) / kThreads, (long)c->n_cu * 8));
+  decode_act_kernel<<<dim3(g_act), dim3(kThreads), 0, s>>>(P1, info, H, f);
+  if (hipError_t e = hipGetLastError()) return e;
+  decode_down_kernel<<<dim3(grid), dim3(kThreads2), TL2::LDS_BYTES, s>>>(H, info, expert_off, (const bf16_t*)w_down,
+                                                                         P2, d, f, E);
+  if (hipError_t e = hipGetLastError()) return e;
+  decode_combine_kernel<<<dim3(T), dim3(kThreads), 0, s>>>(P2, info, row_weight, tok_off, tok_rows, d, (bf16_t*)out);
+  return hipGetLastError();
+}
+
+}  // namespace dsmoe

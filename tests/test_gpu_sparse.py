@@ -130,7 +130,13 @@ def run_staged_and_check(torch, dsmoe, inp, mode, k, eps, max_rows=None, materia
     np.testing.assert_array_equal(mask_to_bool(m2, E), M_ref)
     np.testing.assert_array_equal(eo2.cpu().numpy(), r_ref.expert_off)
     np.testing.assert_array_equal(rt2.cpu().numpy()[:nnz], r_ref.row_token)
-    assert torch.equal(out2, out)
+    if cfg.dtype == "bf16" and 0 < T <= 128:
+        # decode-sized batches take the weight-streaming kernels (fp32 partial sums, one final rounding)
+        err2 = helpers.rel_err(out2.float().cpu().numpy(), O_ref)
+        say(f"  weight-streaming path rel err {err2:.3e}")
+        assert err2 <= tol
+    else:
+        assert torch.equal(out2, out)
     return o_gpu
 
 
@@ -216,6 +222,37 @@ def test_c3_decode_sizes(torch, dsmoe, T, mode, k, eps):
     if T:
         helpers.condition_margins(inp, mode, k, eps)
     run_staged_and_check(torch, dsmoe, inp, mode, k, eps, max_rows=T * 32)
+
+
+@pytest.mark.parametrize("T,d,E,f,mode,k,eps,zipf", [
+    (128, 320, 16, 192, "threshold", 0, 0.0, 0.0),     # every expert on every token; ragged column slices
+    (128, 256, 64, 64, "topk", 2, 0.0, 3.0),           # 64 experts, a few of them take nearly all tokens
+    (100, 512, 8, 256, "topk", 1, 0.0, 0.0),
+    (3, 2048, 32, 512, "topk", 1, 0.0, 0.0),           # at most three active experts: deepest K split
+    (65, 192, 8, 64, "threshold", 0, 0.1, 0.0),
+])
+def test_weight_streaming_path_shapes(torch, dsmoe, T, d, E, f, mode, k, eps, zipf):
+    cfg = gen.LayerConfig("decode", 16, T=T, d=d, E=E, f=f, dtype="bf16", mode=mode, k=k, eps=eps,
+                          router_std=1.0 / np.sqrt(d), zipf_s=zipf)
+    run_staged_and_check(torch, dsmoe, conditioned(cfg, mode, k, eps), mode, k, eps)
+
+
+def test_weight_streaming_path_overflow_and_repeatability(torch, dsmoe):
+    cfg = gen.CONFIGS["c3"].with_(T=64)
+    inp = conditioned(cfg, "topk", 4, 0.0)
+    w = weights_to_dev(torch, inp)
+    args = (w["x"], w["w_r"], None, w["w_gate"], w["w_up"], w["w_down"], dsmoe.SEL_TOPK, 4, 0.0)
+    small = dsmoe.Layer(cfg.d, cfg.f, cfg.E, cfg.dtype, max_tokens=64, max_rows=200)    # needs 256 rows
+    out = small.sparse_fwd(*args)
+    assert small.poll_error() == dsmoe.ERR_CAPACITY
+    _, _, eo, _ = small.sparse_fwd_routing(64)
+    assert int(eo.abs().sum().item()) == 0 and float(out.float().abs().max().item()) == 0.0
+    layer = dsmoe.Layer(cfg.d, cfg.f, cfg.E, cfg.dtype, max_tokens=64)
+    outs = [layer.sparse_fwd(*args).clone() for _ in range(3)]
+    assert layer.poll_error() == dsmoe.OK
+    assert torch.equal(outs[0], outs[1]) and torch.equal(outs[0], outs[2])
+    O, _, _ = orc.sparse_forward(inp.x, inp.w_r, None, inp.w_gate, inp.w_up, inp.w_down, "topk", 4)
+    assert helpers.rel_err(outs[0].float().cpu().numpy(), O) <= TOL["bf16"]
 
 
 def test_capacity_overflow_is_reported_and_harmless(torch, dsmoe):
