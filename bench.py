@@ -1,14 +1,16 @@
 #!/usr/bin/env python3
 """Benchmark of the DS-MoE expert layer on one MI355X.
 
-A "step" is one pass of the whole sparse-inference hot path (dsmoe_sparse_fwd: router + softmax +
-selection, dispatch, grouped SwiGLU FFN, weighted combine) over one batch of synthetic tokens that is
-already resident in HBM.  The default workload is the sparse-prefill configuration ("c2": T=4096,
-d_model=2048, 32 experts, d_ff=512, threshold 0.02, bf16 storage with fp32 accumulation).
+Headline (`value`): a "step" is one pass of the whole sparse-inference hot path (dsmoe_sparse_fwd: router +
+softmax + selection, dispatch, grouped SwiGLU FFN, weighted combine) over one batch of synthetic tokens
+already resident in HBM, on the sparse-prefill configuration "c2" (T=4096, d_model=2048, 32 experts,
+d_ff=512, threshold 0.02, bf16 storage with fp32 accumulation).
 
-Prints ONE JSON line.  `roofline` describes the dominant kernel (the grouped gate/up GEMM): algorithmic
-FLOPs per launch (4 * nnz * d * f) over its average duration, measured with HIP events on the launch
-stream during the timed steps.  `cpu_baseline` is the fp64 CPU checker timed on this host.
+Prints ONE JSON line.  `roofline` describes the dominant kernel of the headline workload (the grouped
+gate/up GEMM): algorithmic FLOPs per launch (4 * nnz * d * f) over its average duration, measured with HIP
+events on the launch stream during the timed steps.  `cpu_baseline` is the fp64 CPU checker timed on this
+host.  `workloads` carries the other configurations (decode sizes "c3", dense training "c4", skewed prefill
+"c5") with their own throughput and roofline fractions; they are context, not the headline.
 """
 from __future__ import annotations
 
@@ -43,7 +45,6 @@ def read_traffic(workload: str):
 
 
 def cpu_baseline(inp, cfg, passes: int):
-    import numpy as np
     from oracle import dsmoe_oracle as orc
     try:
         from threadpoolctl import threadpool_info
@@ -59,91 +60,222 @@ def cpu_baseline(inp, cfg, passes: int):
                       f"{dt:.1f} s wall"}
 
 
+class Bench:
+    def __init__(self):
+        import numpy as np
+        import torch
+        import dsmoe_inputs as gen
+        import paper_2404_05567_amd as dsmoe
+        self.np, self.torch, self.gen, self.dsmoe = np, torch, gen, dsmoe
+        self.dev = torch.device("cuda:0")
+
+    def to_dev(self, a, dtype):
+        if a is None:
+            return None
+        t = self.torch.from_numpy(self.np.ascontiguousarray(a)).to(self.dev)
+        return t.to(self.torch.bfloat16) if dtype == "bf16" else t
+
+    def timed(self, fn, steps, warmup):
+        """Wall-clock milliseconds per call of fn, stream-synchronised on both sides."""
+        torch = self.torch
+        for _ in range(warmup):
+            fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / steps * 1e3
+
+    # ---- sparse prefill (c2, c5) ---------------------------------------------------------------------
+    def sparse_prefill(self, name, steps, warmup, keep_inputs=False):
+        torch, gen, dsmoe = self.torch, self.gen, self.dsmoe
+        cfg = gen.CONFIGS[name]
+        inp = gen.make_layer(cfg, 0)
+        x, w_r, b_r = (self.to_dev(a, cfg.dtype) for a in (inp.x, inp.w_r, inp.b_r))
+        w_gate, w_up, w_down = (self.to_dev(a, cfg.dtype) for a in (inp.w_gate, inp.w_up, inp.w_down))
+        max_rows = cfg.T * (16 if name == "c2" else 24)
+        layer = dsmoe.Layer(cfg.d, cfg.f, cfg.E, cfg.dtype, max_tokens=cfg.T, max_rows=max_rows)
+        mode = dsmoe.SEL_TOPK if cfg.mode == "topk" else dsmoe.SEL_THRESHOLD
+        out = torch.empty((cfg.T, cfg.d), dtype=x.dtype, device=self.dev)
+
+        def step():
+            layer.sparse_fwd(x, w_r, b_r, w_gate, w_up, w_down, mode, cfg.k, cfg.eps, out=out)
+
+        for _ in range(warmup):
+            step()
+        torch.cuda.synchronize()
+        assert layer.poll_error() == dsmoe.OK, "capacity overflow"
+        _, _, expert_off, _ = layer.sparse_fwd_routing(cfg.T)
+        eo = expert_off.cpu().numpy()
+        nnz = int(eo[-1])
+        layer.profile_enable(steps)
+        ms = self.timed(step, steps, 0)
+        n_calls, gateup_ms, down_ms = layer.profile_read()
+        layer.profile_enable(0)
+        assert n_calls == steps
+        assert torch.isfinite(out.float()).all()
+        gateup_tf = 4.0 * nnz * cfg.d * cfg.f / (gateup_ms / n_calls * 1e-3) / 1e12
+        down_tf = 2.0 * nnz * cfg.d * cfg.f / (down_ms / n_calls * 1e-3) / 1e12
+        layer_flops = 6.0 * nnz * cfg.d * cfg.f + 2.0 * cfg.T * cfg.d * cfg.E
+        res = {
+            "workload": f"{name}: sparse prefill T={cfg.T} d_model={cfg.d} E={cfg.E} d_ff={cfg.f} "
+                        f"{cfg.mode} eps={cfg.eps} k={cfg.k}",
+            "tokens_per_s": cfg.T / (ms * 1e-3), "ms_per_step": ms, "nnz": nnz,
+            "active_fraction": nnz / (cfg.T * cfg.E),
+            "rows_per_expert_min_max": [int((eo[1:] - eo[:-1]).min()), int((eo[1:] - eo[:-1]).max())],
+            "layer_tflops_per_s": layer_flops / (ms * 1e-3) / 1e12,
+            "layer_frac_of_bf16_peak": layer_flops / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+            "gateup_kernel_ms": gateup_ms / n_calls, "gateup_tflops_per_s": gateup_tf,
+            "gateup_frac_of_bf16_peak": gateup_tf / PEAK_BF16_TFLOPS,
+            "down_kernel_ms": down_ms / n_calls, "down_tflops_per_s": down_tf,
+            "down_frac_of_bf16_peak": down_tf / PEAK_BF16_TFLOPS,
+        }
+        return (res, inp, cfg) if keep_inputs else res
+
+    # ---- dense training forward + backward (c4) -----------------------------------------------------
+    def dense_training(self, steps, warmup):
+        torch, gen, dsmoe = self.torch, self.gen, self.dsmoe
+        cfg = gen.CONFIGS["c4"]
+        inp = gen.make_layer(cfg, 0, with_grad=True)
+        w = {k: self.to_dev(getattr(inp, k), cfg.dtype) for k in ("x", "w_r", "w_gate", "w_up", "w_down", "d_out")}
+        layer = dsmoe.Layer(cfg.d, cfg.f, cfg.E, cfg.dtype, max_tokens=cfg.T, max_rows=cfg.T)
+        bufs = layer.dense_buffers(cfg.T)
+
+        def fwd():
+            layer.dense_fwd(w["x"], w["w_r"], None, w["w_gate"], w["w_up"], w["w_down"], buffers=bufs)
+
+        def bwd():
+            layer.dense_bwd(w["x"], w["w_r"], w["w_gate"], w["w_up"], w["w_down"], bufs["saved"], w["d_out"],
+                            buffers=bufs)
+
+        def both():
+            fwd()
+            bwd()
+
+        ms = self.timed(both, steps, warmup)
+        ms_f = self.timed(fwd, steps, 1)
+        ms_b = self.timed(bwd, steps, 1)
+        assert torch.isfinite(bufs["dx"].float()).all()
+        unit = 2.0 * cfg.T * cfg.d * cfg.E * cfg.f          # one T x d x (E f) product
+        flops_f, flops_b = 3 * unit, 6 * unit
+        return {
+            "workload": f"c4: dense training forward+backward T={cfg.T} d_model={cfg.d} E={cfg.E} d_ff={cfg.f}",
+            "tokens_per_s": cfg.T / (ms * 1e-3), "ms_per_step": ms, "fwd_ms": ms_f, "bwd_ms": ms_b,
+            "tflops_per_s": (flops_f + flops_b) / (ms * 1e-3) / 1e12,
+            "frac_of_bf16_peak": (flops_f + flops_b) / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+            "fwd_frac_of_bf16_peak": flops_f / (ms_f * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+            "bwd_frac_of_bf16_peak": flops_b / (ms_b * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+        }
+
+    # ---- decode sizes (c3) --------------------------------------------------------------------------
+    def decode(self, steps, warmup, n_sets=16):
+        """T in {1, 8, 32, 128} x {top-4, threshold 0.02} on the c2 layer shape.  The loop cycles through
+        `n_sets` independent weight sets (3.2 GB in all), as a model's layers would, so no call finds its
+        weights in the 256 MB last-level cache.  Timed both as plain launches and as a replayed HIP graph of
+        the n_sets calls (a serving loop would use the latter; it removes the host's launch cost)."""
+        torch, gen, dsmoe = self.torch, self.gen, self.dsmoe
+        cfg = gen.CONFIGS["c3"]
+        d, f, E = cfg.d, cfg.f, cfg.E
+        g = torch.Generator(device=self.dev)
+        g.manual_seed(gen.BASE_SEED + 3000)
+        bf = torch.bfloat16
+
+        def rnd(shape, std):
+            return (torch.randn(shape, generator=g, device=self.dev, dtype=torch.float32) * std).to(bf)
+
+        sets = [dict(w_r=rnd((d, E), cfg.router_std), w_gate=rnd((E, d, f), 0.02), w_up=rnd((E, d, f), 0.02),
+                     w_down=rnd((E, f, d), 0.02)) for _ in range(n_sets)]
+        layer = dsmoe.Layer(d, f, E, "bf16", max_tokens=128)
+        results = []
+        for T in (1, 8, 32, 128):
+            x = rnd((T, d), 1.0)
+            out = torch.empty((T, d), dtype=bf, device=self.dev)
+            for mode_name, mode, k, eps in (("top4", dsmoe.SEL_TOPK, 4, 0.0), ("eps0.02", dsmoe.SEL_THRESHOLD, 0, 0.02)):
+                def sweep():
+                    for s in sets:
+                        layer.sparse_fwd(x, s["w_r"], None, s["w_gate"], s["w_up"], s["w_down"], mode, k, eps, out=out)
+
+                # bytes actually needed: the union of active experts per weight set
+                union = []
+                for s in sets:
+                    layer.sparse_fwd(x, s["w_r"], None, s["w_gate"], s["w_up"], s["w_down"], mode, k, eps, out=out)
+                    _, _, eo, _ = layer.sparse_fwd_routing(T)
+                    eo = eo.cpu().numpy()
+                    union.append(int(((eo[1:] - eo[:-1]) > 0).sum()))
+                assert layer.poll_error() == dsmoe.OK
+                mean_union = sum(union) / len(union)
+                bytes_per_call = mean_union * 3 * d * f * 2 + d * E * 2 + 2 * T * d * 2
+                ms_eager = self.timed(sweep, steps, warmup) / n_sets
+                graph = torch.cuda.CUDAGraph()
+                side = torch.cuda.Stream()
+                side.wait_stream(torch.cuda.current_stream())
+                with torch.cuda.stream(side):
+                    sweep()
+                    with torch.cuda.graph(graph, stream=side):
+                        sweep()
+                torch.cuda.current_stream().wait_stream(side)
+                ms_graph = self.timed(graph.replay, steps, warmup) / n_sets
+                best = min(ms_eager, ms_graph)
+                results.append({
+                    "T": T, "selection": mode_name, "active_experts_mean": mean_union,
+                    "bytes_per_call": bytes_per_call, "us_per_call_eager": ms_eager * 1e3,
+                    "us_per_call_graph": ms_graph * 1e3, "tokens_per_s": T / (best * 1e-3),
+                    "gb_per_s": bytes_per_call / (best * 1e-3) / 1e9,
+                    "frac_of_hbm_peak": bytes_per_call / (best * 1e-3) / 1e9 / PEAK_HBM_GBS,
+                })
+        return {"workload": f"c3: sparse decode on the c2 layer, {n_sets} weight sets cycled", "cases": results}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--config", default="c2", choices=["c2", "c5"])
+    ap.add_argument("--workloads", default="c2,c3,c4,c5",
+                    help="comma-separated subset of c2,c3,c4,c5 (c2 is the headline and always runs)")
     ap.add_argument("--cpu-passes", type=int, default=20, help="0 skips the CPU baseline")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU (no collectives, no sharding); use --gpus 1")
 
-    import numpy as np
     import torch
-    import dsmoe_inputs as gen
     import paper_2404_05567_amd as dsmoe
 
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible")
     dsmoe.load_library()   # no fallback: raises if the HIP library is missing
+    wl = set(args.workloads.split(","))
+    b = Bench()
 
-    cfg = gen.CONFIGS[args.config]
-    inp = gen.make_layer(cfg, 0)
-    dev = torch.device("cuda:0")
+    head, inp, cfg = b.sparse_prefill("c2", args.steps, args.warmup, keep_inputs=True)
+    side_steps = max(5, min(args.steps, 20))
+    others = {}
+    if "c3" in wl:
+        others["c3"] = b.decode(side_steps, 3)
+    if "c4" in wl:
+        others["c4"] = b.dense_training(side_steps, 3)
+    if "c5" in wl:
+        others["c5"] = b.sparse_prefill("c5", side_steps, 3)
 
-    def to_dev(a):
-        if a is None:
-            return None
-        t = torch.from_numpy(np.ascontiguousarray(a)).to(dev)
-        return t.to(torch.bfloat16) if cfg.dtype == "bf16" else t
-
-    x, w_r, b_r = to_dev(inp.x), to_dev(inp.w_r), to_dev(inp.b_r)
-    w_gate, w_up, w_down = to_dev(inp.w_gate), to_dev(inp.w_up), to_dev(inp.w_down)
-    max_rows = cfg.T * (16 if cfg.name == "c2" else 24)
-    layer = dsmoe.Layer(cfg.d, cfg.f, cfg.E, cfg.dtype, max_tokens=cfg.T, max_rows=max_rows)
-    mode = dsmoe.SEL_TOPK if cfg.mode == "topk" else dsmoe.SEL_THRESHOLD
-    out = torch.empty((cfg.T, cfg.d), dtype=x.dtype, device=dev)
-
-    def step():
-        layer.sparse_fwd(x, w_r, b_r, w_gate, w_up, w_down, mode, cfg.k, cfg.eps, out=out)
-
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-    assert layer.poll_error() == dsmoe.OK, "capacity overflow"
-    _, _, expert_off, _ = layer.sparse_fwd_routing(cfg.T)
-    nnz = int(expert_off[-1].item())
-
-    layer.profile_enable(args.steps)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step()
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
-    n_calls, gateup_ms, down_ms = layer.profile_read()
-    layer.profile_enable(0)
-    assert n_calls == args.steps
-    assert torch.isfinite(out.float()).all()
-
-    ms_per_step = dt / args.steps * 1e3
-    gateup_flops = 4.0 * nnz * cfg.d * cfg.f
-    gateup_avg_s = gateup_ms / n_calls * 1e-3
-    achieved = gateup_flops / gateup_avg_s / 1e12
-    layer_flops = 6.0 * nnz * cfg.d * cfg.f + 2.0 * cfg.T * cfg.d * cfg.E
     result = {
         "metric": METRIC,
-        "value": cfg.T / (dt / args.steps),
+        "value": head["tokens_per_s"],
         "unit": "tokens/s",
         "n_gpus": 1,
         "steps": args.steps,
         "warmup": args.warmup,
-        "ms_per_step": ms_per_step,
+        "ms_per_step": head["ms_per_step"],
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "bf16" if cfg.dtype == "bf16" else "f32",
+        "dtype": "bf16",
         "data": "synthetic",
-        "config": {"workload": f"{cfg.name}: sparse prefill T={cfg.T} d_model={cfg.d} E={cfg.E} d_ff={cfg.f} "
-                               f"{cfg.mode} eps={cfg.eps} k={cfg.k}",
-                   "nnz": nnz, "active_fraction": nnz / (cfg.T * cfg.E),
-                   "layer_tflops_per_s": layer_flops / (dt / args.steps) / 1e12,
-                   "layer_frac_of_bf16_peak": layer_flops / (dt / args.steps) / 1e12 / PEAK_BF16_TFLOPS,
-                   "down_kernel_ms": down_ms / n_calls, "gateup_kernel_ms": gateup_ms / n_calls},
-        "roofline": {"bound": "mfma", "kernel": "gateup_kernel", "achieved": achieved, "peak": PEAK_BF16_TFLOPS,
-                     "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS, "traffic": read_traffic(cfg.name)},
+        "config": {k: v for k, v in head.items() if k not in ("tokens_per_s", "ms_per_step")},
+        "roofline": {"bound": "mfma", "kernel": "gateup_bf16_kernel", "achieved": head["gateup_tflops_per_s"],
+                     "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                     "frac": head["gateup_tflops_per_s"] / PEAK_BF16_TFLOPS, "traffic": read_traffic("c2")},
+        "workloads": others,
     }
     if args.cpu_passes > 0:
         result["cpu_baseline"] = cpu_baseline(inp, cfg, args.cpu_passes)

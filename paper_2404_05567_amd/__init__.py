@@ -204,31 +204,52 @@ class Layer:
     def poll_error(self) -> int:
         return self.lib.dsmoe_poll_error(self.ctx, _stream())
 
-    def dense_fwd(self, x, w_r, b_r, w_gate, w_up, w_down, want_probs=False, save=False):
+    def dense_buffers(self, T: int, with_bias_grad: bool = False):
+        """Every output and scratch buffer of one dense forward + backward, allocated once."""
+        t = self.torch
+        n1, n2 = c_size_t(), c_size_t()
+        self._check(self.lib.dsmoe_dense_saved_bytes(self.ctx, T, byref(n1)))
+        self._check(self.lib.dsmoe_dense_bwd_scratch_bytes(self.ctx, T, byref(n2)))
+        return dict(out=self._empty((T, self.d), self.tdtype), probs=self._empty((T, self.E), t.float32),
+                    saved=self._empty((max(n1.value, 16),), t.uint8),
+                    scratch=self._empty((max(n2.value, 16),), t.uint8),
+                    dx=self._empty((T, self.d), self.tdtype), dw_r=self._empty((self.d, self.E), t.float32),
+                    db_r=self._empty((self.E,), t.float32) if with_bias_grad else None,
+                    dw_gate=self._empty((self.E, self.d, self.f), t.float32),
+                    dw_up=self._empty((self.E, self.d, self.f), t.float32),
+                    dw_down=self._empty((self.E, self.f, self.d), t.float32))
+
+    def dense_fwd(self, x, w_r, b_r, w_gate, w_up, w_down, want_probs=False, save=False, buffers=None):
         T = x.shape[0]
         t = self.torch
-        out = self._empty((T, self.d), self.tdtype)
-        probs = self._empty((T, self.E), t.float32) if want_probs else None
-        saved = None
-        if save:
-            n = c_size_t()
-            self._check(self.lib.dsmoe_dense_saved_bytes(self.ctx, T, byref(n)))
-            saved = self._empty((max(n.value, 16),), t.uint8)
+        if buffers is not None:
+            out, probs, saved = buffers["out"], buffers["probs"], buffers["saved"]
+        else:
+            out = self._empty((T, self.d), self.tdtype)
+            probs = self._empty((T, self.E), t.float32) if want_probs else None
+            saved = None
+            if save:
+                n = c_size_t()
+                self._check(self.lib.dsmoe_dense_saved_bytes(self.ctx, T, byref(n)))
+                saved = self._empty((max(n.value, 16),), t.uint8)
         self._check(self.lib.dsmoe_dense_fwd(self.ctx, _ptr(x), _ptr(w_r), _ptr(b_r), _ptr(w_gate), _ptr(w_up),
                                              _ptr(w_down), T, _ptr(out), _ptr(probs), _ptr(saved), _stream()))
         return out, probs, saved
 
-    def dense_bwd(self, x, w_r, w_gate, w_up, w_down, saved, d_out, with_bias_grad=False):
+    def dense_bwd(self, x, w_r, w_gate, w_up, w_down, saved, d_out, with_bias_grad=False, buffers=None):
         T = x.shape[0]
         t = self.torch
-        n = c_size_t()
-        self._check(self.lib.dsmoe_dense_bwd_scratch_bytes(self.ctx, T, byref(n)))
-        scratch = self._empty((max(n.value, 16),), t.uint8)
-        g = dict(dx=self._empty((T, self.d), self.tdtype), dw_r=self._empty((self.d, self.E), t.float32),
-                 db_r=self._empty((self.E,), t.float32) if with_bias_grad else None,
-                 dw_gate=self._empty((self.E, self.d, self.f), t.float32),
-                 dw_up=self._empty((self.E, self.d, self.f), t.float32),
-                 dw_down=self._empty((self.E, self.f, self.d), t.float32))
+        if buffers is not None:
+            scratch, g = buffers["scratch"], buffers
+        else:
+            n = c_size_t()
+            self._check(self.lib.dsmoe_dense_bwd_scratch_bytes(self.ctx, T, byref(n)))
+            scratch = self._empty((max(n.value, 16),), t.uint8)
+            g = dict(dx=self._empty((T, self.d), self.tdtype), dw_r=self._empty((self.d, self.E), t.float32),
+                     db_r=self._empty((self.E,), t.float32) if with_bias_grad else None,
+                     dw_gate=self._empty((self.E, self.d, self.f), t.float32),
+                     dw_up=self._empty((self.E, self.d, self.f), t.float32),
+                     dw_down=self._empty((self.E, self.f, self.d), t.float32))
         self._check(self.lib.dsmoe_dense_bwd(self.ctx, _ptr(x), _ptr(w_r), _ptr(w_gate), _ptr(w_up), _ptr(w_down),
                                              _ptr(saved), _ptr(d_out), T, _ptr(scratch), _ptr(g["dx"]),
                                              _ptr(g["dw_r"]), _ptr(g["db_r"]), _ptr(g["dw_gate"]), _ptr(g["dw_up"]),
