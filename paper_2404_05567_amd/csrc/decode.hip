@@ -11,7 +11,7 @@
 //   * gate/up partials -> H = silu(G) * U (small elementwise kernel) -> down partials -> weighted combine.
 #include <algorithm>
 
-#include "gemm_bf16.h"
+#include "gemm_dma.h"
 
 namespace dsmoe {
 
@@ -87,8 +87,7 @@ decode_gateup_kernel(const bf16_t* __restrict__ x, const unsigned long long* __r
                      int32_t* __restrict__ row_token, float* __restrict__ row_weight, int32_t* __restrict__ tok_off,
                      int32_t* __restrict__ tok_rows, int32_t* __restrict__ nnz_out, int32_t* __restrict__ err_flag) {
   constexpr int BNS = 128;                       // columns of gate and of up per item
-  typedef Tile2<kDecT, 2 * BNS, 2, 4, 2> TL;
-  extern __shared__ __align__(16) char smem[];
+  typedef Tile3<kDecT, 2 * BNS, 2> TL;
   __shared__ DecodePlan plan;
   __shared__ int toks[kDecT];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -144,19 +143,15 @@ decode_gateup_kernel(const bf16_t* __restrict__ x, const unsigned long long* __r
         toks[__popcll(bits & ((1ull << lane) - 1ull)) + (wave == 1 ? plan.cnt_w0[e] : 0)] = threadIdx.x;
     }
     __syncthreads();
-    LRows2<kDecT> L;
-    L.seg_stride = 0;
-    {
-      const int r = min((int)(threadIdx.x >> 2), Me - 1);
-      L.p[0] = reinterpret_cast<const char*>(x + (size_t)toks[r] * d + (size_t)c * kc) + (threadIdx.x & 3) * 16;
-    }
-    RCols2<2 * BNS, 2> R;
+    typename TL::LSrc L;
+    L.init(Me, 0, [&](int r) { return x + (size_t)toks[r] * d + (size_t)c * kc; });
+    typename TL::RSrc R;
     const size_t wo = (size_t)e * d * f + (size_t)c * kc * f + n0;
     const bf16_t* const base[2] = {w_gate + wo, w_up + wo};
     R.init(base, f, min(BNS, f - n0), kc);
     typename TL::Acc acc;
     TL::zero(acc);
-    TL::mainloop(acc, L, R, kc / kBK2, 1 << 30, smem);
+    TL::mainloop(acc, L, R, kc / kBK2, 1 << 30, nullptr);
 #pragma unroll
     for (int mt = 0; mt < TL::MT; ++mt) {
       const int mrow = TL::acc_m(mt);
@@ -199,8 +194,7 @@ decode_down_kernel(const bf16_t* __restrict__ H, const int32_t* __restrict__ inf
                    const int32_t* __restrict__ expert_off, const bf16_t* __restrict__ w_down,
                    float* __restrict__ P2, int d, int f, int E) {
   constexpr int BN = 256;
-  typedef Tile2<kDecT, BN, 2, 4> TL;
-  extern __shared__ __align__(16) char smem[];
+  typedef Tile3<kDecT, BN> TL;
   __shared__ int sOff[kMaxExperts + 1], sAct[kMaxExperts];
   __shared__ int sU;
   if (threadIdx.x < 64) {
@@ -220,18 +214,14 @@ decode_down_kernel(const bf16_t* __restrict__ H, const int32_t* __restrict__ inf
   for (int item = blockIdx.x; item < items; item += gridDim.x) {
     const int c = item % ks2, j = (item / ks2) % ns2, e = sAct[item / (ks2 * ns2)];
     const int row0 = sOff[e], Me = sOff[e + 1] - row0, n0 = j * BN;
-    LRows2<kDecT> L;
-    L.seg_stride = 0;
-    {
-      const int r = min((int)(threadIdx.x >> 2), Me - 1);
-      L.p[0] = reinterpret_cast<const char*>(H + (size_t)(row0 + r) * f + (size_t)c * kc) + (threadIdx.x & 3) * 16;
-    }
-    RCols2<BN, 1> R;
+    typename TL::LSrc L;
+    L.init(Me, 0, [&](int r) { return H + (size_t)(row0 + r) * f + (size_t)c * kc; });
+    typename TL::RSrc R;
     const bf16_t* const base[1] = {w_down + (size_t)e * f * d + (size_t)c * kc * d + n0};
     R.init(base, d, min(BN, d - n0), kc);
     typename TL::Acc acc;
     TL::zero(acc);
-    TL::mainloop(acc, L, R, kc / kBK2, 1 << 30, smem);
+    TL::mainloop(acc, L, R, kc / kBK2, 1 << 30, nullptr);
 #pragma unroll
     for (int mt = 0; mt < TL::MT; ++mt) {
       const int mrow = TL::acc_m(mt);
@@ -255,17 +245,25 @@ __global__ void __launch_bounds__(kThreads)
 decode_combine_kernel(const float* __restrict__ P2, const int32_t* __restrict__ info,
                       const float* __restrict__ row_weight, const int32_t* __restrict__ tok_off,
                       const int32_t* __restrict__ tok_rows, int d, bf16_t* __restrict__ out) {
+  __shared__ int sRow[kMaxExperts];
+  __shared__ float sW[kMaxExperts];
   const int t = blockIdx.x;
   const int nnz = info[0], ks2 = info[3];
-  const int lo = tok_off[t], hi = tok_off[t + 1];
+  const int lo = tok_off[t], n = tok_off[t + 1] - lo;
+  if ((int)threadIdx.x < n) {
+    const int row = tok_rows[lo + threadIdx.x];
+    sRow[threadIdx.x] = row;
+    sW[threadIdx.x] = row_weight[row];
+  }
+  __syncthreads();
   for (int c0 = threadIdx.x * 4; c0 < d; c0 += kThreads * 4) {
     f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-    for (int j = lo; j < hi; ++j) {
-      const int row = tok_rows[j];
-      const float w = row_weight[row];
-      f32x4 y = {0.f, 0.f, 0.f, 0.f};
-      for (int c = 0; c < ks2; ++c)
-        y += __builtin_bit_cast(f32x4, ldg16(P2 + ((size_t)c * nnz + row) * (size_t)d + c0));
+#pragma unroll 4
+    for (int j = 0; j < n; ++j) {
+      const float* p = P2 + (size_t)sRow[j] * d + c0;
+      f32x4 y = __builtin_bit_cast(f32x4, ldg16(p));
+      for (int c = 1; c < ks2; ++c) y += __builtin_bit_cast(f32x4, ldg16(p + (size_t)c * nnz * d));
+      const float w = sW[j];
       acc.x = fmaf(w, y.x, acc.x);
       acc.y = fmaf(w, y.y, acc.y);
       acc.z = fmaf(w, y.z, acc.z);
@@ -279,18 +277,6 @@ decode_combine_kernel(const float* __restrict__ P2, const int32_t* __restrict__ 
 
 hipError_t launch_decode_fwd(const dsmoe_ctx* c, const void* x, const void* w_gate, const void* w_up,
                              const void* w_down, int T, void* out, hipStream_t s) {
-  typedef Tile2<kDecT, 256, 2, 4, 2> TL1;
-  typedef Tile2<kDecT, 256, 2, 4> TL2;
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e1 = hipFuncSetAttribute(reinterpret_cast<const void*>(&decode_gateup_kernel),
-                                        hipFuncAttributeMaxDynamicSharedMemorySize, TL1::LDS_BYTES);
-    hipError_t e2 = hipFuncSetAttribute(reinterpret_cast<const void*>(&decode_down_kernel),
-                                        hipFuncAttributeMaxDynamicSharedMemorySize, TL2::LDS_BYTES);
-    if (e1 != hipSuccess) return e1;
-    if (e2 != hipSuccess) return e2;
-    attr_set = true;
-  }
   const int d = c->desc.d_model, f = c->desc.d_ff, E = c->desc.n_experts;
   char* w = c->workspace;
   const float* probs = reinterpret_cast<const float*>(w + c->ws.probs);
@@ -309,7 +295,7 @@ hipError_t launch_decode_fwd(const dsmoe_ctx* c, const void* x, const void* w_ga
   const int grid = (c->n_cu + 7) / 8 * 8;
   const int row_cap = decode_row_cap(c);
 
-  decode_gateup_kernel<<<dim3(grid), dim3(kThreads2), TL1::LDS_BYTES, s>>>(
+  decode_gateup_kernel<<<dim3(grid), dim3(kThreads2), 0, s>>>(
       (const bf16_t*)x, mask, probs, (const bf16_t*)w_gate, (const bf16_t*)w_up, P1, T, d, f, E,
       (long long)c->desc.max_rows, row_cap, info, expert_off, row_token, row_weight, tok_off, tok_rows, nnz, err_flag);
   if (hipError_t e = hipGetLastError()) return e;
@@ -317,7 +303,7 @@ hipError_t launch_decode_fwd(const dsmoe_ctx* c, const void* x, const void* w_ga
   const int g_act = (int)std::max<long>(1, std::min<long>((quads + kThreads - 1) / kThreads, (long)c->n_cu * 8));
   decode_act_kernel<<<dim3(g_act), dim3(kThreads), 0, s>>>(P1, info, H, f);
   if (hipError_t e = hipGetLastError()) return e;
-  decode_down_kernel<<<dim3(grid), dim3(kThreads2), TL2::LDS_BYTES, s>>>(H, info, expert_off, (const bf16_t*)w_down,
+  decode_down_kernel<<<dim3(grid), dim3(kThreads2), 0, s>>>(H, info, expert_off, (const bf16_t*)w_down,
                                                                          P2, d, f, E);
   if (hipError_t e = hipGetLastError()) return e;
   decode_combine_kernel<<<dim3(T), dim3(kThreads), 0, s>>>(P2, info, row_weight, tok_off, tok_rows, d, (bf16_t*)out);

@@ -42,7 +42,7 @@ SavedLayout saved_layout(const dsmoe_ctx* c, int T) {
 
 constexpr int kWrTokens = 512;   // tokens per block of the router weight-gradient kernel
 
-struct ScratchLayout { size_t dU, dG, dS_part, dZ, dWr_part, dbr_part, total; int ntb, nsplit; };
+struct ScratchLayout { size_t zeros, dU, dG, dS_part, dZ, dWr_part, dbr_part, total; int ntb, nsplit; };
 ScratchLayout scratch_layout(const dsmoe_ctx* c, int T) {
   const size_t E = c->desc.n_experts, n = (size_t)T * E, nf = n * c->desc.d_ff * c->esize;
   const int bn1 = c->desc.dtype == DSMOE_BF16 ? DenseTiles<bf16_t>::BN1 : DenseTiles<float>::BN1;
@@ -50,6 +50,7 @@ ScratchLayout scratch_layout(const dsmoe_ctx* c, int T) {
   l.ntb = (c->desc.d_ff + bn1 - 1) / bn1;
   l.nsplit = std::max(1, (T + kWrTokens - 1) / kWrTokens);
   size_t o = 0;
+  l.zeros = o; o = al256(o + 256);   // read in place of token rows past T by the token-contracted products
   l.dU = o; o = al256(o + nf);
   l.dG = o; o = al256(o + nf);
   l.dS_part = o; o = al256(o + n * l.ntb * 4);
@@ -185,7 +186,7 @@ dense_bwd_dh_kernel(const T* __restrict__ d_out, const T* __restrict__ w_down, c
 template <typename T>
 __global__ void __launch_bounds__((Gemm<T, DenseTiles<T>::BM, DenseTiles<T>::BN1, 1, true, true, true>::THREADS))
 dense_bwd_dwdown_kernel(const T* __restrict__ Ht, const T* __restrict__ d_out, float* __restrict__ dw_down, int Tn,
-                        int d, int f, int E) {
+                        int d, int f, int E, const void* __restrict__ zeros) {
   typedef Gemm<T, DenseTiles<T>::BM, DenseTiles<T>::BN1, 1, true, true, true> GM;
   extern __shared__ __align__(16) char smem[];
   const int n_mt = (f + GM::BM - 1) / GM::BM, n_nt = (d + GM::BN - 1) / GM::BN;
@@ -197,10 +198,10 @@ dense_bwd_dwdown_kernel(const T* __restrict__ Ht, const T* __restrict__ d_out, f
     const int nt = idx % n_nt, mt = (idx / n_nt) % n_mt, e = idx / (n_nt * n_mt);
     const int m0 = mt * GM::BM, n0 = nt * GM::BN;
     typename GM::LSrc L;
-    GM::l_cols(L, Ht + (size_t)e * f + m0, EF, f - m0, Tn);
+    GM::l_cols(L, Ht + (size_t)e * f + m0, EF, f - m0, Tn, zeros);
     typename GM::RSrc R;
     const T* const base[1] = {d_out + n0};
-    GM::r_cols(R, base, d, d - n0, Tn);
+    GM::r_cols(R, base, d, d - n0, Tn, zeros);
     typename GM::Acc acc;
     GM::zero(acc);
     GM::mainloop(acc, L, R, (Tn + GM::BK - 1) / GM::BK, 1 << 30, smem);
@@ -215,7 +216,8 @@ dense_bwd_dwdown_kernel(const T* __restrict__ Ht, const T* __restrict__ d_out, f
 template <typename T>
 __global__ void __launch_bounds__((Gemm<T, DenseTiles<T>::BM, DenseTiles<T>::BN2, 2, true, true, true>::THREADS))
 dense_bwd_dwgu_kernel(const T* __restrict__ x, const T* __restrict__ dG, const T* __restrict__ dU,
-                      float* __restrict__ dw_gate, float* __restrict__ dw_up, int Tn, int d, int f, int E) {
+                      float* __restrict__ dw_gate, float* __restrict__ dw_up, int Tn, int d, int f, int E,
+                      const void* __restrict__ zeros) {
   typedef Gemm<T, DenseTiles<T>::BM, DenseTiles<T>::BN2, 2, true, true, true> GM;
   extern __shared__ __align__(16) char smem[];
   const int n_mt = (d + GM::BM - 1) / GM::BM, n_nt = (f + GM::BN - 1) / GM::BN;
@@ -227,10 +229,10 @@ dense_bwd_dwgu_kernel(const T* __restrict__ x, const T* __restrict__ dG, const T
     const int nt = idx % n_nt, mt = (idx / n_nt) % n_mt, e = idx / (n_nt * n_mt);
     const int m0 = mt * GM::BM, n0 = nt * GM::BN;
     typename GM::LSrc L;
-    GM::l_cols(L, x + m0, d, d - m0, Tn);
+    GM::l_cols(L, x + m0, d, d - m0, Tn, zeros);
     typename GM::RSrc R;
     const T* const base[2] = {dG + (size_t)e * f + n0, dU + (size_t)e * f + n0};
-    GM::r_cols(R, base, EF, f - n0, Tn);
+    GM::r_cols(R, base, EF, f - n0, Tn, zeros);
     typename GM::Acc acc;
     GM::zero(acc);
     GM::mainloop(acc, L, R, (Tn + GM::BK - 1) / GM::BK, 1 << 30, smem);
@@ -290,7 +292,8 @@ dense_bwd_dx_kernel(const T* __restrict__ dU, const T* __restrict__ dG, const T*
 // ---- softmax backward: dZ = S (dS - sum_k S_k dS_k), one wave per token, one lane per expert -------------
 __global__ void __launch_bounds__(kThreads)
 dense_softmax_bwd_kernel(const float* __restrict__ S, const float* __restrict__ dS_part, int ntb, int Tn, int E,
-                         float* __restrict__ dZ) {
+                         float* __restrict__ dZ, unsigned* __restrict__ zeros) {
+  if (blockIdx.x == 0 && threadIdx.x < 64) zeros[threadIdx.x] = 0u;   // the zero page of the later kernels
   const int lane = threadIdx.x & 63;
   const int t = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (t >= Tn) return;
@@ -429,7 +432,8 @@ hipError_t dense_bwd_t(const dsmoe_ctx* c, const void* x, const void* w_r, const
       (const T*)d_out, (const T*)w_down, S, G, U, dU, dG, dS_part, Tn, d, f, E);
   if (hipError_t e = hipGetLastError()) return e;
 
-  dense_softmax_bwd_kernel<<<dim3((Tn + 3) / 4), dim3(kThreads), 0, s>>>(S, dS_part, sc.ntb, Tn, E, dZ);
+  dense_softmax_bwd_kernel<<<dim3((Tn + 3) / 4), dim3(kThreads), 0, s>>>(S, dS_part, sc.ntb, Tn, E, dZ,
+                                                                                  reinterpret_cast<unsigned*>(scratch + sc.zeros));
   if (hipError_t e = hipGetLastError()) return e;
 
   dense_router_dw_kernel<T><<<dim3(d / 64, sc.nsplit), dim3(kThreads), 0, s>>>((const T*)x, dZ, Tn, d, E, dWr_part,
@@ -441,12 +445,12 @@ hipError_t dense_bwd_t(const dsmoe_ctx* c, const void* x, const void* w_r, const
 
   tiles = E * cdiv(f, DT::BM) * cdiv(d, DT::BN1);
   dense_bwd_dwdown_kernel<T><<<dim3(grid_for(c, tiles, bpc)), dim3(GCC1::THREADS), GCC1::LDS_BYTES, s>>>(
-      Ht, (const T*)d_out, dw_down, Tn, d, f, E);
+      Ht, (const T*)d_out, dw_down, Tn, d, f, E, scratch + sc.zeros);
   if (hipError_t e = hipGetLastError()) return e;
 
   tiles = E * cdiv(d, DT::BM) * cdiv(f, DT::BN2);
   dense_bwd_dwgu_kernel<T><<<dim3(grid_for(c, tiles, bpc)), dim3(GCC2::THREADS), GCC2::LDS_BYTES, s>>>(
-      (const T*)x, dG, dU, dw_gate, dw_up, Tn, d, f, E);
+      (const T*)x, dG, dU, dw_gate, dw_up, Tn, d, f, E, scratch + sc.zeros);
   if (hipError_t e = hipGetLastError()) return e;
 
   tiles = cdiv(Tn, DT::BM) * cdiv(d, DT::BN1);

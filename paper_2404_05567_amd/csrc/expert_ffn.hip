@@ -9,7 +9,7 @@
 // through row_token while staging the L operand (no permuted copy of X is required).
 #include <algorithm>
 
-#include "gemm_bf16.h"
+#include "gemm_dma.h"
 
 namespace dsmoe {
 
@@ -138,8 +138,7 @@ gateup_bf16_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ x_pe
                    const int32_t* __restrict__ expert_off, const bf16_t* __restrict__ w_gate,
                    const bf16_t* __restrict__ w_up, bf16_t* __restrict__ h, int d, int f, int E) {
   constexpr int BNS = 128;                         // columns per source (gate, up) and block
-  typedef Tile2<BM, 2 * BNS, 2, 4, 2> TL;
-  extern __shared__ __align__(16) char smem[];
+  typedef Tile3<BM, 2 * BNS, 2> TL;
   __shared__ GroupTiles gt;
   build_group_tiles(gt, expert_off, E, BM);
   const int n_tiles = (f + BNS - 1) / BNS;
@@ -153,20 +152,16 @@ gateup_bf16_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ x_pe
     const int valid = min(BM, gt.row_off[e + 1] - row0);
     const int n0 = nt_blk * BNS;
 
-    LRows2<BM> L;
-    L.seg_stride = 0;
-#pragma unroll
-    for (int i = 0; i < LRows2<BM>::NV; ++i) {
-      const int r = min((int)(threadIdx.x >> 2) + 128 * i, valid - 1);
-      const bf16_t* src = x_perm ? x_perm + (size_t)(row0 + r) * d : x + (size_t)row_token[row0 + r] * d;
-      L.p[i] = reinterpret_cast<const char*>(src) + (threadIdx.x & 3) * 16;
-    }
-    RCols2<2 * BNS, 2> R;
+    typename TL::LSrc L;
+    L.init(valid, 0, [&](int r) {
+      return x_perm ? x_perm + (size_t)(row0 + r) * d : x + (size_t)row_token[row0 + r] * d;
+    });
+    typename TL::RSrc R;
     const bf16_t* const base[2] = {w_gate + (size_t)e * d * f + n0, w_up + (size_t)e * d * f + n0};
     R.init(base, f, min(BNS, f - n0), d);
     typename TL::Acc acc;
     TL::zero(acc);
-    TL::mainloop(acc, L, R, d / TL::BK, 1 << 30, smem);
+    TL::mainloop(acc, L, R, d / TL::BK, 1 << 30, nullptr);
 
 #pragma unroll
     for (int mt = 0; mt < TL::MT; ++mt) {
@@ -191,8 +186,7 @@ __global__ void __launch_bounds__(kThreads2)
 down_bf16_kernel(const bf16_t* __restrict__ h, const int32_t* __restrict__ expert_off,
                  const bf16_t* __restrict__ w_down, bf16_t* __restrict__ y, int d, int f, int E, int uniform_rows) {
   constexpr int BN = 256;
-  typedef Tile2<BM, BN, 2, 4> TL;
-  extern __shared__ __align__(16) char smem[];
+  typedef Tile3<BM, BN> TL;
   __shared__ GroupTiles gt;
   build_group_tiles(gt, expert_off, E, BM, uniform_rows);
   const int n_tiles = (d + BN - 1) / BN;
@@ -206,19 +200,14 @@ down_bf16_kernel(const bf16_t* __restrict__ h, const int32_t* __restrict__ exper
     const int valid = min(BM, gt.row_off[e + 1] - row0);
     const int n0 = nt_blk * BN;
 
-    LRows2<BM> L;
-    L.seg_stride = 0;
-#pragma unroll
-    for (int i = 0; i < LRows2<BM>::NV; ++i) {
-      const int r = min((int)(threadIdx.x >> 2) + 128 * i, valid - 1);
-      L.p[i] = reinterpret_cast<const char*>(h + (size_t)(row0 + r) * f) + (threadIdx.x & 3) * 16;
-    }
-    RCols2<BN, 1> R;
+    typename TL::LSrc L;
+    L.init(valid, 0, [&](int r) { return h + (size_t)(row0 + r) * f; });
+    typename TL::RSrc R;
     const bf16_t* const base[1] = {w_down + (size_t)e * f * d + n0};
     R.init(base, d, min(BN, d - n0), f);
     typename TL::Acc acc;
     TL::zero(acc);
-    TL::mainloop(acc, L, R, f / TL::BK, 1 << 30, smem);
+    TL::mainloop(acc, L, R, f / TL::BK, 1 << 30, nullptr);
 
 #pragma unroll
     for (int mt = 0; mt < TL::MT; ++mt) {
@@ -238,41 +227,24 @@ down_bf16_kernel(const bf16_t* __restrict__ h, const int32_t* __restrict__ exper
   }
 }
 
-// kernels whose dynamic LDS exceeds the default limit need the attribute once per process
-static hipError_t ffn_bf16_attrs() {
-  static bool attr_set = false;
-  if (attr_set) return hipSuccess;
-  typedef Tile2<256, 256, 2, 4> TL;
-  hipError_t e1 = hipFuncSetAttribute(reinterpret_cast<const void*>(&gateup_bf16_kernel<256>),
-                                      hipFuncAttributeMaxDynamicSharedMemorySize, TL::LDS_BYTES);
-  hipError_t e2 = hipFuncSetAttribute(reinterpret_cast<const void*>(&down_bf16_kernel<256>),
-                                      hipFuncAttributeMaxDynamicSharedMemorySize, TL::LDS_BYTES);
-  if (e1 != hipSuccess) return e1;
-  if (e2 != hipSuccess) return e2;
-  attr_set = true;
-  return hipSuccess;
-}
-
 static hipError_t launch_ffn_bf16(const dsmoe_ctx* c, const void* x, const void* x_perm, const int32_t* row_token,
                                   const int32_t* expert_off, const void* w_gate, const void* w_up,
                                   const void* w_down, void* y_perm, hipStream_t s) {
   constexpr int BM = 256;
-  typedef Tile2<BM, 256, 2, 4> TL;
   const int d = c->desc.d_model, f = c->desc.d_ff, E = c->desc.n_experts;
   bf16_t* h = reinterpret_cast<bf16_t*>(c->workspace + c->ws.h);
-  if (hipError_t e = ffn_bf16_attrs()) return e;
   const long max_mt = (c->desc.max_rows + BM - 1) / BM + E;
   const long t1 = max_mt * ((f + 127) / 128), t2 = max_mt * ((d + 255) / 256);
   const int g1 = (int)((std::min<long>(t1, c->n_cu) + 7) / 8 * 8), g2 = (int)((std::min<long>(t2, c->n_cu) + 7) / 8 * 8);
   hipEvent_t* ev = (c->prof.ev && c->prof.n < c->prof.max_calls) ? c->prof.ev + 3 * c->prof.n++ : nullptr;
   if (ev) (void)hipEventRecord(ev[0], s);
-  gateup_bf16_kernel<BM><<<dim3(g1), dim3(kThreads2), TL::LDS_BYTES, s>>>(
+  gateup_bf16_kernel<BM><<<dim3(g1), dim3(kThreads2), 0, s>>>(
       (const bf16_t*)x, (const bf16_t*)x_perm, row_token, expert_off, (const bf16_t*)w_gate, (const bf16_t*)w_up, h,
       d, f, E);
   hipError_t err = hipGetLastError();
   if (err != hipSuccess) return err;
   if (ev) (void)hipEventRecord(ev[1], s);
-  down_bf16_kernel<BM><<<dim3(g2), dim3(kThreads2), TL::LDS_BYTES, s>>>(h, expert_off, (const bf16_t*)w_down,
+  down_bf16_kernel<BM><<<dim3(g2), dim3(kThreads2), 0, s>>>(h, expert_off, (const bf16_t*)w_down,
                                                                         (bf16_t*)y_perm, d, f, E, 0);
   err = hipGetLastError();
   if (ev) (void)hipEventRecord(ev[2], s);
@@ -312,11 +284,9 @@ hipError_t launch_down_dense(const dsmoe_ctx* c, const void* h, int T, int k_tot
                              hipStream_t s) {
   const int d = c->desc.d_model;
   if (c->desc.dtype == DSMOE_BF16) {
-    if (hipError_t e = ffn_bf16_attrs()) return e;
-    typedef Tile2<256, 256, 2, 4> TL;
     const long tiles = (long)((T + 255) / 256) * ((d + 255) / 256);
     const int g = (int)((std::min<long>(tiles, c->n_cu) + 7) / 8 * 8);
-    down_bf16_kernel<256><<<dim3(g), dim3(kThreads2), TL::LDS_BYTES, s>>>((const bf16_t*)h, nullptr, (const bf16_t*)w,
+    down_bf16_kernel<256><<<dim3(g), dim3(kThreads2), 0, s>>>((const bf16_t*)h, nullptr, (const bf16_t*)w,
                                                                           (bf16_t*)out, d, k_total, 1, T);
   } else {
     constexpr int BM = 128, BN = 256;

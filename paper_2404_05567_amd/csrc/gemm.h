@@ -1,7 +1,8 @@
 // One front end for the two MFMA contraction cores, so that a kernel body is written once for both
 // storage types:
 //   float  -> Tile  (gemm_core.h): 256 threads, [row][k] LDS tiles, fp32 MFMA (exact fp32 products)
-//   bf16_t -> Tile2 (gemm_bf16.h): 512 threads, k-major tiles read with the transposing LDS load
+//   bf16_t -> Tile3 (gemm_dma.h): 512 threads, direct global -> LDS loads, k-major tiles read with the
+//             transposing LDS load
 //
 //   Out[m][n] = sum_k L[m][k] * R_s[k][n]      for NSRC weight-side sources s sharing one L tile
 //
@@ -15,7 +16,7 @@
 
 #include <type_traits>
 
-#include "gemm_bf16.h"
+#include "gemm_dma.h"
 
 namespace dsmoe {
 
@@ -70,7 +71,8 @@ struct Gemm<float, BM_, BN_, NSRC_, LK, RK, KTAIL> {
   static __device__ __forceinline__ void l_rows(LSrc& s, int valid, size_t seg_stride_bytes, F row_base) {
     init_rows(s, valid, seg_stride_bytes, row_base);
   }
-  static __device__ __forceinline__ void l_cols(LSrc& s, const T* base, size_t ld, int rows_valid, int k_valid) {
+  static __device__ __forceinline__ void l_cols(LSrc& s, const T* base, size_t ld, int rows_valid, int k_valid,
+                                                const void* = nullptr) {
     init_cols(s, base, ld, rows_valid, k_valid);
   }
   template <class F>
@@ -79,7 +81,7 @@ struct Gemm<float, BM_, BN_, NSRC_, LK, RK, KTAIL> {
     init_rows(s.s[0], valid, seg_stride_bytes, row_base);
   }
   static __device__ __forceinline__ void r_cols(RSrc& s, const T* const (&base)[NSRC], size_t ld, int rows_valid,
-                                                int k_valid) {
+                                                int k_valid, const void* = nullptr) {
 #pragma unroll
     for (int b = 0; b < NSRC; ++b) init_cols(s.s[b], base[b], ld, rows_valid, k_valid);
   }
@@ -113,29 +115,30 @@ struct Gemm<float, BM_, BN_, NSRC_, LK, RK, KTAIL> {
 template <int BM_, int BN_, int NSRC_, bool LK, bool RK, bool KTAIL>
 struct Gemm<bf16_t, BM_, BN_, NSRC_, LK, RK, KTAIL> {
   typedef bf16_t T;
-  typedef Tile2<BM_, BN_ * NSRC_, 2, 4, NSRC_, LK, RK> TL;
+  typedef Tile3<BM_, BN_ * NSRC_, NSRC_, LK, RK, KTAIL> TL;
   static constexpr int BM = BM_, BN = BN_, NSRC = NSRC_, BK = TL::BK, THREADS = kThreads2, LDS_BYTES = TL::LDS_BYTES;
   static constexpr int WAVES_N = 4;
-  typedef std::conditional_t<LK, RCols2<BM, 1, KTAIL>, LRows2<BM>> LSrc;
-  typedef std::conditional_t<RK, RCols2<BN * NSRC, NSRC, KTAIL>, LRows2<BN * NSRC>> RSrc;
+  typedef typename TL::LSrc LSrc;
+  typedef typename TL::RSrc RSrc;
   typedef typename TL::Acc Acc;
 
   template <class F>
   static __device__ __forceinline__ void l_rows(LSrc& s, int valid, size_t seg_stride_bytes, F row_base) {
-    init_rows(s, valid, seg_stride_bytes, row_base);
+    s.init(valid, seg_stride_bytes, row_base);
   }
-  static __device__ __forceinline__ void l_cols(LSrc& s, const T* base, size_t ld, int rows_valid, int k_valid) {
+  static __device__ __forceinline__ void l_cols(LSrc& s, const T* base, size_t ld, int rows_valid, int k_valid,
+                                                const void* zeros = nullptr) {
     const T* const b[1] = {base};
-    s.init(b, ld, rows_valid, k_valid);
+    s.init(b, ld, rows_valid, k_valid, zeros);
   }
   template <class F>
   static __device__ __forceinline__ void r_rows(RSrc& s, int valid, size_t seg_stride_bytes, F row_base) {
     static_assert(NSRC == 1, "one source");
-    init_rows(s, valid, seg_stride_bytes, row_base);
+    s.init(valid, seg_stride_bytes, row_base);
   }
   static __device__ __forceinline__ void r_cols(RSrc& s, const T* const (&base)[NSRC], size_t ld, int rows_valid,
-                                                int k_valid) {
-    s.init(base, ld, rows_valid, k_valid);
+                                                int k_valid, const void* zeros = nullptr) {
+    s.init(base, ld, rows_valid, k_valid, zeros);
   }
   static __device__ __forceinline__ void zero(Acc& acc) { TL::zero(acc); }
   static __device__ __forceinline__ void mainloop(Acc& acc, const LSrc& L, const RSrc& R, int nkt, int seg_tiles,

@@ -1,0 +1,290 @@
+// bf16 MFMA contraction for gfx950 with direct global -> LDS loads, 512 threads (8 waves, 2 x 4).
+//
+//   Out[m][n] = sum_k L[m][k] * R[k][n]
+//
+// Per K step of 32 every wave issues `global_load_lds_dwordx4` instructions: each moves 64 x 16 bytes
+// from per-lane global addresses into 1 KB of consecutive LDS, without passing through registers.  Four
+// LDS stages of one K step each are kept in flight (three steps of prefetch distance); a step costs one
+// barrier, placed between the MFMAs of its two 16-wide K slices so that the fragments of the next slice
+// are read while the current one multiplies.
+//
+// The LDS image of a 1 KB chunk is fixed (lane i writes bytes [16 i, 16 i + 16)), so bank conflicts are
+// avoided by choosing WHICH global 16 bytes a lane fetches (an XOR swizzle), not by padding:
+//   "rows" operand (rows k-contiguous: activations, or a weight used transposed): tile [row][32 k], 64 bytes
+//       per row; the 16-byte piece kc of row r lies at position kc ^ ((r >> 2) & 3).  Read with ds_read_b128.
+//   "cols" operand (stored [k][n], n contiguous: a weight, or X^T / dY for weight gradients): tile [32 k][n];
+//       the 64-byte unit U of row k lies at unit U ^ (k & 3).  Read with the transposing ds_read_b64_tr_b16,
+//       which hands a lane the 4 k-consecutive values of one column.
+// Both layouts can serve either side of the product.  Each stage is a separate __shared__ array: the
+// compiler then knows which loads a fragment read depends on and waits only for those.
+//
+// The weight fragment is the MFMA "A" operand and the token fragment the "B" operand: a lane of the 32x32
+// accumulator owns one token row and 4 consecutive output columns per register quad.
+#pragma once
+
+#include <type_traits>
+
+#include "gemm_bf16.h"
+
+namespace dsmoe {
+
+constexpr int kStages3 = 4;
+
+typedef __attribute__((address_space(1))) const void gvoid_t;
+typedef __attribute__((address_space(3))) void lvoid_t;
+
+__device__ __forceinline__ void dma16(const char* g, char* lds) {
+  __builtin_amdgcn_global_load_lds((gvoid_t*)g, (lvoid_t*)lds, 16, 0, 0);
+}
+// s_waitcnt on the vector-memory counter alone (N outstanding loads allowed), optionally also on all LDS reads
+template <int N, bool LGKM0>
+__device__ __forceinline__ void wait_vm() {
+  __builtin_amdgcn_s_waitcnt((N & 0xF) | ((N >> 4) << 14) | (7 << 4) | ((LGKM0 ? 0 : 15) << 8));
+}
+
+// ---- "rows" operand -----------------------------------------------------------------------------------
+template <int ROWS>
+struct DRows {
+  static constexpr bool kKMajor = false;
+  static constexpr int LDS = ROWS * 64;
+  static constexpr int CPW = ROWS / 128;          // 1 KB chunks (16 rows) per wave and K step
+  static constexpr int NI = CPW;
+  const char* p[CPW];   // this lane's piece of each of its chunks, K segment 0, step 0
+  size_t seg_stride;    // bytes between K segments
+
+  // row_base(r): address of element [row r][k = 0]; rows >= valid re-read row valid - 1
+  template <class F>
+  __device__ __forceinline__ void init(int valid, size_t seg_stride_bytes, F row_base) {
+    seg_stride = seg_stride_bytes;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+#pragma unroll
+    for (int i = 0; i < CPW; ++i) {
+      const int r = 16 * (wave * CPW + i) + (lane >> 2);
+      const int kc = (lane & 3) ^ ((r >> 2) & 3);
+      p[i] = reinterpret_cast<const char*>(row_base(min(r, valid - 1))) + kc * 16;
+    }
+  }
+  __device__ __forceinline__ void issue(char* stage, int seg, int kin) const {
+    const size_t off = (size_t)seg * seg_stride + (size_t)kin * 64;
+    char* dst = stage + (threadIdx.x >> 6) * (CPW * 1024);
+#pragma unroll
+    for (int i = 0; i < CPW; ++i) dma16(p[i] + off, dst + i * 1024);
+  }
+  // lane offset of the fragment of 32 rows starting at `first` (a multiple of 32), K slice ks
+  static __device__ __forceinline__ int frag_off(int first, int ks) {
+    const int lane = threadIdx.x & 63;
+    return (first + (lane & 31)) * 64 + (((2 * ks + (lane >> 5)) ^ ((lane >> 2) & 3)) * 16);
+  }
+  static __device__ __forceinline__ u32x4 read(const char* tile, int off, int group) {
+    return *reinterpret_cast<const u32x4*>(tile + off + group * (32 * 64));
+  }
+};
+
+// ---- "cols" operand -----------------------------------------------------------------------------------
+// NSRC matrices each contribute COLS / NSRC columns; source s occupies tile columns [s * COLS / NSRC, ...).
+// KTAIL: k >= k_valid is read from `zeros` (at least 16 readable zero bytes).
+template <int COLS, int NSRC, bool KTAIL = false>
+struct DCols {
+  static constexpr bool kKMajor = true;
+  static constexpr int RB = COLS * 2;             // bytes per k row
+  static constexpr int LDS = kBK2 * RB;
+  static constexpr int KPC = 1024 / RB;           // k rows per 1 KB chunk
+  static constexpr int PPR = RB / 16;             // 16-byte pieces per k row
+  static constexpr int CPW = COLS / 128;          // chunks per wave and K step
+  static constexpr int NI = CPW;
+  const char* p[CPW];
+  size_t step_bytes;    // bytes between K steps (32 * ld)
+  size_t seg_stride;
+  int k_valid;
+  const char* zeros;
+
+  // base[s]: element [k = 0][first column of the tile] of source s; cols_valid: columns of each source that
+  // exist from there on (columns past the end are read from column 0 and never reach a stored output)
+  __device__ __forceinline__ void init(const bf16_t* const (&base)[NSRC], size_t ld_elems, int cols_valid, int kv,
+                                       const void* zero_page = nullptr) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    step_bytes = (size_t)kBK2 * ld_elems * 2;
+    seg_stride = 0;
+    k_valid = kv;
+    zeros = static_cast<const char*>(zero_page);
+#pragma unroll
+    for (int i = 0; i < CPW; ++i) {
+      const int k = (wave * CPW + i) * KPC + lane / PPR, q = lane % PPR;
+      const int U = (q >> 2) ^ (k & 3), col = U * 32 + (q & 3) * 8;      // tile column of this lane's piece
+      constexpr int CPS = COLS / NSRC;
+      const int src = col / CPS, cs = col % CPS;
+      p[i] = reinterpret_cast<const char*>(base[src] + (size_t)k * ld_elems + (cs < cols_valid ? cs : 0));
+    }
+  }
+  __device__ __forceinline__ void issue(char* stage, int seg, int kin) const {
+    const size_t off = (size_t)seg * seg_stride + (size_t)kin * step_bytes;
+    char* dst = stage + (threadIdx.x >> 6) * (CPW * 1024);
+#pragma unroll
+    for (int i = 0; i < CPW; ++i) {
+      const char* g = p[i] + off;
+      if (KTAIL) {
+        const int k = kin * kBK2 + ((threadIdx.x >> 6) * CPW + i) * KPC + (threadIdx.x & 63) / PPR;
+        g = k < k_valid ? g : zeros;
+      }
+      dma16(g, dst + i * 1024);
+    }
+  }
+  // lane offset (without the column-unit term) of a fragment, K slice ks; unit_off(first) adds the columns
+  static __device__ __forceinline__ int frag_off(int first, int ks) {
+    const int lane = threadIdx.x & 63, i = lane & 15;
+    return (16 * ks + 8 * (lane >> 5) + (i >> 2)) * RB + (((first >> 5) ^ (i >> 2)) * 64) + 32 * ((lane >> 4) & 1) +
+           8 * (i & 3);
+  }
+  static __device__ __forceinline__ u32x4 read(const char* tile, int off) {
+    const u32x2 lo = lds_read_tr16(tile + off);
+    const u32x2 hi = lds_read_tr16(tile + off + 4 * RB);
+    return u32x4{lo.x, lo.y, hi.x, hi.y};
+  }
+};
+
+// NSRC = 2: the wave's two column tiles are the same 32 columns of source 0 (gate) and source 1 (up).
+template <int BM_, int BN_, int NSRC_ = 1, bool L_KMAJOR = false, bool R_KMAJOR = true, bool KTAIL = false>
+struct Tile3 {
+  static constexpr int BM = BM_, BN = BN_, NSRC = NSRC_, BK = kBK2, WGM = 2, WGN = 4;
+  static constexpr int WM = BM / WGM, WN = BN / WGN;
+  static constexpr int MT = WM / 32, NT = WN / 32;
+  static_assert(NSRC == 1 || NT == NSRC, "one column tile per source");
+  static_assert(NSRC == 1 || R_KMAJOR, "several sources need the k-major weight layout");
+  typedef std::conditional_t<L_KMAJOR, DCols<BM, 1, KTAIL>, DRows<BM>> LSrc;
+  typedef std::conditional_t<R_KMAJOR, DCols<BN, NSRC, KTAIL>, DRows<BN>> RSrc;
+  static constexpr int LDS_L = LSrc::LDS, LDS_R = RSrc::LDS;
+  static constexpr int LDS_BYTES = 0;                                   // stages are static arrays
+  static constexpr int NI = LSrc::NI + RSrc::NI;                        // loads per wave and K step
+  static constexpr int WCOL = NSRC == 1 ? WN : 32, NT_COLS = NSRC == 1 ? 32 : BN / NSRC;
+  static constexpr int NFR = (L_KMAJOR ? 2 : 1) * MT + (R_KMAJOR ? 2 : 1) * NT;   // LDS reads per K slice
+  static constexpr int NMMA = MT * NT;
+  typedef f32x16 Acc[NT][MT];
+  struct Frag { u32x4 x[MT], w[NT]; };
+  struct Offs { int l[2][L_KMAJOR ? MT : 1], r[2][R_KMAJOR ? NT : 1]; };
+
+  static __device__ __forceinline__ void zero(Acc& acc) {
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc[nt][mt][i] = 0.f;
+  }
+
+  static __device__ __forceinline__ void offsets(Offs& o) {
+    const int wave = threadIdx.x >> 6;
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks) {
+      if constexpr (L_KMAJOR) {
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) o.l[ks][mt] = LSrc::frag_off((wave / WGN) * WM + mt * 32, ks);
+      } else {
+        o.l[ks][0] = LSrc::frag_off((wave / WGN) * WM, ks);
+      }
+      if constexpr (R_KMAJOR) {
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) o.r[ks][nt] = RSrc::frag_off((wave % WGN) * WCOL + nt * NT_COLS, ks);
+      } else {
+        o.r[ks][0] = RSrc::frag_off((wave % WGN) * WCOL, ks);
+      }
+    }
+  }
+  static __device__ __forceinline__ void read_frags(Frag& f, const char* sl, const char* sr, const Offs& o, int ks) {
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+      if constexpr (L_KMAJOR) f.x[mt] = LSrc::read(sl, o.l[ks][mt]);
+      else f.x[mt] = LSrc::read(sl, o.l[ks][0], mt);
+    }
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+      if constexpr (R_KMAJOR) f.w[nt] = RSrc::read(sr, o.r[ks][nt]);
+      else f.w[nt] = RSrc::read(sr, o.r[ks][0], nt);
+    }
+  }
+  static __device__ __forceinline__ void mma(Acc& acc, const Frag& f) {
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) Mma<bf16_t>::run(acc[nt][mt], f.w[nt], f.x[mt]);
+  }
+  // issue order for the scheduler: the LDS reads of the next slice spread over the MFMAs of this one
+  static __device__ __forceinline__ void interleave() { Interleave<0, NMMA, NFR, kSgDsRd>::run(); }
+
+  // acc += L * R over nkt K steps; K may be split in segments of seg_tiles steps (see the sources).
+  // Must be called by all 512 threads; returns with none of this wave's loads in flight.
+  static __device__ __forceinline__ void mainloop(Acc& acc, const LSrc& L, const RSrc& R, int nkt, int seg_tiles,
+                                                  char* /*unused: stages are static*/) {
+    __shared__ __align__(1024) char sL0[LDS_L], sL1[LDS_L], sL2[LDS_L], sL3[LDS_L];
+    __shared__ __align__(1024) char sR0[LDS_R], sR1[LDS_R], sR2[LDS_R], sR3[LDS_R];
+    Offs o;
+    offsets(o);
+    int seg = 0, kin = 0, next = 0;   // position of the next K step to load
+    // Loads are issued unconditionally (steps past the end re-read the last one, into a stage nobody reads
+    // any more): the loop body stays free of branches and the number of loads in flight is a constant.
+    auto issue_next = [&](char* sl, char* sr) {
+      L.issue(sl, seg, kin);
+      R.issue(sr, seg, kin);
+      if (++next < nkt && ++kin == seg_tiles) { kin = 0; ++seg; }
+    };
+    issue_next(sL0, sR0);
+    issue_next(sL1, sR1);
+    issue_next(sL2, sR2);
+    issue_next(sL3, sR3);
+    Frag fa, fb;
+    __builtin_amdgcn_sched_barrier(0);
+    wait_vm<3 * NI, true>();          // step 0 has landed
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_sched_barrier(0);
+    read_frags(fa, sL0, sR0, o, 0);
+
+    // One K step on stage ST: slice 0 multiplies while slice 1 is read; then, once step + 1 has landed for
+    // every wave (and every wave has read this stage to the end), the stage is refilled with step + 4 and
+    // slice 0 of the next stage is read while slice 1 multiplies.
+#define DSMOE_STEP3(ST, NX)                                                   \
+  {                                                                           \
+    read_frags(fb, sL##ST, sR##ST, o, 1);                                     \
+    mma(acc, fa);                                                             \
+    interleave();                                                             \
+    __builtin_amdgcn_sched_barrier(0);                                        \
+    wait_vm<2 * NI, true>();                                                  \
+    __builtin_amdgcn_s_barrier();                                             \
+    __builtin_amdgcn_sched_barrier(0);                                        \
+    issue_next(sL##ST, sR##ST);                                               \
+    __builtin_amdgcn_sched_barrier(0);                                        \
+    read_frags(fa, sL##NX, sR##NX, o, 0);                                     \
+    mma(acc, fb);                                                             \
+    interleave();                                                             \
+  }
+    int kt = 0;
+    for (; kt + kStages3 <= nkt; kt += kStages3) {
+      DSMOE_STEP3(0, 1)
+      DSMOE_STEP3(1, 2)
+      DSMOE_STEP3(2, 3)
+      DSMOE_STEP3(3, 0)
+    }
+    if (kt < nkt) {
+      DSMOE_STEP3(0, 1)
+      if (kt + 1 < nkt) {
+        DSMOE_STEP3(1, 2)
+        if (kt + 2 < nkt) DSMOE_STEP3(2, 3)
+      }
+    }
+#undef DSMOE_STEP3
+    // every wave read its last fragments before the last barrier; drain the re-read loads
+    __builtin_amdgcn_sched_barrier(0);
+    wait_vm<0, true>();
+    __builtin_amdgcn_sched_barrier(0);
+  }
+
+  static __device__ __forceinline__ int acc_m(int mt) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    return (wave / WGN) * WM + mt * 32 + (lane & 31);
+  }
+  // column (inside its source) of register quad g of column tile nt
+  static __device__ __forceinline__ int acc_n(int nt, int g) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    return (wave % WGN) * WCOL + (NSRC == 1 ? nt * 32 : 0) + g * 8 + (lane >> 5) * 4;
+  }
+};
+
+}  // namespace dsmoe
