@@ -11,7 +11,7 @@
 //   * gate/up partials -> H = silu(G) * U (small elementwise kernel) -> down partials -> weighted combine.
 #include <algorithm>
 
-#include "gemm_dma.h"
+#include "gemm.h"
 
 namespace dsmoe {
 
@@ -88,6 +88,7 @@ decode_gateup_kernel(const bf16_t* __restrict__ x, const unsigned long long* __r
                      int32_t* __restrict__ tok_rows, int32_t* __restrict__ nnz_out, int32_t* __restrict__ err_flag) {
   constexpr int BNS = 128;                       // columns of gate and of up per item
   typedef Tile3<kDecT, 2 * BNS, 2> TL;
+  DSMOE_TILE3_STAGES(TL, st);
   __shared__ DecodePlan plan;
   __shared__ int toks[kDecT];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -151,7 +152,8 @@ decode_gateup_kernel(const bf16_t* __restrict__ x, const unsigned long long* __r
     R.init(base, f, min(BNS, f - n0), kc);
     typename TL::Acc acc;
     TL::zero(acc);
-    TL::mainloop(acc, L, R, kc / kBK2, 1 << 30, nullptr);
+    TL::mainloop(acc, L, R, kc / kBK2, 1 << 30, st);
+    // few rows and fp32 partial sums: stored straight from the accumulator layout
 #pragma unroll
     for (int mt = 0; mt < TL::MT; ++mt) {
       const int mrow = TL::acc_m(mt);
@@ -195,6 +197,7 @@ decode_down_kernel(const bf16_t* __restrict__ H, const int32_t* __restrict__ inf
                    float* __restrict__ P2, int d, int f, int E) {
   constexpr int BN = 256;
   typedef Tile3<kDecT, BN> TL;
+  DSMOE_TILE3_STAGES(TL, st);
   __shared__ int sOff[kMaxExperts + 1], sAct[kMaxExperts];
   __shared__ int sU;
   if (threadIdx.x < 64) {
@@ -221,7 +224,7 @@ decode_down_kernel(const bf16_t* __restrict__ H, const int32_t* __restrict__ inf
     R.init(base, d, min(BN, d - n0), kc);
     typename TL::Acc acc;
     TL::zero(acc);
-    TL::mainloop(acc, L, R, kc / kBK2, 1 << 30, nullptr);
+    TL::mainloop(acc, L, R, kc / kBK2, 1 << 30, st);
 #pragma unroll
     for (int mt = 0; mt < TL::MT; ++mt) {
       const int mrow = TL::acc_m(mt);

@@ -63,18 +63,6 @@ ScratchLayout scratch_layout(const dsmoe_ctx* c, int T) {
 
 __device__ __forceinline__ float sigmoid_f(float g) { return 1.f / (1.f + __expf(-g)); }
 
-template <typename T> __device__ __forceinline__ void load4(const T* p, float (&v)[4]);
-template <> __device__ __forceinline__ void load4<float>(const float* p, float (&v)[4]) {
-  const f32x4 q = __builtin_bit_cast(f32x4, ldg16(p));
-  v[0] = q.x; v[1] = q.y; v[2] = q.z; v[3] = q.w;
-}
-template <> __device__ __forceinline__ void load4<bf16_t>(const bf16_t* p, float (&v)[4]) {
-  typedef __attribute__((address_space(1))) const u32x2 g_u32x2;
-  const u32x2 q = *(g_u32x2*)(p);
-  v[0] = __uint_as_float(q.x << 16); v[1] = __uint_as_float(q.x & 0xffff0000u);
-  v[2] = __uint_as_float(q.y << 16); v[3] = __uint_as_float(q.y & 0xffff0000u);
-}
-
 // ---- forward: gate / up products of every expert on every token --------------------------------------
 template <typename T>
 __global__ void __launch_bounds__((Gemm<T, DenseTiles<T>::BM, DenseTiles<T>::BN2, 2, false, true>::THREADS))
@@ -82,7 +70,7 @@ dense_gateup_kernel(const T* __restrict__ x, const T* __restrict__ w_gate, const
                     const float* __restrict__ S, T* __restrict__ G, T* __restrict__ U, T* __restrict__ Ht, int Tn,
                     int d, int f, int E) {
   typedef Gemm<T, DenseTiles<T>::BM, DenseTiles<T>::BN2, 2, false, true> GM;
-  extern __shared__ __align__(16) char smem[];
+  DSMOE_GEMM_STAGES(GM, st);
   const int n_mt = (Tn + GM::BM - 1) / GM::BM, n_nt = (f + GM::BN - 1) / GM::BN;
   const size_t EF = (size_t)E * f;
   TileWalker tw;
@@ -98,18 +86,20 @@ dense_gateup_kernel(const T* __restrict__ x, const T* __restrict__ w_gate, const
     GM::r_cols(R, base, f, f - n0, d);
     typename GM::Acc acc;
     GM::zero(acc);
-    GM::mainloop(acc, L, R, d / GM::BK, 1 << 30, smem);
-    GM::for_each_quad(acc, [&](int m, int n, const float (&v)[2][4]) {
+    GM::mainloop(acc, L, R, d / GM::BK, 1 << 30, st);
+    GM::for_each_chunk(acc, st, [&](int m, int n, const float (&v)[2][GM::CHUNK]) {
       const int t = t0 + m, col = n0 + n;
       if (t >= Tn || col >= f) return;
       const float s = S[(size_t)t * E + e];
       const size_t o = (size_t)t * EF + (size_t)e * f + col;
       if (G != nullptr) {
-        store4(G + o, v[0][0], v[0][1], v[0][2], v[0][3]);
-        store4(U + o, v[1][0], v[1][1], v[1][2], v[1][3]);
+        store_chunk(G + o, v[0]);
+        store_chunk(U + o, v[1]);
       }
-      store4(Ht + o, s * silu_f(v[0][0]) * v[1][0], s * silu_f(v[0][1]) * v[1][1], s * silu_f(v[0][2]) * v[1][2],
-             s * silu_f(v[0][3]) * v[1][3]);
+      float h[GM::CHUNK];
+#pragma unroll
+      for (int i = 0; i < GM::CHUNK; ++i) h[i] = s * silu_f(v[0][i]) * v[1][i];
+      store_chunk(Ht + o, h);
     });
   }
 }
@@ -121,11 +111,10 @@ dense_bwd_dh_kernel(const T* __restrict__ d_out, const T* __restrict__ w_down, c
                     const T* __restrict__ G, const T* __restrict__ U, T* __restrict__ dU, T* __restrict__ dG,
                     float* __restrict__ dS_part, int Tn, int d, int f, int E) {
   typedef Gemm<T, DenseTiles<T>::BM, DenseTiles<T>::BN1, 1, false, false> GM;
-  extern __shared__ __align__(16) char smem[];
+  DSMOE_GEMM_STAGES(GM, st);
   __shared__ float red[GM::WAVES_N][GM::BM];
   const int n_mt = (Tn + GM::BM - 1) / GM::BM, n_nt = (f + GM::BN - 1) / GM::BN;
   const size_t EF = (size_t)E * f;
-  const int lane = threadIdx.x & 63;
   TileWalker tw;
   tw.init(E * n_mt * n_nt);
   int idx;
@@ -138,35 +127,35 @@ dense_bwd_dh_kernel(const T* __restrict__ d_out, const T* __restrict__ w_down, c
     GM::r_rows(R, min(GM::BN, f - n0), 0, [&](int r) { return w_down + ((size_t)e * f + n0 + r) * d; });
     typename GM::Acc acc;
     GM::zero(acc);
-    GM::mainloop(acc, L, R, d / GM::BK, 1 << 30, smem);
+    GM::mainloop(acc, L, R, d / GM::BK, 1 << 30, st);
 
-    // a lane's quads of one 32-row group share the token; for_each_quad walks the row groups in order
+    // calls for one tile row come in a run; the lanes sharing the row add their partial sums at its end
     float part = 0.f;
     int cur_m = -1;
     auto flush = [&]() {
       if (cur_m < 0) return;
-      const float p = part + __shfl_xor(part, 32, 64);
-      if (lane < 32) red[GM::wave_n()][cur_m] = p;
+      const float p = GM::row_sum(part);
+      if (GM::row_leader()) red[GM::wave_n()][cur_m] = p;
     };
-    GM::for_each_quad(acc, [&](int m, int n, const float (&v)[1][4]) {
+    GM::for_each_chunk(acc, st, [&](int m, int n, const float (&v)[1][GM::CHUNK]) {
       if (m != cur_m) { flush(); cur_m = m; part = 0.f; }
       const int t = t0 + m, col = n0 + n;
       if (t >= Tn || col >= f) return;
       const float s = S[(size_t)t * E + e];
       const size_t o = (size_t)t * EF + (size_t)e * f + col;
-      float g[4], u[4], du[4], dg[4];
-      load4(G + o, g);
-      load4(U + o, u);
+      float g[GM::CHUNK], u[GM::CHUNK], du[GM::CHUNK], dg[GM::CHUNK];
+      load_chunk(G + o, g);
+      load_chunk(U + o, u);
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
+      for (int i = 0; i < GM::CHUNK; ++i) {
         const float sg = sigmoid_f(g[i]), sl = g[i] * sg;
         part = fmaf(sl * u[i], v[0][i], part);
         const float dh = s * v[0][i];
         du[i] = dh * sl;
         dg[i] = dh * u[i] * (sg * (1.f + g[i] * (1.f - sg)));
       }
-      store4(dU + o, du[0], du[1], du[2], du[3]);
-      store4(dG + o, dg[0], dg[1], dg[2], dg[3]);
+      store_chunk(dU + o, du);
+      store_chunk(dG + o, dg);
     });
     flush();
     __syncthreads();
@@ -188,7 +177,7 @@ __global__ void __launch_bounds__((Gemm<T, DenseTiles<T>::BM, DenseTiles<T>::BN1
 dense_bwd_dwdown_kernel(const T* __restrict__ Ht, const T* __restrict__ d_out, float* __restrict__ dw_down, int Tn,
                         int d, int f, int E, const void* __restrict__ zeros) {
   typedef Gemm<T, DenseTiles<T>::BM, DenseTiles<T>::BN1, 1, true, true, true> GM;
-  extern __shared__ __align__(16) char smem[];
+  DSMOE_GEMM_STAGES(GM, st);
   const int n_mt = (f + GM::BM - 1) / GM::BM, n_nt = (d + GM::BN - 1) / GM::BN;
   const size_t EF = (size_t)E * f;
   TileWalker tw;
@@ -204,10 +193,10 @@ dense_bwd_dwdown_kernel(const T* __restrict__ Ht, const T* __restrict__ d_out, f
     GM::r_cols(R, base, d, d - n0, Tn, zeros);
     typename GM::Acc acc;
     GM::zero(acc);
-    GM::mainloop(acc, L, R, (Tn + GM::BK - 1) / GM::BK, 1 << 30, smem);
-    GM::for_each_quad(acc, [&](int m, int n, const float (&v)[1][4]) {
+    GM::mainloop(acc, L, R, (Tn + GM::BK - 1) / GM::BK, 1 << 30, st);
+    GM::for_each_chunk(acc, st, [&](int m, int n, const float (&v)[1][GM::CHUNK]) {
       if (m0 + m >= f || n0 + n >= d) return;
-      store4(dw_down + ((size_t)e * f + m0 + m) * d + n0 + n, v[0][0], v[0][1], v[0][2], v[0][3]);
+      store_chunk(dw_down + ((size_t)e * f + m0 + m) * d + n0 + n, v[0]);
     });
   }
 }
@@ -219,7 +208,7 @@ dense_bwd_dwgu_kernel(const T* __restrict__ x, const T* __restrict__ dG, const T
                       float* __restrict__ dw_gate, float* __restrict__ dw_up, int Tn, int d, int f, int E,
                       const void* __restrict__ zeros) {
   typedef Gemm<T, DenseTiles<T>::BM, DenseTiles<T>::BN2, 2, true, true, true> GM;
-  extern __shared__ __align__(16) char smem[];
+  DSMOE_GEMM_STAGES(GM, st);
   const int n_mt = (d + GM::BM - 1) / GM::BM, n_nt = (f + GM::BN - 1) / GM::BN;
   const size_t EF = (size_t)E * f;
   TileWalker tw;
@@ -235,12 +224,12 @@ dense_bwd_dwgu_kernel(const T* __restrict__ x, const T* __restrict__ dG, const T
     GM::r_cols(R, base, EF, f - n0, Tn, zeros);
     typename GM::Acc acc;
     GM::zero(acc);
-    GM::mainloop(acc, L, R, (Tn + GM::BK - 1) / GM::BK, 1 << 30, smem);
-    GM::for_each_quad(acc, [&](int m, int n, const float (&v)[2][4]) {
+    GM::mainloop(acc, L, R, (Tn + GM::BK - 1) / GM::BK, 1 << 30, st);
+    GM::for_each_chunk(acc, st, [&](int m, int n, const float (&v)[2][GM::CHUNK]) {
       if (m0 + m >= d || n0 + n >= f) return;
       const size_t o = ((size_t)e * d + m0 + m) * f + n0 + n;
-      store4(dw_gate + o, v[0][0], v[0][1], v[0][2], v[0][3]);
-      store4(dw_up + o, v[1][0], v[1][1], v[1][2], v[1][3]);
+      store_chunk(dw_gate + o, v[0]);
+      store_chunk(dw_up + o, v[1]);
     });
   }
 }
@@ -252,7 +241,7 @@ dense_bwd_dx_kernel(const T* __restrict__ dU, const T* __restrict__ dG, const T*
                     const T* __restrict__ w_gate, const float* __restrict__ dZ, const T* __restrict__ w_r,
                     T* __restrict__ dx, int Tn, int d, int f, int E) {
   typedef Gemm<T, DenseTiles<T>::BM, DenseTiles<T>::BN1, 1, false, false> GM;
-  extern __shared__ __align__(16) char smem[];
+  DSMOE_GEMM_STAGES(GM, st);
   const int n_mt = (Tn + GM::BM - 1) / GM::BM, n_nt = (d + GM::BN - 1) / GM::BN;
   const size_t EF = (size_t)E * f;
   TileWalker tw;
@@ -272,19 +261,21 @@ dense_bwd_dx_kernel(const T* __restrict__ dU, const T* __restrict__ dG, const T*
       GM::l_rows(L, min(GM::BM, Tn - t0), (size_t)f * sizeof(T), [&](int r) { return a + (size_t)(t0 + r) * EF; });
       typename GM::RSrc R;
       GM::r_rows(R, min(GM::BN, d - n0), (size_t)d * f * sizeof(T), [&](int r) { return w + (size_t)(n0 + r) * f; });
-      GM::mainloop(acc, L, R, (int)(EF / GM::BK), f / GM::BK, smem);
+      GM::mainloop(acc, L, R, (int)(EF / GM::BK), f / GM::BK, st);
     }
-    GM::for_each_quad(acc, [&](int m, int n, const float (&v)[1][4]) {
+    GM::for_each_chunk(acc, st, [&](int m, int n, const float (&v)[1][GM::CHUNK]) {
       const int t = t0 + m, col = n0 + n;
       if (t >= Tn || col >= d) return;
-      float o[4] = {v[0][0], v[0][1], v[0][2], v[0][3]};
+      float o[GM::CHUNK];
+#pragma unroll
+      for (int i = 0; i < GM::CHUNK; ++i) o[i] = v[0][i];
       const float* z = dZ + (size_t)t * E;
       for (int e = 0; e < E; ++e) {
         const float ze = z[e];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) o[i] = fmaf(ze, to_f32(w_r[(size_t)(col + i) * E + e]), o[i]);
+        for (int i = 0; i < GM::CHUNK; ++i) o[i] = fmaf(ze, to_f32(w_r[(size_t)(col + i) * E + e]), o[i]);
       }
-      store4(dx + (size_t)t * d + col, o[0], o[1], o[2], o[3]);
+      store_chunk(dx + (size_t)t * d + col, o);
     });
   }
 }

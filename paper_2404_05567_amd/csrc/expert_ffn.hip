@@ -9,7 +9,7 @@
 // through row_token while staging the L operand (no permuted copy of X is required).
 #include <algorithm>
 
-#include "gemm_dma.h"
+#include "gemm.h"
 
 namespace dsmoe {
 
@@ -139,6 +139,7 @@ gateup_bf16_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ x_pe
                    const bf16_t* __restrict__ w_up, bf16_t* __restrict__ h, int d, int f, int E) {
   constexpr int BNS = 128;                         // columns per source (gate, up) and block
   typedef Tile3<BM, 2 * BNS, 2> TL;
+  DSMOE_TILE3_STAGES(TL, st);
   __shared__ GroupTiles gt;
   build_group_tiles(gt, expert_off, E, BM);
   const int n_tiles = (f + BNS - 1) / BNS;
@@ -161,23 +162,14 @@ gateup_bf16_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ x_pe
     R.init(base, f, min(BNS, f - n0), d);
     typename TL::Acc acc;
     TL::zero(acc);
-    TL::mainloop(acc, L, R, d / TL::BK, 1 << 30, nullptr);
-
+    TL::mainloop(acc, L, R, d / TL::BK, 1 << 30, st);
+    TL::for_each_chunk(acc, st, [&](int m, int n, const float (&v)[2][TL::CHUNK]) {
+      if (m >= valid || n0 + n >= f) return;
+      float o[TL::CHUNK];
 #pragma unroll
-    for (int mt = 0; mt < TL::MT; ++mt) {
-      const int m = TL::acc_m(mt);
-      if (m >= valid) continue;
-      bf16_t* hrow = h + (size_t)(row0 + m) * f;
-#pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        const int n = n0 + TL::acc_n(0, g);   // column tile 0 holds gate, tile 1 the same columns of up
-        if (n >= f) continue;
-        const f32x16& G = acc[0][mt];
-        const f32x16& U = acc[1][mt];
-        store4(hrow + n, silu_f(G[4 * g]) * U[4 * g], silu_f(G[4 * g + 1]) * U[4 * g + 1],
-               silu_f(G[4 * g + 2]) * U[4 * g + 2], silu_f(G[4 * g + 3]) * U[4 * g + 3]);
-      }
-    }
+      for (int i = 0; i < TL::CHUNK; ++i) o[i] = silu_f(v[0][i]) * v[1][i];
+      store_chunk(h + (size_t)(row0 + m) * f + n0 + n, o);
+    });
   }
 }
 
@@ -187,6 +179,7 @@ down_bf16_kernel(const bf16_t* __restrict__ h, const int32_t* __restrict__ exper
                  const bf16_t* __restrict__ w_down, bf16_t* __restrict__ y, int d, int f, int E, int uniform_rows) {
   constexpr int BN = 256;
   typedef Tile3<BM, BN> TL;
+  DSMOE_TILE3_STAGES(TL, st);
   __shared__ GroupTiles gt;
   build_group_tiles(gt, expert_off, E, BM, uniform_rows);
   const int n_tiles = (d + BN - 1) / BN;
@@ -207,23 +200,11 @@ down_bf16_kernel(const bf16_t* __restrict__ h, const int32_t* __restrict__ exper
     R.init(base, d, min(BN, d - n0), f);
     typename TL::Acc acc;
     TL::zero(acc);
-    TL::mainloop(acc, L, R, f / TL::BK, 1 << 30, nullptr);
-
-#pragma unroll
-    for (int mt = 0; mt < TL::MT; ++mt) {
-      const int m = TL::acc_m(mt);
-      if (m >= valid) continue;
-      bf16_t* yrow = y + (size_t)(row0 + m) * d;
-#pragma unroll
-      for (int nt = 0; nt < TL::NT; ++nt)
-#pragma unroll
-        for (int g = 0; g < 4; ++g) {
-          const int n = n0 + TL::acc_n(nt, g);
-          if (n >= d) continue;
-          const f32x16& A = acc[nt][mt];
-          store4(yrow + n, A[4 * g], A[4 * g + 1], A[4 * g + 2], A[4 * g + 3]);
-        }
-    }
+    TL::mainloop(acc, L, R, f / TL::BK, 1 << 30, st);
+    TL::for_each_chunk(acc, st, [&](int m, int n, const float (&v)[1][TL::CHUNK]) {
+      if (m >= valid || n0 + n >= d) return;
+      store_chunk(y + (size_t)(row0 + m) * d + n0 + n, v[0]);
+    });
   }
 }
 

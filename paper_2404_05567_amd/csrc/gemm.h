@@ -55,6 +55,54 @@ __device__ __forceinline__ void init_cols(SrcCols<T, ROWS>& s, const T* base, si
 template <typename T, int BM_, int BN_, int NSRC_, bool LK, bool RK, bool KTAIL = false>
 struct Gemm;
 
+// LDS of a kernel built on Gemm<...> GM: static stage arrays (bf16 core) or the dynamic buffer (fp32 core)
+#define DSMOE_GEMM_STAGES(GM, st)                                                                            \
+  extern __shared__ __align__(16) char dsmoe_dyn_smem[];                                                     \
+  __shared__ __align__(1024) char st##L0[GM::ST_L], st##L1[GM::ST_L], st##L2[GM::ST_L], st##L3[GM::ST_L];     \
+  __shared__ __align__(1024) char st##R0[GM::ST_R], st##R1[GM::ST_R], st##R2[GM::ST_R], st##R3[GM::ST_R];     \
+  typename GM::Stages st =                                                                                   \
+      GM::make_stages(st##L0, st##L1, st##L2, st##L3, st##R0, st##R1, st##R2, st##R3, dsmoe_dyn_smem)
+
+// W consecutive values to / from memory (W = 4 or 8)
+template <int W>
+__device__ __forceinline__ void store_chunk(float* p, const float (&v)[W]) {
+#pragma unroll
+  for (int i = 0; i < W; i += 4) store4(p + i, v[i], v[i + 1], v[i + 2], v[i + 3]);
+}
+template <int W>
+__device__ __forceinline__ void store_chunk(bf16_t* p, const float (&v)[W]) {
+  if constexpr (W == 8) {
+    const u32x4 o = {pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]), pack_bf16x2(v[4], v[5]), pack_bf16x2(v[6], v[7])};
+    stg16(p, o);
+  } else {
+    store4(p, v[0], v[1], v[2], v[3]);
+  }
+}
+template <int W>
+__device__ __forceinline__ void load_chunk(const float* p, float (&v)[W]) {
+#pragma unroll
+  for (int i = 0; i < W; i += 4) {
+    const f32x4 q = __builtin_bit_cast(f32x4, ldg16(p + i));
+    v[i] = q.x; v[i + 1] = q.y; v[i + 2] = q.z; v[i + 3] = q.w;
+  }
+}
+template <int W>
+__device__ __forceinline__ void load_chunk(const bf16_t* p, float (&v)[W]) {
+  if constexpr (W == 8) {
+    const u32x4 q = ldg16(p);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      v[2 * i] = __uint_as_float(q[i] << 16);
+      v[2 * i + 1] = __uint_as_float(q[i] & 0xffff0000u);
+    }
+  } else {
+    typedef __attribute__((address_space(1))) const u32x2 g_u32x2;
+    const u32x2 q = *(g_u32x2*)(p);
+    v[0] = __uint_as_float(q.x << 16); v[1] = __uint_as_float(q.x & 0xffff0000u);
+    v[2] = __uint_as_float(q.y << 16); v[3] = __uint_as_float(q.y & 0xffff0000u);
+  }
+}
+
 // ---- fp32 ----------------------------------------------------------------------------------------
 template <int BM_, int BN_, int NSRC_, bool LK, bool RK, bool KTAIL>
 struct Gemm<float, BM_, BN_, NSRC_, LK, RK, KTAIL> {
@@ -66,6 +114,12 @@ struct Gemm<float, BM_, BN_, NSRC_, LK, RK, KTAIL> {
   typedef std::conditional_t<RK, SrcCols<float, BN>, SrcRows<float, BN>> RSrc1;
   struct RSrc { RSrc1 s[NSRC]; };
   typedef typename TL::Acc Acc;
+  struct Stages { char* smem; };
+  static constexpr int ST_L = 16, ST_R = 16, CHUNK = 4;   // stages live in dynamic LDS; 4 columns per lane
+  static __device__ __forceinline__ Stages make_stages(char*, char*, char*, char*, char*, char*, char*, char*,
+                                                       char* dyn) {
+    return Stages{dyn};
+  }
 
   template <class F>
   static __device__ __forceinline__ void l_rows(LSrc& s, int valid, size_t seg_stride_bytes, F row_base) {
@@ -87,13 +141,13 @@ struct Gemm<float, BM_, BN_, NSRC_, LK, RK, KTAIL> {
   }
   static __device__ __forceinline__ void zero(Acc& acc) { TL::zero(acc); }
   static __device__ __forceinline__ void mainloop(Acc& acc, const LSrc& L, const RSrc& R, int nkt, int seg_tiles,
-                                                  char* smem) {
-    TL::mainloop(acc, L, R.s, nkt, seg_tiles, smem);
+                                                  const Stages& st) {
+    TL::mainloop(acc, L, R.s, nkt, seg_tiles, st.smem);
     __syncthreads();   // the tile may be restaged (or LDS reused) right after
   }
-  // f(m, n, v): row m of the tile, first of 4 consecutive columns n (inside a source), v[s][0..3]
+  // f(m, n, v): row m of the tile, first of CHUNK consecutive columns n (inside a source), v[s][0..CHUNK)
   template <class F>
-  static __device__ __forceinline__ void for_each_quad(const Acc& acc, F f) {
+  static __device__ __forceinline__ void for_each_chunk(const Acc& acc, const Stages&, F f) {
 #pragma unroll
     for (int mt = 0; mt < TL::MT; ++mt)
 #pragma unroll
@@ -109,6 +163,9 @@ struct Gemm<float, BM_, BN_, NSRC_, LK, RK, KTAIL> {
         }
   }
   static __device__ __forceinline__ int wave_n() { return threadIdx.x >> 7; }
+  // sum of p over the lanes that hold the same tile row in one for_each_chunk call; row_leader() is true on one of them
+  static __device__ __forceinline__ float row_sum(float p) { return p + __shfl_xor(p, 32, 64); }
+  static __device__ __forceinline__ bool row_leader() { return (threadIdx.x & 63) < 32; }
 };
 
 // ---- bf16 ----------------------------------------------------------------------------------------
@@ -121,6 +178,15 @@ struct Gemm<bf16_t, BM_, BN_, NSRC_, LK, RK, KTAIL> {
   typedef typename TL::LSrc LSrc;
   typedef typename TL::RSrc RSrc;
   typedef typename TL::Acc Acc;
+  typedef Stages3 Stages;
+  static constexpr int ST_L = TL::LDS_L, ST_R = TL::LDS_R, CHUNK = TL::CHUNK;
+  static __device__ __forceinline__ Stages make_stages(char* l0, char* l1, char* l2, char* l3, char* r0, char* r1,
+                                                       char* r2, char* r3, char*) {
+    Stages s;
+    s.l[0] = (lds_char*)l0; s.l[1] = (lds_char*)l1; s.l[2] = (lds_char*)l2; s.l[3] = (lds_char*)l3;
+    s.r[0] = (lds_char*)r0; s.r[1] = (lds_char*)r1; s.r[2] = (lds_char*)r2; s.r[3] = (lds_char*)r3;
+    return s;
+  }
 
   template <class F>
   static __device__ __forceinline__ void l_rows(LSrc& s, int valid, size_t seg_stride_bytes, F row_base) {
@@ -142,26 +208,21 @@ struct Gemm<bf16_t, BM_, BN_, NSRC_, LK, RK, KTAIL> {
   }
   static __device__ __forceinline__ void zero(Acc& acc) { TL::zero(acc); }
   static __device__ __forceinline__ void mainloop(Acc& acc, const LSrc& L, const RSrc& R, int nkt, int seg_tiles,
-                                                  char* smem) {
-    TL::mainloop(acc, L, R, nkt, seg_tiles, smem);
+                                                  const Stages& st) {
+    TL::mainloop(acc, L, R, nkt, seg_tiles, st);
   }
   template <class F>
-  static __device__ __forceinline__ void for_each_quad(const Acc& acc, F f) {
-#pragma unroll
-    for (int mt = 0; mt < TL::MT; ++mt)
-#pragma unroll
-      for (int nt = 0; nt < (NSRC == 1 ? TL::NT : 1); ++nt)
-#pragma unroll
-        for (int g = 0; g < 4; ++g) {
-          float v[NSRC][4];
-#pragma unroll
-          for (int b = 0; b < NSRC; ++b)
-#pragma unroll
-            for (int i = 0; i < 4; ++i) v[b][i] = acc[NSRC == 1 ? nt : b][mt][4 * g + i];
-          f(TL::acc_m(mt), TL::acc_n(nt, g), v);
-        }
+  static __device__ __forceinline__ void for_each_chunk(const Acc& acc, const Stages& st, F f) {
+    TL::for_each_chunk(acc, st, f);
   }
   static __device__ __forceinline__ int wave_n() { return (threadIdx.x >> 6) % 4; }
+  static __device__ __forceinline__ float row_sum(float p) {
+    constexpr int OPR = NSRC == 1 ? 8 : 4;
+#pragma unroll
+    for (int o = 1; o < OPR; o <<= 1) p += __shfl_xor(p, o, 64);
+    return p;
+  }
+  static __device__ __forceinline__ bool row_leader() { return (threadIdx.x & (NSRC == 1 ? 7 : 3)) == 0; }
 };
 
 }  // namespace dsmoe

@@ -32,9 +32,16 @@ constexpr int kStages3 = 4;
 
 typedef __attribute__((address_space(1))) const void gvoid_t;
 typedef __attribute__((address_space(3))) void lvoid_t;
+typedef __attribute__((address_space(3))) char lds_char;           // LDS pointers stay typed as such
+typedef __attribute__((address_space(3))) u32x4 lds_u32x4;
+typedef __attribute__((address_space(3))) f32x4 lds_f32x4;
 
-__device__ __forceinline__ void dma16(const char* g, char* lds) {
+__device__ __forceinline__ void dma16(const char* g, lds_char* lds) {
   __builtin_amdgcn_global_load_lds((gvoid_t*)g, (lvoid_t*)lds, 16, 0, 0);
+}
+__device__ __forceinline__ u32x2 lds_read_tr16(const lds_char* p) {
+  const s16x4 v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p));
+  return __builtin_bit_cast(u32x2, v);
 }
 // s_waitcnt on the vector-memory counter alone (N outstanding loads allowed), optionally also on all LDS reads
 template <int N, bool LGKM0>
@@ -64,9 +71,9 @@ struct DRows {
       p[i] = reinterpret_cast<const char*>(row_base(min(r, valid - 1))) + kc * 16;
     }
   }
-  __device__ __forceinline__ void issue(char* stage, int seg, int kin) const {
+  __device__ __forceinline__ void issue(lds_char* stage, int seg, int kin) const {
     const size_t off = (size_t)seg * seg_stride + (size_t)kin * 64;
-    char* dst = stage + (threadIdx.x >> 6) * (CPW * 1024);
+    lds_char* dst = stage + (threadIdx.x >> 6) * (CPW * 1024);
 #pragma unroll
     for (int i = 0; i < CPW; ++i) dma16(p[i] + off, dst + i * 1024);
   }
@@ -75,8 +82,8 @@ struct DRows {
     const int lane = threadIdx.x & 63;
     return (first + (lane & 31)) * 64 + (((2 * ks + (lane >> 5)) ^ ((lane >> 2) & 3)) * 16);
   }
-  static __device__ __forceinline__ u32x4 read(const char* tile, int off, int group) {
-    return *reinterpret_cast<const u32x4*>(tile + off + group * (32 * 64));
+  static __device__ __forceinline__ u32x4 read(const lds_char* tile, int off, int group) {
+    return *reinterpret_cast<const lds_u32x4*>(tile + off + group * (32 * 64));
   }
 };
 
@@ -116,9 +123,9 @@ struct DCols {
       p[i] = reinterpret_cast<const char*>(base[src] + (size_t)k * ld_elems + (cs < cols_valid ? cs : 0));
     }
   }
-  __device__ __forceinline__ void issue(char* stage, int seg, int kin) const {
+  __device__ __forceinline__ void issue(lds_char* stage, int seg, int kin) const {
     const size_t off = (size_t)seg * seg_stride + (size_t)kin * step_bytes;
-    char* dst = stage + (threadIdx.x >> 6) * (CPW * 1024);
+    lds_char* dst = stage + (threadIdx.x >> 6) * (CPW * 1024);
 #pragma unroll
     for (int i = 0; i < CPW; ++i) {
       const char* g = p[i] + off;
@@ -135,12 +142,24 @@ struct DCols {
     return (16 * ks + 8 * (lane >> 5) + (i >> 2)) * RB + (((first >> 5) ^ (i >> 2)) * 64) + 32 * ((lane >> 4) & 1) +
            8 * (i & 3);
   }
-  static __device__ __forceinline__ u32x4 read(const char* tile, int off) {
+  static __device__ __forceinline__ u32x4 read(const lds_char* tile, int off) {
     const u32x2 lo = lds_read_tr16(tile + off);
     const u32x2 hi = lds_read_tr16(tile + off + 4 * RB);
     return u32x4{lo.x, lo.y, hi.x, hi.y};
   }
 };
+
+// The LDS stages of a kernel: separate __shared__ arrays (so that the compiler can tell the stages apart),
+// declared once per kernel with DSMOE_TILE3_STAGES and handed to the main loop and the epilogue.
+struct Stages3 { lds_char* l[kStages3]; lds_char* r[kStages3]; };
+#define DSMOE_TILE3_STAGES(TL, st)                                                                         \
+  __shared__ __align__(1024) char st##L0[TL::LDS_L], st##L1[TL::LDS_L], st##L2[TL::LDS_L], st##L3[TL::LDS_L]; \
+  __shared__ __align__(1024) char st##R0[TL::LDS_R], st##R1[TL::LDS_R], st##R2[TL::LDS_R], st##R3[TL::LDS_R]; \
+  dsmoe::Stages3 st;                                                                                       \
+  st.l[0] = (dsmoe::lds_char*)st##L0; st.l[1] = (dsmoe::lds_char*)st##L1;                                  \
+  st.l[2] = (dsmoe::lds_char*)st##L2; st.l[3] = (dsmoe::lds_char*)st##L3;                                  \
+  st.r[0] = (dsmoe::lds_char*)st##R0; st.r[1] = (dsmoe::lds_char*)st##R1;                                  \
+  st.r[2] = (dsmoe::lds_char*)st##R2; st.r[3] = (dsmoe::lds_char*)st##R3
 
 // NSRC = 2: the wave's two column tiles are the same 32 columns of source 0 (gate) and source 1 (up).
 template <int BM_, int BN_, int NSRC_ = 1, bool L_KMAJOR = false, bool R_KMAJOR = true, bool KTAIL = false>
@@ -153,7 +172,7 @@ struct Tile3 {
   typedef std::conditional_t<L_KMAJOR, DCols<BM, 1, KTAIL>, DRows<BM>> LSrc;
   typedef std::conditional_t<R_KMAJOR, DCols<BN, NSRC, KTAIL>, DRows<BN>> RSrc;
   static constexpr int LDS_L = LSrc::LDS, LDS_R = RSrc::LDS;
-  static constexpr int LDS_BYTES = 0;                                   // stages are static arrays
+  static constexpr int LDS_BYTES = 0;                                   // stages are static arrays of the kernel
   static constexpr int NI = LSrc::NI + RSrc::NI;                        // loads per wave and K step
   static constexpr int WCOL = NSRC == 1 ? WN : 32, NT_COLS = NSRC == 1 ? 32 : BN / NSRC;
   static constexpr int NFR = (L_KMAJOR ? 2 : 1) * MT + (R_KMAJOR ? 2 : 1) * NT;   // LDS reads per K slice
@@ -189,7 +208,8 @@ struct Tile3 {
       }
     }
   }
-  static __device__ __forceinline__ void read_frags(Frag& f, const char* sl, const char* sr, const Offs& o, int ks) {
+  static __device__ __forceinline__ void read_frags(Frag& f, const lds_char* sl, const lds_char* sr, const Offs& o,
+                                                    int ks) {
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
       if constexpr (L_KMAJOR) f.x[mt] = LSrc::read(sl, o.l[ks][mt]);
@@ -213,45 +233,43 @@ struct Tile3 {
   // acc += L * R over nkt K steps; K may be split in segments of seg_tiles steps (see the sources).
   // Must be called by all 512 threads; returns with none of this wave's loads in flight.
   static __device__ __forceinline__ void mainloop(Acc& acc, const LSrc& L, const RSrc& R, int nkt, int seg_tiles,
-                                                  char* /*unused: stages are static*/) {
-    __shared__ __align__(1024) char sL0[LDS_L], sL1[LDS_L], sL2[LDS_L], sL3[LDS_L];
-    __shared__ __align__(1024) char sR0[LDS_R], sR1[LDS_R], sR2[LDS_R], sR3[LDS_R];
+                                                  const Stages3& st) {
     Offs o;
     offsets(o);
     int seg = 0, kin = 0, next = 0;   // position of the next K step to load
     // Loads are issued unconditionally (steps past the end re-read the last one, into a stage nobody reads
     // any more): the loop body stays free of branches and the number of loads in flight is a constant.
-    auto issue_next = [&](char* sl, char* sr) {
+    auto issue_next = [&](lds_char* sl, lds_char* sr) {
       L.issue(sl, seg, kin);
       R.issue(sr, seg, kin);
       if (++next < nkt && ++kin == seg_tiles) { kin = 0; ++seg; }
     };
-    issue_next(sL0, sR0);
-    issue_next(sL1, sR1);
-    issue_next(sL2, sR2);
-    issue_next(sL3, sR3);
+    issue_next(st.l[0], st.r[0]);
+    issue_next(st.l[1], st.r[1]);
+    issue_next(st.l[2], st.r[2]);
+    issue_next(st.l[3], st.r[3]);
     Frag fa, fb;
     __builtin_amdgcn_sched_barrier(0);
     wait_vm<3 * NI, true>();          // step 0 has landed
     __builtin_amdgcn_s_barrier();
     __builtin_amdgcn_sched_barrier(0);
-    read_frags(fa, sL0, sR0, o, 0);
+    read_frags(fa, st.l[0], st.r[0], o, 0);
 
     // One K step on stage ST: slice 0 multiplies while slice 1 is read; then, once step + 1 has landed for
     // every wave (and every wave has read this stage to the end), the stage is refilled with step + 4 and
     // slice 0 of the next stage is read while slice 1 multiplies.
 #define DSMOE_STEP3(ST, NX)                                                   \
   {                                                                           \
-    read_frags(fb, sL##ST, sR##ST, o, 1);                                     \
+    read_frags(fb, st.l[ST], st.r[ST], o, 1);                                   \
     mma(acc, fa);                                                             \
     interleave();                                                             \
     __builtin_amdgcn_sched_barrier(0);                                        \
     wait_vm<2 * NI, true>();                                                  \
     __builtin_amdgcn_s_barrier();                                             \
     __builtin_amdgcn_sched_barrier(0);                                        \
-    issue_next(sL##ST, sR##ST);                                               \
+    issue_next(st.l[ST], st.r[ST]);                                             \
     __builtin_amdgcn_sched_barrier(0);                                        \
-    read_frags(fa, sL##NX, sR##NX, o, 0);                                     \
+    read_frags(fa, st.l[NX], st.r[NX], o, 0);                                   \
     mma(acc, fb);                                                             \
     interleave();                                                             \
   }
@@ -274,6 +292,63 @@ struct Tile3 {
     __builtin_amdgcn_sched_barrier(0);
     wait_vm<0, true>();
     __builtin_amdgcn_sched_barrier(0);
+  }
+
+  // Transposed walk over the accumulators.  The MFMA leaves a lane with one row and 4 consecutive columns
+  // per register quad, which makes 8-byte accesses spread over 32 rows.  Here every 32-row block of the
+  // wave goes through the wave's own slice of the weight-side stages (fp32, XOR-swizzled 16-byte units, no
+  // barrier needed: no other wave writes there once this wave's loads have drained), and comes back with
+  // a lane owning 8 consecutive columns of one row: f(m, n, v) gets the tile row m, the first column n
+  // (inside its source) and v[s][0..7]; 8 (NSRC = 1) or 4 (NSRC = 2) neighbouring lanes cover a row, so
+  // global accesses made from f are whole 128-byte (bf16: 64..128-byte) row segments.
+  static constexpr int CHUNK = 8;
+  template <class F>
+  static __device__ __forceinline__ void for_each_chunk(const Acc& acc, const Stages3& st, F f) {
+    static_assert(RSrc::LDS / 8 >= 2048, "the wave's slice of a weight-side stage holds 8 rows of 64 floats");
+    constexpr int OPR = NSRC == 1 ? 8 : 4;        // lanes (column octets) per row and source
+    constexpr int RPI = 64 / OPR;                  // rows covered by one read instruction
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int wslice = wave * (RSrc::LDS / 8);
+    const int m = lane & 31, kg = lane >> 5;
+    // the stage addresses are link-time constants: keep them as values (a table in memory would be indexed)
+    lds_char* const r0 = st.r[0];
+    lds_char* const r1 = st.r[1];
+    lds_char* const r2 = st.r[2];
+    lds_char* const r3 = st.r[3];
+    auto area = [=](int row) -> lds_char* {        // 8 rows of 256 bytes in each of the four stages
+      const int piece = row >> 3;
+      lds_char* const lo = (piece & 1) ? r1 : r0;
+      lds_char* const hi = (piece & 1) ? r3 : r2;
+      return ((piece & 2) ? hi : lo) + wslice + (row & 7) * 256;
+    };
+    lds_char* wrow = area(m);
+    const int q = lane % OPR;
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const int u = nt * 8 + g * 2 + kg;
+          f32x4 v = {acc[nt][mt][4 * g], acc[nt][mt][4 * g + 1], acc[nt][mt][4 * g + 2], acc[nt][mt][4 * g + 3]};
+          *reinterpret_cast<lds_f32x4*>(wrow + ((u ^ (m & 15)) * 16)) = v;
+        }
+#pragma unroll
+      for (int j = 0; j < 32 / RPI; ++j) {
+        const int r = RPI * j + lane / OPR;
+        const lds_char* rrow = area(r);
+        float v[NSRC][8];
+#pragma unroll
+        for (int s = 0; s < NSRC; ++s) {
+          const int ub = s * 8 + 2 * q;
+          const f32x4 a = *reinterpret_cast<const lds_f32x4*>(rrow + ((ub ^ (r & 15)) * 16));
+          const f32x4 b = *reinterpret_cast<const lds_f32x4*>(rrow + (((ub + 1) ^ (r & 15)) * 16));
+          v[s][0] = a.x; v[s][1] = a.y; v[s][2] = a.z; v[s][3] = a.w;
+          v[s][4] = b.x; v[s][5] = b.y; v[s][6] = b.z; v[s][7] = b.w;
+        }
+        f((wave / WGN) * WM + mt * 32 + r, (wave % WGN) * WCOL + 8 * q, v);
+      }
+    }
   }
 
   static __device__ __forceinline__ int acc_m(int mt) {
