@@ -11,7 +11,8 @@
 //              dW_down[j] = Ht_j^T dO                                               (kernel dense_bwd_dwdown)
 //              dW_gate[j] = X^T dG_j, dW_up[j] = X^T dU_j                           (kernel dense_bwd_dwgu)
 //              dZ = S (dS - sum_k S_k dS_k)   (softmax), dW_r = X^T dZ, db_r = sum_t dZ
-//              dX = sum_j dU_j W_up[j]^T + dG_j W_gate[j]^T + dZ W_r^T              (kernel dense_bwd_dx)
+//              dX = sum_j dU_j W_up[j]^T + dG_j W_gate[j]^T + dZ W_r^T              (kernel dense_bwd_dx; the
+//                   router term is one more K segment of the same contraction, with dZ in the storage type)
 // All reductions have a fixed order: results are bitwise reproducible.
 #include <algorithm>
 
@@ -40,9 +41,9 @@ SavedLayout saved_layout(const dsmoe_ctx* c, int T) {
   return l;
 }
 
-constexpr int kWrTokens = 512;   // tokens per block of the router weight-gradient kernel
+constexpr int kWrTokens = 256;   // tokens per slab of the router weight-gradient kernel
 
-struct ScratchLayout { size_t zeros, dU, dG, dS_part, dZ, dWr_part, dbr_part, total; int ntb, nsplit; };
+struct ScratchLayout { size_t zeros, dU, dG, dS_part, dZ, dZt, WrP, dWr_part, total; int ntb, nsplit, EP; };
 ScratchLayout scratch_layout(const dsmoe_ctx* c, int T) {
   const size_t E = c->desc.n_experts, n = (size_t)T * E, nf = n * c->desc.d_ff * c->esize;
   const int bn1 = c->desc.dtype == DSMOE_BF16 ? DenseTiles<bf16_t>::BN1 : DenseTiles<float>::BN1;
@@ -55,8 +56,10 @@ ScratchLayout scratch_layout(const dsmoe_ctx* c, int T) {
   l.dG = o; o = al256(o + nf);
   l.dS_part = o; o = al256(o + n * l.ntb * 4);
   l.dZ = o; o = al256(o + n * 4);
+  l.EP = (c->desc.n_experts + 31) / 32 * 32;   // the router term of dX runs through the MFMA core: K padded to 32
+  l.dZt = o; o = al256(o + (size_t)T * l.EP * c->esize);
+  l.WrP = o; o = al256(o + (size_t)c->desc.d_model * l.EP * c->esize);
   l.dWr_part = o; o = al256(o + (size_t)l.nsplit * c->desc.d_model * E * 4);
-  l.dbr_part = o; o = al256(o + (size_t)l.nsplit * E * 4);
   l.total = o;
   return l;
 }
@@ -87,20 +90,48 @@ dense_gateup_kernel(const T* __restrict__ x, const T* __restrict__ w_gate, const
     typename GM::Acc acc;
     GM::zero(acc);
     GM::mainloop(acc, L, R, d / GM::BK, 1 << 30, st);
-    GM::for_each_chunk(acc, st, [&](int m, int n, const float (&v)[2][GM::CHUNK]) {
-      const int t = t0 + m, col = n0 + n;
-      if (t >= Tn || col >= f) return;
-      const float s = S[(size_t)t * E + e];
-      const size_t o = (size_t)t * EF + (size_t)e * f + col;
-      if (G != nullptr) {
-        store_chunk(G + o, v[0]);
-        store_chunk(U + o, v[1]);
-      }
-      float h[GM::CHUNK];
+    if constexpr (std::is_same<T, bf16_t>::value) {
+      // bf16: the three outputs are formed in the accumulator layout and cross the LDS already rounded
+      auto pre = [&](int m, int, const float (&v)[2][4], auto& out) {
+        const float s = t0 + m < Tn ? S[(size_t)(t0 + m) * E + e] : 0.f;
+        constexpr int NO = sizeof(out) / sizeof(out[0]);
 #pragma unroll
-      for (int i = 0; i < GM::CHUNK; ++i) h[i] = s * silu_f(v[0][i]) * v[1][i];
-      store_chunk(Ht + o, h);
-    });
+        for (int i = 0; i < 4; ++i) {
+          out[NO - 1][i] = s * silu_f(v[0][i]) * v[1][i];
+          if constexpr (NO == 3) { out[0][i] = v[0][i]; out[1][i] = v[1][i]; }
+        }
+      };
+      if (G != nullptr)
+        GM::TL::template for_each_chunk_bf16<3>(acc, st, pre, [&](int m, int n, const u32x4 (&p)[3]) {
+          const int t = t0 + m, col = n0 + n;
+          if (t >= Tn || col >= f) return;
+          const size_t o = (size_t)t * EF + (size_t)e * f + col;
+          stg16(G + o, p[0]);
+          stg16(U + o, p[1]);
+          stg16(Ht + o, p[2]);
+        });
+      else
+        GM::TL::template for_each_chunk_bf16<1>(acc, st, pre, [&](int m, int n, const u32x4 (&p)[1]) {
+          const int t = t0 + m, col = n0 + n;
+          if (t >= Tn || col >= f) return;
+          stg16(Ht + (size_t)t * EF + (size_t)e * f + col, p[0]);
+        });
+    } else {
+      GM::for_each_chunk(acc, st, [&](int m, int n, const float (&v)[2][GM::CHUNK]) {
+        const int t = t0 + m, col = n0 + n;
+        if (t >= Tn || col >= f) return;
+        const float s = S[(size_t)t * E + e];
+        const size_t o = (size_t)t * EF + (size_t)e * f + col;
+        if (G != nullptr) {
+          store_chunk(G + o, v[0]);
+          store_chunk(U + o, v[1]);
+        }
+        float h[GM::CHUNK];
+#pragma unroll
+        for (int i = 0; i < GM::CHUNK; ++i) h[i] = s * silu_f(v[0][i]) * v[1][i];
+        store_chunk(Ht + o, h);
+      });
+    }
   }
 }
 
@@ -238,8 +269,8 @@ dense_bwd_dwgu_kernel(const T* __restrict__ x, const T* __restrict__ dG, const T
 template <typename T>
 __global__ void __launch_bounds__((Gemm<T, DenseTiles<T>::BM, DenseTiles<T>::BN1, 1, false, false>::THREADS))
 dense_bwd_dx_kernel(const T* __restrict__ dU, const T* __restrict__ dG, const T* __restrict__ w_up,
-                    const T* __restrict__ w_gate, const float* __restrict__ dZ, const T* __restrict__ w_r,
-                    T* __restrict__ dx, int Tn, int d, int f, int E) {
+                    const T* __restrict__ w_gate, const T* __restrict__ dZt, const T* __restrict__ w_rp,
+                    T* __restrict__ dx, int Tn, int d, int f, int E, int EP) {
   typedef Gemm<T, DenseTiles<T>::BM, DenseTiles<T>::BN1, 1, false, false> GM;
   DSMOE_GEMM_STAGES(GM, st);
   const int n_mt = (Tn + GM::BM - 1) / GM::BM, n_nt = (d + GM::BN - 1) / GM::BN;
@@ -253,37 +284,36 @@ dense_bwd_dx_kernel(const T* __restrict__ dU, const T* __restrict__ dG, const T*
     typename GM::Acc acc;
     GM::zero(acc);
 #pragma unroll 1
-    for (int half = 0; half < 2; ++half) {
-      const T* a = half ? dG : dU;
-      const T* w = half ? w_gate : w_up;
-      // K runs over (expert, hidden unit): one segment of f per expert on both sides
+    for (int part = 0; part < 3; ++part) {
       typename GM::LSrc L;
-      GM::l_rows(L, min(GM::BM, Tn - t0), (size_t)f * sizeof(T), [&](int r) { return a + (size_t)(t0 + r) * EF; });
       typename GM::RSrc R;
-      GM::r_rows(R, min(GM::BN, d - n0), (size_t)d * f * sizeof(T), [&](int r) { return w + (size_t)(n0 + r) * f; });
-      GM::mainloop(acc, L, R, (int)(EF / GM::BK), f / GM::BK, st);
+      if (part < 2) {
+        // K runs over (expert, hidden unit): one segment of f per expert on both sides
+        const T* a = part ? dG : dU;
+        const T* w = part ? w_gate : w_up;
+        GM::l_rows(L, min(GM::BM, Tn - t0), (size_t)f * sizeof(T), [&](int r) { return a + (size_t)(t0 + r) * EF; });
+        GM::r_rows(R, min(GM::BN, d - n0), (size_t)d * f * sizeof(T), [&](int r) { return w + (size_t)(n0 + r) * f; });
+        GM::mainloop(acc, L, R, (int)(EF / GM::BK), f / GM::BK, st);
+      } else {
+        // router path: K runs over the (padded) experts
+        GM::l_rows(L, min(GM::BM, Tn - t0), 0, [&](int r) { return dZt + (size_t)(t0 + r) * EP; });
+        GM::r_rows(R, min(GM::BN, d - n0), 0, [&](int r) { return w_rp + (size_t)(n0 + r) * EP; });
+        GM::mainloop(acc, L, R, EP / GM::BK, 1 << 30, st);
+      }
     }
     GM::for_each_chunk(acc, st, [&](int m, int n, const float (&v)[1][GM::CHUNK]) {
       const int t = t0 + m, col = n0 + n;
       if (t >= Tn || col >= d) return;
-      float o[GM::CHUNK];
-#pragma unroll
-      for (int i = 0; i < GM::CHUNK; ++i) o[i] = v[0][i];
-      const float* z = dZ + (size_t)t * E;
-      for (int e = 0; e < E; ++e) {
-        const float ze = z[e];
-#pragma unroll
-        for (int i = 0; i < GM::CHUNK; ++i) o[i] = fmaf(ze, to_f32(w_r[(size_t)(col + i) * E + e]), o[i]);
-      }
-      store_chunk(dx + (size_t)t * d + col, o);
+      store_chunk(dx + (size_t)t * d + col, v[0]);
     });
   }
 }
 
 // ---- softmax backward: dZ = S (dS - sum_k S_k dS_k), one wave per token, one lane per expert -------------
+template <typename T>
 __global__ void __launch_bounds__(kThreads)
-dense_softmax_bwd_kernel(const float* __restrict__ S, const float* __restrict__ dS_part, int ntb, int Tn, int E,
-                         float* __restrict__ dZ, unsigned* __restrict__ zeros) {
+dense_softmax_bwd_kernel(const float* __restrict__ S, const float* __restrict__ dS_part, int ntb, int Tn, int E, int EP,
+                         float* __restrict__ dZ, T* __restrict__ dZt, unsigned* __restrict__ zeros) {
   if (blockIdx.x == 0 && threadIdx.x < 64) zeros[threadIdx.x] = 0u;   // the zero page of the later kernels
   const int lane = threadIdx.x & 63;
   const int t = blockIdx.x * 4 + (threadIdx.x >> 6);
@@ -296,64 +326,75 @@ dense_softmax_bwd_kernel(const float* __restrict__ S, const float* __restrict__ 
   float dot = s * ds;
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) dot += __shfl_xor(dot, o, 64);
-  if (lane < E) dZ[(size_t)t * E + lane] = s * (ds - dot);
+  const float dz = s * (ds - dot);
+  if (lane < E) dZ[(size_t)t * E + lane] = dz;
+  if (lane < EP) dZt[(size_t)t * EP + lane] = (T)(lane < E ? dz : 0.f);
 }
 
-// ---- router weight gradient: partial dW_r = X^T dZ and db_r = sum_t dZ over a slab of tokens ---------------
-// grid (d / 64, n_split); thread (i = tid % 64, expert group tid / 64) accumulates E/4 experts.
+// ---- router weight gradient: partial dW_r = X^T dZ over a slab of tokens, through the MFMA core ---------------
+// (dZ in the storage type, padded to EP columns); the slabs are added in order by the reduce kernel.
+template <typename T>
+__global__ void __launch_bounds__((Gemm<T, DenseTiles<T>::BM, DenseTiles<T>::BN1, 1, true, true, true>::THREADS))
+dense_router_dw_kernel(const T* __restrict__ x, const T* __restrict__ dZt, int Tn, int d, int E, int EP, int nsplit,
+                       float* __restrict__ dWr_part, const void* __restrict__ zeros) {
+  typedef Gemm<T, DenseTiles<T>::BM, DenseTiles<T>::BN1, 1, true, true, true> GM;
+  DSMOE_GEMM_STAGES(GM, st);
+  const int n_mt = (d + GM::BM - 1) / GM::BM;
+  TileWalker tw;
+  tw.init(n_mt * nsplit);
+  int idx;
+  while (tw.next(idx)) {
+    const int mt = idx % n_mt, ks = idx / n_mt;
+    const int m0 = mt * GM::BM, k0 = ks * kWrTokens, kv = min(kWrTokens, Tn - k0);
+    typename GM::LSrc L;
+    GM::l_cols(L, x + (size_t)k0 * d + m0, d, d - m0, kv, zeros);
+    typename GM::RSrc R;
+    const T* const base[1] = {dZt + (size_t)k0 * EP};
+    GM::r_cols(R, base, EP, EP, kv, zeros);
+    typename GM::Acc acc;
+    GM::zero(acc);
+    GM::mainloop(acc, L, R, (kv + GM::BK - 1) / GM::BK, 1 << 30, st);
+    float* out = dWr_part + (size_t)ks * d * E;
+    GM::for_each_chunk(acc, st, [&](int m, int n, const float (&v)[1][GM::CHUNK]) {
+      if (m0 + m >= d || n >= E) return;
+      store_chunk(out + (size_t)(m0 + m) * E + n, v[0]);
+    });
+  }
+}
+
+__global__ void __launch_bounds__(kThreads)
+dense_router_dw_reduce_kernel(const float* __restrict__ dWr_part, int nsplit, int n, float* __restrict__ dw_r) {
+  const int i = blockIdx.x * kThreads + threadIdx.x;
+  if (i >= n) return;
+  float s = 0.f;
+  for (int k = 0; k < nsplit; ++k) s += dWr_part[(size_t)k * n + i];
+  dw_r[i] = s;
+}
+
+// db_r[e] = sum_t dZ[t, e]: one block per expert, strided partial sums, then a fixed-order tree
+__global__ void __launch_bounds__(kThreads)
+dense_router_db_kernel(const float* __restrict__ dZ, int Tn, int E, float* __restrict__ db_r) {
+  __shared__ float sSum[kThreads];
+  const int e = blockIdx.x;
+  float s = 0.f;
+  for (int t = threadIdx.x; t < Tn; t += kThreads) s += dZ[(size_t)t * E + e];
+  sSum[threadIdx.x] = s;
+  __syncthreads();
+  for (int w = kThreads / 2; w > 0; w >>= 1) {
+    if ((int)threadIdx.x < w) sSum[threadIdx.x] += sSum[threadIdx.x + w];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) db_r[e] = sSum[0];
+}
+
+// w_rp[i][0..EP) = w_r[i][0..E) followed by zeros
 template <typename T>
 __global__ void __launch_bounds__(kThreads)
-dense_router_dw_kernel(const T* __restrict__ x, const float* __restrict__ dZ, int Tn, int d, int E,
-                       float* __restrict__ dWr_part, float* __restrict__ dbr_part) {
-  __shared__ float sX[64][65];
-  __shared__ float sZ[64][kMaxExperts];
-  const int i0 = blockIdx.x * 64, il = threadIdx.x & 63, eg = threadIdx.x >> 6, ept = E / 4;
-  const int tb = blockIdx.y * kWrTokens, te = min(Tn, tb + kWrTokens);
-  float acc[kMaxExperts / 4];
-#pragma unroll
-  for (int j = 0; j < kMaxExperts / 4; ++j) acc[j] = 0.f;
-  float bsum = 0.f;
-  for (int c0 = tb; c0 < te; c0 += 64) {
-    __syncthreads();
-    for (int q = threadIdx.x; q < 64 * 64; q += kThreads) {
-      const int tt = q >> 6, ii = q & 63;
-      sX[tt][ii] = c0 + tt < te ? to_f32(x[(size_t)(c0 + tt) * d + i0 + ii]) : 0.f;
-    }
-    for (int q = threadIdx.x; q < 64 * E; q += kThreads) {
-      const int tt = q / E, ee = q % E;
-      sZ[tt][ee] = c0 + tt < te ? dZ[(size_t)(c0 + tt) * E + ee] : 0.f;
-    }
-    __syncthreads();
-    for (int tt = 0; tt < 64; ++tt) {
-      const float xv = sX[tt][il];
-#pragma unroll
-      for (int j = 0; j < kMaxExperts / 4; ++j)
-        if (j < ept) acc[j] = fmaf(xv, sZ[tt][eg * ept + j], acc[j]);
-    }
-    if (blockIdx.x == 0 && threadIdx.x < E)
-      for (int tt = 0; tt < 64; ++tt) bsum += sZ[tt][threadIdx.x];
-  }
-  float* out = dWr_part + (size_t)blockIdx.y * d * E;
-#pragma unroll
-  for (int j = 0; j < kMaxExperts / 4; ++j)
-    if (j < ept) out[(size_t)(i0 + il) * E + eg * ept + j] = acc[j];
-  if (blockIdx.x == 0 && threadIdx.x < E) dbr_part[(size_t)blockIdx.y * E + threadIdx.x] = bsum;
-}
-
-__global__ void __launch_bounds__(kThreads)
-dense_router_dw_reduce_kernel(const float* __restrict__ dWr_part, const float* __restrict__ dbr_part, int nsplit,
-                              int n, int E, float* __restrict__ dw_r, float* __restrict__ db_r) {
+dense_pad_wr_kernel(const T* __restrict__ w_r, int d, int E, int EP, T* __restrict__ w_rp) {
   const int i = blockIdx.x * kThreads + threadIdx.x;
-  if (i < n) {
-    float s = 0.f;
-    for (int k = 0; k < nsplit; ++k) s += dWr_part[(size_t)k * n + i];
-    dw_r[i] = s;
-  }
-  if (db_r != nullptr && i < E) {
-    float s = 0.f;
-    for (int k = 0; k < nsplit; ++k) s += dbr_part[(size_t)k * E + i];
-    db_r[i] = s;
-  }
+  if (i >= d * EP) return;
+  const int row = i / EP, e = i % EP;
+  w_rp[i] = e < E ? w_r[(size_t)row * E + e] : (T)0.f;
 }
 
 template <typename K>
@@ -405,8 +446,9 @@ hipError_t dense_bwd_t(const dsmoe_ctx* c, const void* x, const void* w_r, const
   T* dG = reinterpret_cast<T*>(scratch + sc.dG);
   float* dS_part = reinterpret_cast<float*>(scratch + sc.dS_part);
   float* dZ = reinterpret_cast<float*>(scratch + sc.dZ);
+  T* dZt = reinterpret_cast<T*>(scratch + sc.dZt);
+  T* w_rp = reinterpret_cast<T*>(scratch + sc.WrP);
   float* dWr_part = reinterpret_cast<float*>(scratch + sc.dWr_part);
-  float* dbr_part = reinterpret_cast<float*>(scratch + sc.dbr_part);
   auto cdiv = [](long a, long b) { return (a + b - 1) / b; };
 
   static bool attrs = false;
@@ -414,6 +456,7 @@ hipError_t dense_bwd_t(const dsmoe_ctx* c, const void* x, const void* w_r, const
     if (hipError_t e = set_lds(dense_bwd_dh_kernel<T>, GRR::LDS_BYTES)) return e;
     if (hipError_t e = set_lds(dense_bwd_dx_kernel<T>, GRR::LDS_BYTES)) return e;
     if (hipError_t e = set_lds(dense_bwd_dwdown_kernel<T>, GCC1::LDS_BYTES)) return e;
+    if (hipError_t e = set_lds(dense_router_dw_kernel<T>, GCC1::LDS_BYTES)) return e;
     if (hipError_t e = set_lds(dense_bwd_dwgu_kernel<T>, GCC2::LDS_BYTES)) return e;
     attrs = true;
   }
@@ -423,16 +466,24 @@ hipError_t dense_bwd_t(const dsmoe_ctx* c, const void* x, const void* w_r, const
       (const T*)d_out, (const T*)w_down, S, G, U, dU, dG, dS_part, Tn, d, f, E);
   if (hipError_t e = hipGetLastError()) return e;
 
-  dense_softmax_bwd_kernel<<<dim3((Tn + 3) / 4), dim3(kThreads), 0, s>>>(S, dS_part, sc.ntb, Tn, E, dZ,
+  dense_softmax_bwd_kernel<T><<<dim3((Tn + 3) / 4), dim3(kThreads), 0, s>>>(S, dS_part, sc.ntb, Tn, E, sc.EP, dZ, dZt,
                                                                                   reinterpret_cast<unsigned*>(scratch + sc.zeros));
   if (hipError_t e = hipGetLastError()) return e;
 
-  dense_router_dw_kernel<T><<<dim3(d / 64, sc.nsplit), dim3(kThreads), 0, s>>>((const T*)x, dZ, Tn, d, E, dWr_part,
-                                                                              dbr_part);
+  dense_pad_wr_kernel<T><<<dim3((d * sc.EP + kThreads - 1) / kThreads), dim3(kThreads), 0, s>>>((const T*)w_r, d, E, sc.EP,
+                                                                                               w_rp);
   if (hipError_t e = hipGetLastError()) return e;
-  dense_router_dw_reduce_kernel<<<dim3((d * E + kThreads - 1) / kThreads), dim3(kThreads), 0, s>>>(
-      dWr_part, dbr_part, sc.nsplit, d * E, E, dw_r, db_r);
+  tiles = cdiv(d, DT::BM) * sc.nsplit;
+  dense_router_dw_kernel<T><<<dim3(grid_for(c, tiles, bpc)), dim3(GCC1::THREADS), GCC1::LDS_BYTES, s>>>(
+      (const T*)x, dZt, Tn, d, E, sc.EP, sc.nsplit, dWr_part, scratch + sc.zeros);
   if (hipError_t e = hipGetLastError()) return e;
+  dense_router_dw_reduce_kernel<<<dim3((d * E + kThreads - 1) / kThreads), dim3(kThreads), 0, s>>>(dWr_part, sc.nsplit,
+                                                                                                  d * E, dw_r);
+  if (hipError_t e = hipGetLastError()) return e;
+  if (db_r != nullptr) {
+    dense_router_db_kernel<<<dim3(E), dim3(kThreads), 0, s>>>(dZ, Tn, E, db_r);
+    if (hipError_t e = hipGetLastError()) return e;
+  }
 
   tiles = E * cdiv(f, DT::BM) * cdiv(d, DT::BN1);
   dense_bwd_dwdown_kernel<T><<<dim3(grid_for(c, tiles, bpc)), dim3(GCC1::THREADS), GCC1::LDS_BYTES, s>>>(
@@ -446,7 +497,7 @@ hipError_t dense_bwd_t(const dsmoe_ctx* c, const void* x, const void* w_r, const
 
   tiles = cdiv(Tn, DT::BM) * cdiv(d, DT::BN1);
   dense_bwd_dx_kernel<T><<<dim3(grid_for(c, tiles, bpc)), dim3(GRR::THREADS), GRR::LDS_BYTES, s>>>(
-      dU, dG, (const T*)w_up, (const T*)w_gate, dZ, (const T*)w_r, (T*)dx, Tn, d, f, E);
+      dU, dG, (const T*)w_up, (const T*)w_gate, dZt, w_rp, (T*)dx, Tn, d, f, E, sc.EP);
   return hipGetLastError();
 }
 

@@ -131,7 +131,11 @@ down_kernel(const T* __restrict__ h, const int32_t* __restrict__ expert_off, con
   }
 }
 
-// ---- bf16: 256-row tiles, 8 waves, transposing LDS reads of the weights ------------------------------
+// ---- bf16: 256-row tiles, 8 waves, direct global -> LDS loads -------------------------------------------
+// Both kernels are software-pipelined over tiles: the first K steps of the next tile are requested before
+// the epilogue of the current one.
+struct FfnTile { int e, row0, valid, n0; };
+
 template <int BM>
 __global__ void __launch_bounds__(kThreads2)
 gateup_bf16_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ x_perm, const int32_t* __restrict__ row_token,
@@ -142,34 +146,55 @@ gateup_bf16_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ x_pe
   DSMOE_TILE3_STAGES(TL, st);
   __shared__ GroupTiles gt;
   build_group_tiles(gt, expert_off, E, BM);
-  const int n_tiles = (f + BNS - 1) / BNS;
+  const int n_tiles = (f + BNS - 1) / BNS, nkt = d / TL::BK;
   TileWalker tw;
   tw.init(gt.tile_off[E] * n_tiles);
-  int idx;
-  while (tw.next(idx)) {
+  auto setup = [&](int idx, FfnTile& t, typename TL::LSrc& L, typename TL::RSrc& R) {
     const int nt_blk = idx % n_tiles, mg = idx / n_tiles;
-    const int e = find_group(gt, E, mg);
-    const int row0 = gt.row_off[e] + (mg - gt.tile_off[e]) * BM;
-    const int valid = min(BM, gt.row_off[e + 1] - row0);
-    const int n0 = nt_blk * BNS;
-
-    typename TL::LSrc L;
-    L.init(valid, 0, [&](int r) {
+    t.e = find_group(gt, E, mg);
+    t.row0 = gt.row_off[t.e] + (mg - gt.tile_off[t.e]) * BM;
+    t.valid = min(BM, gt.row_off[t.e + 1] - t.row0);
+    t.n0 = nt_blk * BNS;
+    const int row0 = t.row0;
+    L.init(t.valid, 0, [&](int r) {
       return x_perm ? x_perm + (size_t)(row0 + r) * d : x + (size_t)row_token[row0 + r] * d;
     });
-    typename TL::RSrc R;
-    const bf16_t* const base[2] = {w_gate + (size_t)e * d * f + n0, w_up + (size_t)e * d * f + n0};
-    R.init(base, f, min(BNS, f - n0), d);
+    const bf16_t* const base[2] = {w_gate + (size_t)t.e * d * f + t.n0, w_up + (size_t)t.e * d * f + t.n0};
+    R.init(base, f, min(BNS, f - t.n0), d);
+  };
+  int idx;
+  if (!tw.next(idx)) return;
+  FfnTile cur;
+  typename TL::LSrc L;
+  typename TL::RSrc R;
+  typename TL::Iter it;
+  setup(idx, cur, L, R);
+  TL::prefetch(L, R, it, nkt, 1 << 30, st);
+  while (true) {
     typename TL::Acc acc;
     TL::zero(acc);
-    TL::mainloop(acc, L, R, d / TL::BK, 1 << 30, st);
-    TL::for_each_chunk(acc, st, [&](int m, int n, const float (&v)[2][TL::CHUNK]) {
-      if (m >= valid || n0 + n >= f) return;
-      float o[TL::CHUNK];
+    TL::run(acc, L, R, it, nkt, 1 << 30, st);
+    FfnTile nxt;
+    typename TL::LSrc Ln;
+    typename TL::RSrc Rn;
+    typename TL::Iter itn;
+    const bool more = tw.next(idx);
+    if (more) {
+      setup(idx, nxt, Ln, Rn);
+      TL::prefetch(Ln, Rn, itn, nkt, 1 << 30, st);
+    }
+    TL::template for_each_chunk_bf16<1>(
+        acc, st,
+        [&](int, int, const float (&v)[2][4], float (&o)[1][4]) {
 #pragma unroll
-      for (int i = 0; i < TL::CHUNK; ++i) o[i] = silu_f(v[0][i]) * v[1][i];
-      store_chunk(h + (size_t)(row0 + m) * f + n0 + n, o);
-    });
+          for (int i = 0; i < 4; ++i) o[0][i] = silu_f(v[0][i]) * v[1][i];
+        },
+        [&](int m, int n, const u32x4 (&p)[1]) {
+          if (m >= cur.valid || cur.n0 + n >= f) return;
+          stg16(h + (size_t)(cur.row0 + m) * f + cur.n0 + n, p[0]);
+        });
+    if (!more) break;
+    cur = nxt; L = Ln; R = Rn; it = itn;
   }
 }
 
@@ -182,29 +207,53 @@ down_bf16_kernel(const bf16_t* __restrict__ h, const int32_t* __restrict__ exper
   DSMOE_TILE3_STAGES(TL, st);
   __shared__ GroupTiles gt;
   build_group_tiles(gt, expert_off, E, BM, uniform_rows);
-  const int n_tiles = (d + BN - 1) / BN;
+  const int n_tiles = (d + BN - 1) / BN, nkt = f / TL::BK;
   TileWalker tw;
   tw.init(gt.tile_off[E] * n_tiles);
-  int idx;
-  while (tw.next(idx)) {
+  auto setup = [&](int idx, FfnTile& t, typename TL::LSrc& L, typename TL::RSrc& R) {
     const int nt_blk = idx % n_tiles, mg = idx / n_tiles;
-    const int e = find_group(gt, E, mg);
-    const int row0 = gt.row_off[e] + (mg - gt.tile_off[e]) * BM;
-    const int valid = min(BM, gt.row_off[e + 1] - row0);
-    const int n0 = nt_blk * BN;
-
-    typename TL::LSrc L;
-    L.init(valid, 0, [&](int r) { return h + (size_t)(row0 + r) * f; });
-    typename TL::RSrc R;
-    const bf16_t* const base[1] = {w_down + (size_t)e * f * d + n0};
-    R.init(base, d, min(BN, d - n0), f);
+    t.e = find_group(gt, E, mg);
+    t.row0 = gt.row_off[t.e] + (mg - gt.tile_off[t.e]) * BM;
+    t.valid = min(BM, gt.row_off[t.e + 1] - t.row0);
+    t.n0 = nt_blk * BN;
+    const int row0 = t.row0;
+    L.init(t.valid, 0, [&](int r) { return h + (size_t)(row0 + r) * f; });
+    const bf16_t* const base[1] = {w_down + (size_t)t.e * f * d + t.n0};
+    R.init(base, d, min(BN, d - t.n0), f);
+  };
+  int idx;
+  if (!tw.next(idx)) return;
+  FfnTile cur;
+  typename TL::LSrc L;
+  typename TL::RSrc R;
+  typename TL::Iter it;
+  setup(idx, cur, L, R);
+  TL::prefetch(L, R, it, nkt, 1 << 30, st);
+  while (true) {
     typename TL::Acc acc;
     TL::zero(acc);
-    TL::mainloop(acc, L, R, f / TL::BK, 1 << 30, st);
-    TL::for_each_chunk(acc, st, [&](int m, int n, const float (&v)[1][TL::CHUNK]) {
-      if (m >= valid || n0 + n >= d) return;
-      store_chunk(y + (size_t)(row0 + m) * d + n0 + n, v[0]);
-    });
+    TL::run(acc, L, R, it, nkt, 1 << 30, st);
+    FfnTile nxt;
+    typename TL::LSrc Ln;
+    typename TL::RSrc Rn;
+    typename TL::Iter itn;
+    const bool more = tw.next(idx);
+    if (more) {
+      setup(idx, nxt, Ln, Rn);
+      TL::prefetch(Ln, Rn, itn, nkt, 1 << 30, st);
+    }
+    TL::template for_each_chunk_bf16<1>(
+        acc, st,
+        [&](int, int, const float (&v)[1][4], float (&o)[1][4]) {
+#pragma unroll
+          for (int i = 0; i < 4; ++i) o[0][i] = v[0][i];
+        },
+        [&](int m, int n, const u32x4 (&p)[1]) {
+          if (m >= cur.valid || cur.n0 + n >= d) return;
+          stg16(y + (size_t)(cur.row0 + m) * d + cur.n0 + n, p[0]);
+        });
+    if (!more) break;
+    cur = nxt; L = Ln; R = Rn; it = itn;
   }
 }
 

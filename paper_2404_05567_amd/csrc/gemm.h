@@ -145,6 +145,13 @@ struct Gemm<float, BM_, BN_, NSRC_, LK, RK, KTAIL> {
     TL::mainloop(acc, L, R.s, nkt, seg_tiles, st.smem);
     __syncthreads();   // the tile may be restaged (or LDS reused) right after
   }
+  // two-phase form of the main loop (the bf16 core starts loading the next tile before the epilogue)
+  struct Iter {};
+  static __device__ __forceinline__ void prefetch(const LSrc&, const RSrc&, Iter&, int, int, const Stages&) {}
+  static __device__ __forceinline__ void run(Acc& acc, const LSrc& L, const RSrc& R, Iter&, int nkt, int seg_tiles,
+                                             const Stages& st) {
+    mainloop(acc, L, R, nkt, seg_tiles, st);
+  }
   // f(m, n, v): row m of the tile, first of CHUNK consecutive columns n (inside a source), v[s][0..CHUNK)
   template <class F>
   static __device__ __forceinline__ void for_each_chunk(const Acc& acc, const Stages&, F f) {
@@ -210,6 +217,15 @@ struct Gemm<bf16_t, BM_, BN_, NSRC_, LK, RK, KTAIL> {
   static __device__ __forceinline__ void mainloop(Acc& acc, const LSrc& L, const RSrc& R, int nkt, int seg_tiles,
                                                   const Stages& st) {
     TL::mainloop(acc, L, R, nkt, seg_tiles, st);
+  }
+  typedef typename TL::Iter Iter;
+  static __device__ __forceinline__ void prefetch(const LSrc& L, const RSrc& R, Iter& it, int nkt, int seg_tiles,
+                                                  const Stages& st) {
+    TL::prefetch(L, R, it, nkt, seg_tiles, st);
+  }
+  static __device__ __forceinline__ void run(Acc& acc, const LSrc& L, const RSrc& R, Iter& it, int nkt, int seg_tiles,
+                                             const Stages& st) {
+    TL::run(acc, L, R, it, nkt, seg_tiles, st);
   }
   template <class F>
   static __device__ __forceinline__ void for_each_chunk(const Acc& acc, const Stages& st, F f) {

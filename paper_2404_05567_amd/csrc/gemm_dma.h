@@ -227,94 +227,143 @@ struct Tile3 {
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt) Mma<bf16_t>::run(acc[nt][mt], f.w[nt], f.x[mt]);
   }
-  // issue order for the scheduler: the LDS reads of the next slice spread over the MFMAs of this one
-  static __device__ __forceinline__ void interleave() { Interleave<0, NMMA, NFR, kSgDsRd>::run(); }
+  // issue order for the scheduler: the LDS reads of the next slice go out two per MFMA, so that the last of
+  // them has the remaining MFMAs to arrive
+  static __device__ __forceinline__ void interleave() {
+    constexpr int NG = (NFR + 1) / 2 < NMMA ? (NFR + 1) / 2 : NMMA;
+    Interleave<0, NG, NFR, kSgDsRd>::run();
+    sched_group<kSgMfma, NMMA - NG>();
+  }
 
-  // acc += L * R over nkt K steps; K may be split in segments of seg_tiles steps (see the sources).
-  // Must be called by all 512 threads; returns with none of this wave's loads in flight.
-  static __device__ __forceinline__ void mainloop(Acc& acc, const LSrc& L, const RSrc& R, int nkt, int seg_tiles,
+  // Position of the next K step to load.
+  struct Iter { int seg, kin, next; };
+  static __device__ __forceinline__ void issue_step(const LSrc& L, const RSrc& R, Iter& it, int nkt, int seg_tiles,
+                                                    lds_char* sl, lds_char* sr) {
+    L.issue(sl, it.seg, it.kin);
+    R.issue(sr, it.seg, it.kin);
+    // steps past the end re-read the last one (only the variant for ragged step counts asks for them)
+    if (++it.next < nkt && ++it.kin == seg_tiles) { it.kin = 0; ++it.seg; }
+  }
+
+  // First half of the prologue: K steps 0 and 1 into stages 0 and 1.  May be called as soon as every wave has
+  // left the previous run() (nobody reads the stages any more), e.g. before the previous tile's epilogue,
+  // which only touches the wave's own slices of stages 2 and 3.
+  static __device__ __forceinline__ void prefetch(const LSrc& L, const RSrc& R, Iter& it, int nkt, int seg_tiles,
                                                   const Stages3& st) {
+    it.seg = 0; it.kin = 0; it.next = 0;
+    issue_step(L, R, it, nkt, seg_tiles, st.l[0], st.r[0]);
+    issue_step(L, R, it, nkt, seg_tiles, st.l[1], st.r[1]);
+  }
+
+  // One K step on stage ST: slice 0 multiplies while slice 1 is read; then, once step + 1 has landed for
+  // every wave (and every wave has read this stage to the end), the stage is refilled with step + 4 and
+  // slice 0 of the next stage is read while slice 1 multiplies.  WAITN: loads that may stay in flight.
+#define DSMOE_STEP3(ST, NX, WAITN, ISSUE)                                     \
+  {                                                                           \
+    read_frags(fb, st.l[ST], st.r[ST], o, 1);                                 \
+    mma(acc, fa);                                                             \
+    interleave();                                                             \
+    __builtin_amdgcn_sched_barrier(0);                                        \
+    wait_vm<WAITN, true>();                                                   \
+    __builtin_amdgcn_s_barrier();                                             \
+    __builtin_amdgcn_sched_barrier(0);                                        \
+    if (ISSUE) issue_step(L, R, it, nkt, seg_tiles, st.l[ST], st.r[ST]);      \
+    __builtin_amdgcn_sched_barrier(0);                                        \
+    read_frags(fa, st.l[NX], st.r[NX], o, 0);                                 \
+    mma(acc, fb);                                                             \
+    interleave();                                                             \
+  }
+
+  // acc += L * R over nkt K steps (K may be split in segments of seg_tiles steps, see the sources), after
+  // prefetch() with the same arguments.  Must be called by all 512 threads; returns with none of this wave's
+  // loads in flight and no wave reading the stages any more.
+  // Global stores issued between prefetch() and run() are fine: the counter waits below only rely on loads
+  // completing in order among loads, so they can at worst wait for such a store too.
+  static __device__ __forceinline__ void run(Acc& acc, const LSrc& L, const RSrc& R, Iter& it, int nkt, int seg_tiles,
+                                             const Stages3& st) {
     Offs o;
     offsets(o);
-    int seg = 0, kin = 0, next = 0;   // position of the next K step to load
-    // Loads are issued unconditionally (steps past the end re-read the last one, into a stage nobody reads
-    // any more): the loop body stays free of branches and the number of loads in flight is a constant.
-    auto issue_next = [&](lds_char* sl, lds_char* sr) {
-      L.issue(sl, seg, kin);
-      R.issue(sr, seg, kin);
-      if (++next < nkt && ++kin == seg_tiles) { kin = 0; ++seg; }
-    };
-    issue_next(st.l[0], st.r[0]);
-    issue_next(st.l[1], st.r[1]);
-    issue_next(st.l[2], st.r[2]);
-    issue_next(st.l[3], st.r[3]);
     Frag fa, fb;
+    issue_step(L, R, it, nkt, seg_tiles, st.l[2], st.r[2]);
+    issue_step(L, R, it, nkt, seg_tiles, st.l[3], st.r[3]);
     __builtin_amdgcn_sched_barrier(0);
     wait_vm<3 * NI, true>();          // step 0 has landed
     __builtin_amdgcn_s_barrier();
     __builtin_amdgcn_sched_barrier(0);
     read_frags(fa, st.l[0], st.r[0], o, 0);
-
-    // One K step on stage ST: slice 0 multiplies while slice 1 is read; then, once step + 1 has landed for
-    // every wave (and every wave has read this stage to the end), the stage is refilled with step + 4 and
-    // slice 0 of the next stage is read while slice 1 multiplies.
-#define DSMOE_STEP3(ST, NX)                                                   \
-  {                                                                           \
-    read_frags(fb, st.l[ST], st.r[ST], o, 1);                                   \
-    mma(acc, fa);                                                             \
-    interleave();                                                             \
-    __builtin_amdgcn_sched_barrier(0);                                        \
-    wait_vm<2 * NI, true>();                                                  \
-    __builtin_amdgcn_s_barrier();                                             \
-    __builtin_amdgcn_sched_barrier(0);                                        \
-    issue_next(st.l[ST], st.r[ST]);                                             \
-    __builtin_amdgcn_sched_barrier(0);                                        \
-    read_frags(fa, st.l[NX], st.r[NX], o, 0);                                   \
-    mma(acc, fb);                                                             \
-    interleave();                                                             \
-  }
-    int kt = 0;
-    for (; kt + kStages3 <= nkt; kt += kStages3) {
-      DSMOE_STEP3(0, 1)
-      DSMOE_STEP3(1, 2)
-      DSMOE_STEP3(2, 3)
-      DSMOE_STEP3(3, 0)
-    }
-    if (kt < nkt) {
-      DSMOE_STEP3(0, 1)
-      if (kt + 1 < nkt) {
-        DSMOE_STEP3(1, 2)
-        if (kt + 2 < nkt) DSMOE_STEP3(2, 3)
+    if ((nkt & 3) == 0) {
+      // exact: every load is a real step; the last four steps refill nothing
+      for (int kt = 0; kt + 2 * kStages3 <= nkt; kt += kStages3) {
+        DSMOE_STEP3(0, 1, 2 * NI, true)
+        DSMOE_STEP3(1, 2, 2 * NI, true)
+        DSMOE_STEP3(2, 3, 2 * NI, true)
+        DSMOE_STEP3(3, 0, 2 * NI, true)
       }
+      DSMOE_STEP3(0, 1, 2 * NI, false)
+      DSMOE_STEP3(1, 2, NI, false)
+      DSMOE_STEP3(2, 3, 0, false)
+      read_frags(fb, st.l[3], st.r[3], o, 1);
+      mma(acc, fa);
+      interleave();
+      __builtin_amdgcn_sched_barrier(0);
+      wait_vm<0, true>();             // own fragment reads done before the stages may be refilled
+      __builtin_amdgcn_s_barrier();
+      __builtin_amdgcn_sched_barrier(0);
+      mma(acc, fb);
+    } else {
+      // ragged step count: loads are issued unconditionally (re-reading the last step into a stage nobody
+      // reads any more), which keeps the loop free of branches and the number of loads in flight constant
+      int kt = 0;
+      for (; kt + kStages3 <= nkt; kt += kStages3) {
+        DSMOE_STEP3(0, 1, 2 * NI, true)
+        DSMOE_STEP3(1, 2, 2 * NI, true)
+        DSMOE_STEP3(2, 3, 2 * NI, true)
+        DSMOE_STEP3(3, 0, 2 * NI, true)
+      }
+      if (kt < nkt) {
+        DSMOE_STEP3(0, 1, 2 * NI, true)
+        if (kt + 1 < nkt) {
+          DSMOE_STEP3(1, 2, 2 * NI, true)
+          if (kt + 2 < nkt) DSMOE_STEP3(2, 3, 2 * NI, true)
+        }
+      }
+      __builtin_amdgcn_sched_barrier(0);
+      wait_vm<0, true>();             // drain the re-read loads
+      __builtin_amdgcn_s_barrier();
+      __builtin_amdgcn_sched_barrier(0);
     }
+  }
 #undef DSMOE_STEP3
-    // every wave read its last fragments before the last barrier; drain the re-read loads
-    __builtin_amdgcn_sched_barrier(0);
-    wait_vm<0, true>();
-    __builtin_amdgcn_sched_barrier(0);
+
+  static __device__ __forceinline__ void mainloop(Acc& acc, const LSrc& L, const RSrc& R, int nkt, int seg_tiles,
+                                                  const Stages3& st) {
+    Iter it;
+    prefetch(L, R, it, nkt, seg_tiles, st);
+    run(acc, L, R, it, nkt, seg_tiles, st);
   }
 
   // Transposed walk over the accumulators.  The MFMA leaves a lane with one row and 4 consecutive columns
   // per register quad, which makes 8-byte accesses spread over 32 rows.  Here every 32-row block of the
-  // wave goes through the wave's own slice of the weight-side stages (fp32, XOR-swizzled 16-byte units, no
-  // barrier needed: no other wave writes there once this wave's loads have drained), and comes back with
+  // wave goes through the wave's own slices of stages 2 and 3 (fp32, XOR-swizzled 16-byte units, no
+  // barrier needed: no other wave writes there once this wave's loads have drained; stages 0 and 1 may
+  // already be receiving the next tile, see prefetch()), and comes back with
   // a lane owning 8 consecutive columns of one row: f(m, n, v) gets the tile row m, the first column n
   // (inside its source) and v[s][0..7]; 8 (NSRC = 1) or 4 (NSRC = 2) neighbouring lanes cover a row, so
   // global accesses made from f are whole 128-byte (bf16: 64..128-byte) row segments.
   static constexpr int CHUNK = 8;
   template <class F>
   static __device__ __forceinline__ void for_each_chunk(const Acc& acc, const Stages3& st, F f) {
-    static_assert(RSrc::LDS / 8 >= 2048, "the wave's slice of a weight-side stage holds 8 rows of 64 floats");
+    static_assert(RSrc::LDS / 8 == 2048 && LSrc::LDS / 8 == 2048, "a wave's slice of a stage holds 8 rows of 64 floats");
     constexpr int OPR = NSRC == 1 ? 8 : 4;        // lanes (column octets) per row and source
     constexpr int RPI = 64 / OPR;                  // rows covered by one read instruction
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int wslice = wave * (RSrc::LDS / 8);
+    const int wslice = wave * 2048;
     const int m = lane & 31, kg = lane >> 5;
     // the stage addresses are link-time constants: keep them as values (a table in memory would be indexed)
-    lds_char* const r0 = st.r[0];
-    lds_char* const r1 = st.r[1];
-    lds_char* const r2 = st.r[2];
-    lds_char* const r3 = st.r[3];
+    lds_char* const r0 = st.r[2];
+    lds_char* const r1 = st.r[3];
+    lds_char* const r2 = st.l[2];
+    lds_char* const r3 = st.l[3];
     auto area = [=](int row) -> lds_char* {        // 8 rows of 256 bytes in each of the four stages
       const int piece = row >> 3;
       lds_char* const lo = (piece & 1) ? r1 : r0;
@@ -348,6 +397,55 @@ struct Tile3 {
         }
         f((wave / WGN) * WM + mt * 32 + r, (wave % WGN) * WCOL + 8 * q, v);
       }
+    }
+  }
+
+  // Packed variant for bf16 outputs: pre(m, n, v, out) runs in the accumulator layout (row m, 4 consecutive
+  // columns from n, v[s][0..3]) and produces NOUT values per element; they are rounded to bf16, staged (one
+  // 2 KB piece of the wave's scratch slices per output and 32-column tile: 32 rows of 64 bytes, XOR-swizzled),
+  // and handed to f(m, n, p) with p[o] = 8 consecutive bf16 of output o, 4 lanes covering a 64-byte row
+  // segment.  A quarter of the LDS traffic of the fp32 walk when the epilogue has one output.
+  template <int NOUT, class P, class F>
+  static __device__ __forceinline__ void for_each_chunk_bf16(const Acc& acc, const Stages3& st, P pre, F f) {
+    static_assert(RSrc::LDS / 8 == 2048 && LSrc::LDS / 8 == 2048, "a wave's slice of a stage holds 32 rows of 64 bytes");
+    constexpr int NTC = NSRC == 1 ? NT : 1;       // 32-column tiles of an output per wave
+    static_assert(NOUT * NTC <= 4, "four scratch pieces per wave");
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int m = lane & 31, kg = lane >> 5;
+    lds_char* const piece[4] = {st.r[2] + wave * 2048, st.r[3] + wave * 2048, st.l[2] + wave * 2048,
+                                st.l[3] + wave * 2048};
+    const int woff = m * 64 + kg * 8, wsw = (m >> 2) & 3;
+    const int rrow = lane >> 2, rq = lane & 3;
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+#pragma unroll
+      for (int tc = 0; tc < NTC; ++tc)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          float v[NSRC][4];
+          float out[NOUT][4];
+#pragma unroll
+          for (int s = 0; s < NSRC; ++s)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) v[s][i] = acc[NSRC == 1 ? tc : s][mt][4 * g + i];
+          pre(acc_m(mt), acc_n(tc, g), v, out);
+#pragma unroll
+          for (int o = 0; o < NOUT; ++o) {
+            const u32x2 pk = {pack_bf16x2(out[o][0], out[o][1]), pack_bf16x2(out[o][2], out[o][3])};
+            *reinterpret_cast<__attribute__((address_space(3))) u32x2*>(piece[o * NTC + tc] + woff + ((g ^ wsw) * 16)) = pk;
+          }
+        }
+#pragma unroll
+      for (int tc = 0; tc < NTC; ++tc)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+          const int r = 16 * j + rrow;
+          u32x4 p[NOUT];
+#pragma unroll
+          for (int o = 0; o < NOUT; ++o)
+            p[o] = *reinterpret_cast<const lds_u32x4*>(piece[o * NTC + tc] + r * 64 + ((rq ^ ((r >> 2) & 3)) * 16));
+          f((wave / WGN) * WM + mt * 32 + r, (wave % WGN) * WCOL + tc * 32 + 8 * rq, p);
+        }
     }
   }
 
