@@ -87,7 +87,7 @@ decode_gateup_kernel(const bf16_t* __restrict__ x, const unsigned long long* __r
                      int32_t* __restrict__ row_token, float* __restrict__ row_weight, int32_t* __restrict__ tok_off,
                      int32_t* __restrict__ tok_rows, int32_t* __restrict__ nnz_out, int32_t* __restrict__ err_flag) {
   constexpr int BNS = 128;                       // columns of gate and of up per item
-  typedef Tile3<kDecT, 2 * BNS, 2> TL;
+  typedef Tile3<kDecT, 2 * BNS, 2, false, true, false, 6> TL;   // six stages: more weight bytes in flight
   DSMOE_TILE3_STAGES(TL, st);
   __shared__ DecodePlan plan;
   __shared__ int toks[kDecT];
@@ -196,7 +196,7 @@ decode_down_kernel(const bf16_t* __restrict__ H, const int32_t* __restrict__ inf
                    const int32_t* __restrict__ expert_off, const bf16_t* __restrict__ w_down,
                    float* __restrict__ P2, int d, int f, int E) {
   constexpr int BN = 256;
-  typedef Tile3<kDecT, BN> TL;
+  typedef Tile3<kDecT, BN, 1, false, true, false, 6> TL;
   DSMOE_TILE3_STAGES(TL, st);
   __shared__ int sOff[kMaxExperts + 1], sAct[kMaxExperts];
   __shared__ int sU;

@@ -58,8 +58,7 @@ struct Gemm;
 // LDS of a kernel built on Gemm<...> GM: static stage arrays (bf16 core) or the dynamic buffer (fp32 core)
 #define DSMOE_GEMM_STAGES(GM, st)                                                                            \
   extern __shared__ __align__(16) char dsmoe_dyn_smem[];                                                     \
-  __shared__ __align__(1024) char st##L0[GM::ST_L], st##L1[GM::ST_L], st##L2[GM::ST_L], st##L3[GM::ST_L];     \
-  __shared__ __align__(1024) char st##R0[GM::ST_R], st##R1[GM::ST_R], st##R2[GM::ST_R], st##R3[GM::ST_R];     \
+  DSMOE_STAGE_ARRAYS(st, 4, GM::ST_L, GM::ST_R);                                                             \
   typename GM::Stages st =                                                                                   \
       GM::make_stages(st##L0, st##L1, st##L2, st##L3, st##R0, st##R1, st##R2, st##R3, dsmoe_dyn_smem)
 
@@ -192,6 +191,7 @@ struct Gemm<bf16_t, BM_, BN_, NSRC_, LK, RK, KTAIL> {
     Stages s;
     s.l[0] = (lds_char*)l0; s.l[1] = (lds_char*)l1; s.l[2] = (lds_char*)l2; s.l[3] = (lds_char*)l3;
     s.r[0] = (lds_char*)r0; s.r[1] = (lds_char*)r1; s.r[2] = (lds_char*)r2; s.r[3] = (lds_char*)r3;
+    s.l[4] = s.l[5] = s.r[4] = s.r[5] = nullptr;
     return s;
   }
 

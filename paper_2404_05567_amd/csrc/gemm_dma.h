@@ -28,7 +28,7 @@
 
 namespace dsmoe {
 
-constexpr int kStages3 = 4;
+constexpr int kMaxStages3 = 6;   // LDS stages a kernel may use (Tile3's NST: 4 for the MFMA-bound kernels, 6 for streaming)
 
 typedef __attribute__((address_space(1))) const void gvoid_t;
 typedef __attribute__((address_space(3))) void lvoid_t;
@@ -151,20 +151,25 @@ struct DCols {
 
 // The LDS stages of a kernel: separate __shared__ arrays (so that the compiler can tell the stages apart),
 // declared once per kernel with DSMOE_TILE3_STAGES and handed to the main loop and the epilogue.
-struct Stages3 { lds_char* l[kStages3]; lds_char* r[kStages3]; };
-#define DSMOE_TILE3_STAGES(TL, st)                                                                         \
-  __shared__ __align__(1024) char st##L0[TL::LDS_L], st##L1[TL::LDS_L], st##L2[TL::LDS_L], st##L3[TL::LDS_L]; \
-  __shared__ __align__(1024) char st##R0[TL::LDS_R], st##R1[TL::LDS_R], st##R2[TL::LDS_R], st##R3[TL::LDS_R]; \
-  dsmoe::Stages3 st;                                                                                       \
-  st.l[0] = (dsmoe::lds_char*)st##L0; st.l[1] = (dsmoe::lds_char*)st##L1;                                  \
-  st.l[2] = (dsmoe::lds_char*)st##L2; st.l[3] = (dsmoe::lds_char*)st##L3;                                  \
-  st.r[0] = (dsmoe::lds_char*)st##R0; st.r[1] = (dsmoe::lds_char*)st##R1;                                  \
-  st.r[2] = (dsmoe::lds_char*)st##R2; st.r[3] = (dsmoe::lds_char*)st##R3
+struct Stages3 { lds_char* l[kMaxStages3]; lds_char* r[kMaxStages3]; };
+#define DSMOE_STAGE_ARRAYS(st, NST, LB, RB)                                                                  \
+  __shared__ __align__(1024) char st##L0[LB], st##L1[LB], st##L2[LB], st##L3[LB], st##L4[(NST) > 4 ? (LB) : 16],  \
+      st##L5[(NST) > 5 ? (LB) : 16];                                                                         \
+  __shared__ __align__(1024) char st##R0[RB], st##R1[RB], st##R2[RB], st##R3[RB], st##R4[(NST) > 4 ? (RB) : 16],  \
+      st##R5[(NST) > 5 ? (RB) : 16]
+#define DSMOE_TILE3_STAGES(TL, st)                                                                           \
+  DSMOE_STAGE_ARRAYS(st, TL::NST, TL::LDS_L, TL::LDS_R);                                                     \
+  dsmoe::Stages3 st;                                                                                         \
+  st.l[0] = (dsmoe::lds_char*)st##L0; st.l[1] = (dsmoe::lds_char*)st##L1; st.l[2] = (dsmoe::lds_char*)st##L2; \
+  st.l[3] = (dsmoe::lds_char*)st##L3; st.l[4] = (dsmoe::lds_char*)st##L4; st.l[5] = (dsmoe::lds_char*)st##L5; \
+  st.r[0] = (dsmoe::lds_char*)st##R0; st.r[1] = (dsmoe::lds_char*)st##R1; st.r[2] = (dsmoe::lds_char*)st##R2; \
+  st.r[3] = (dsmoe::lds_char*)st##R3; st.r[4] = (dsmoe::lds_char*)st##R4; st.r[5] = (dsmoe::lds_char*)st##R5
 
 // NSRC = 2: the wave's two column tiles are the same 32 columns of source 0 (gate) and source 1 (up).
-template <int BM_, int BN_, int NSRC_ = 1, bool L_KMAJOR = false, bool R_KMAJOR = true, bool KTAIL = false>
+template <int BM_, int BN_, int NSRC_ = 1, bool L_KMAJOR = false, bool R_KMAJOR = true, bool KTAIL = false, int NST_ = 4>
 struct Tile3 {
-  static constexpr int BM = BM_, BN = BN_, NSRC = NSRC_, BK = kBK2, WGM = 2, WGN = 4;
+  static constexpr int BM = BM_, BN = BN_, NSRC = NSRC_, BK = kBK2, WGM = 2, WGN = 4, NST = NST_;
+  static_assert(NST >= 4 && NST <= kMaxStages3, "four to six stages");
   static constexpr int WM = BM / WGM, WN = BN / WGN;
   static constexpr int MT = WM / 32, NT = WN / 32;
   static_assert(NSRC == 1 || NT == NSRC, "one column tile per source");
@@ -245,33 +250,76 @@ struct Tile3 {
     if (++it.next < nkt && ++it.kin == seg_tiles) { it.kin = 0; ++it.seg; }
   }
 
-  // First half of the prologue: K steps 0 and 1 into stages 0 and 1.  May be called as soon as every wave has
-  // left the previous run() (nobody reads the stages any more), e.g. before the previous tile's epilogue,
-  // which only touches the wave's own slices of stages 2 and 3.
+  // First part of the prologue: K steps 0 .. NST-3 into the stages of the same number.  May be called as soon
+  // as every wave has left the previous run() (nobody reads the stages any more), e.g. before the previous
+  // tile's epilogue, which only touches the wave's own slices of the last two stages.
+  template <int ST = 0>
   static __device__ __forceinline__ void prefetch(const LSrc& L, const RSrc& R, Iter& it, int nkt, int seg_tiles,
                                                   const Stages3& st) {
-    it.seg = 0; it.kin = 0; it.next = 0;
-    issue_step(L, R, it, nkt, seg_tiles, st.l[0], st.r[0]);
-    issue_step(L, R, it, nkt, seg_tiles, st.l[1], st.r[1]);
+    if constexpr (ST == 0) { it.seg = 0; it.kin = 0; it.next = 0; }
+    if constexpr (ST < NST - 2) {
+      issue_step(L, R, it, nkt, seg_tiles, st.l[ST], st.r[ST]);
+      prefetch<ST + 1>(L, R, it, nkt, seg_tiles, st);
+    }
   }
 
+  struct Loop {   // what a K step needs besides the stage number
+    Acc& acc; Frag& fa; Frag& fb; const LSrc& L; const RSrc& R; Iter& it; int nkt, seg_tiles; const Stages3& st;
+    const Offs& o;
+  };
   // One K step on stage ST: slice 0 multiplies while slice 1 is read; then, once step + 1 has landed for
-  // every wave (and every wave has read this stage to the end), the stage is refilled with step + 4 and
+  // every wave (and every wave has read this stage to the end), the stage is refilled with step + NST and
   // slice 0 of the next stage is read while slice 1 multiplies.  WAITN: loads that may stay in flight.
-#define DSMOE_STEP3(ST, NX, WAITN, ISSUE)                                     \
-  {                                                                           \
-    read_frags(fb, st.l[ST], st.r[ST], o, 1);                                 \
-    mma(acc, fa);                                                             \
-    interleave();                                                             \
-    __builtin_amdgcn_sched_barrier(0);                                        \
-    wait_vm<WAITN, true>();                                                   \
-    __builtin_amdgcn_s_barrier();                                             \
-    __builtin_amdgcn_sched_barrier(0);                                        \
-    if (ISSUE) issue_step(L, R, it, nkt, seg_tiles, st.l[ST], st.r[ST]);      \
-    __builtin_amdgcn_sched_barrier(0);                                        \
-    read_frags(fa, st.l[NX], st.r[NX], o, 0);                                 \
-    mma(acc, fb);                                                             \
-    interleave();                                                             \
+  template <int ST, int WAITN, bool ISSUE>
+  static __device__ __forceinline__ void step(const Loop& q) {
+    constexpr int NX = (ST + 1) % NST;
+    read_frags(q.fb, q.st.l[ST], q.st.r[ST], q.o, 1);
+    mma(q.acc, q.fa);
+    interleave();
+    __builtin_amdgcn_sched_barrier(0);
+    wait_vm<WAITN, true>();
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_sched_barrier(0);
+    if constexpr (ISSUE) issue_step(q.L, q.R, q.it, q.nkt, q.seg_tiles, q.st.l[ST], q.st.r[ST]);
+    __builtin_amdgcn_sched_barrier(0);
+    read_frags(q.fa, q.st.l[NX], q.st.r[NX], q.o, 0);
+    mma(q.acc, q.fb);
+    interleave();
+  }
+  // N consecutive refilling steps from stage ST
+  template <int ST, int N>
+  static __device__ __forceinline__ void steps(const Loop& q) {
+    if constexpr (N > 0) {
+      step<ST, (NST - 2) * NI, true>(q);
+      steps<(ST + 1) % NST, N - 1>(q);
+    }
+  }
+  // the last NST steps of an exact run: nothing is refilled, ever fewer loads remain in flight
+  template <int ST>
+  static __device__ __forceinline__ void tail(const Loop& q) {
+    if constexpr (ST < NST - 1) {
+      step<ST, (NST - 2 - ST) * NI, false>(q);
+      tail<ST + 1>(q);
+    } else {
+      read_frags(q.fb, q.st.l[ST], q.st.r[ST], q.o, 1);
+      mma(q.acc, q.fa);
+      interleave();
+      __builtin_amdgcn_sched_barrier(0);
+      wait_vm<0, true>();             // own fragment reads done before the stages may be refilled
+      __builtin_amdgcn_s_barrier();
+      __builtin_amdgcn_sched_barrier(0);
+      mma(q.acc, q.fb);
+    }
+  }
+  // up to NST - 1 further refilling steps (ragged step counts)
+  template <int ST>
+  static __device__ __forceinline__ void rest(const Loop& q, int r) {
+    if constexpr (ST < NST - 1) {
+      if (r > 0) {
+        step<ST, (NST - 2) * NI, true>(q);
+        rest<ST + 1>(q, r - 1);
+      }
+    }
   }
 
   // acc += L * R over nkt K steps (K may be split in segments of seg_tiles steps, see the sources), after
@@ -284,56 +332,30 @@ struct Tile3 {
     Offs o;
     offsets(o);
     Frag fa, fb;
-    issue_step(L, R, it, nkt, seg_tiles, st.l[2], st.r[2]);
-    issue_step(L, R, it, nkt, seg_tiles, st.l[3], st.r[3]);
+    issue_step(L, R, it, nkt, seg_tiles, st.l[NST - 2], st.r[NST - 2]);
+    issue_step(L, R, it, nkt, seg_tiles, st.l[NST - 1], st.r[NST - 1]);
     __builtin_amdgcn_sched_barrier(0);
-    wait_vm<3 * NI, true>();          // step 0 has landed
+    wait_vm<(NST - 1) * NI, true>();  // step 0 has landed
     __builtin_amdgcn_s_barrier();
     __builtin_amdgcn_sched_barrier(0);
     read_frags(fa, st.l[0], st.r[0], o, 0);
-    if ((nkt & 3) == 0) {
-      // exact: every load is a real step; the last four steps refill nothing
-      for (int kt = 0; kt + 2 * kStages3 <= nkt; kt += kStages3) {
-        DSMOE_STEP3(0, 1, 2 * NI, true)
-        DSMOE_STEP3(1, 2, 2 * NI, true)
-        DSMOE_STEP3(2, 3, 2 * NI, true)
-        DSMOE_STEP3(3, 0, 2 * NI, true)
-      }
-      DSMOE_STEP3(0, 1, 2 * NI, false)
-      DSMOE_STEP3(1, 2, NI, false)
-      DSMOE_STEP3(2, 3, 0, false)
-      read_frags(fb, st.l[3], st.r[3], o, 1);
-      mma(acc, fa);
-      interleave();
-      __builtin_amdgcn_sched_barrier(0);
-      wait_vm<0, true>();             // own fragment reads done before the stages may be refilled
-      __builtin_amdgcn_s_barrier();
-      __builtin_amdgcn_sched_barrier(0);
-      mma(acc, fb);
+    const Loop q{acc, fa, fb, L, R, it, nkt, seg_tiles, st, o};
+    if (nkt % NST == 0) {
+      // exact: every load is a real step; the last NST steps refill nothing
+      for (int kt = 0; kt + 2 * NST <= nkt; kt += NST) steps<0, NST>(q);
+      tail<0>(q);
     } else {
       // ragged step count: loads are issued unconditionally (re-reading the last step into a stage nobody
       // reads any more), which keeps the loop free of branches and the number of loads in flight constant
       int kt = 0;
-      for (; kt + kStages3 <= nkt; kt += kStages3) {
-        DSMOE_STEP3(0, 1, 2 * NI, true)
-        DSMOE_STEP3(1, 2, 2 * NI, true)
-        DSMOE_STEP3(2, 3, 2 * NI, true)
-        DSMOE_STEP3(3, 0, 2 * NI, true)
-      }
-      if (kt < nkt) {
-        DSMOE_STEP3(0, 1, 2 * NI, true)
-        if (kt + 1 < nkt) {
-          DSMOE_STEP3(1, 2, 2 * NI, true)
-          if (kt + 2 < nkt) DSMOE_STEP3(2, 3, 2 * NI, true)
-        }
-      }
+      for (; kt + NST <= nkt; kt += NST) steps<0, NST>(q);
+      rest<0>(q, nkt - kt);
       __builtin_amdgcn_sched_barrier(0);
       wait_vm<0, true>();             // drain the re-read loads
       __builtin_amdgcn_s_barrier();
       __builtin_amdgcn_sched_barrier(0);
     }
   }
-#undef DSMOE_STEP3
 
   static __device__ __forceinline__ void mainloop(Acc& acc, const LSrc& L, const RSrc& R, int nkt, int seg_tiles,
                                                   const Stages3& st) {
@@ -344,8 +366,8 @@ struct Tile3 {
 
   // Transposed walk over the accumulators.  The MFMA leaves a lane with one row and 4 consecutive columns
   // per register quad, which makes 8-byte accesses spread over 32 rows.  Here every 32-row block of the
-  // wave goes through the wave's own slices of stages 2 and 3 (fp32, XOR-swizzled 16-byte units, no
-  // barrier needed: no other wave writes there once this wave's loads have drained; stages 0 and 1 may
+  // wave goes through the wave's own slices of the last two stages (fp32, XOR-swizzled 16-byte units, no
+  // barrier needed: no other wave writes there once this wave's loads have drained; the first stages may
   // already be receiving the next tile, see prefetch()), and comes back with
   // a lane owning 8 consecutive columns of one row: f(m, n, v) gets the tile row m, the first column n
   // (inside its source) and v[s][0..7]; 8 (NSRC = 1) or 4 (NSRC = 2) neighbouring lanes cover a row, so
@@ -360,10 +382,10 @@ struct Tile3 {
     const int wslice = wave * 2048;
     const int m = lane & 31, kg = lane >> 5;
     // the stage addresses are link-time constants: keep them as values (a table in memory would be indexed)
-    lds_char* const r0 = st.r[2];
-    lds_char* const r1 = st.r[3];
-    lds_char* const r2 = st.l[2];
-    lds_char* const r3 = st.l[3];
+    lds_char* const r0 = st.r[NST - 2];
+    lds_char* const r1 = st.r[NST - 1];
+    lds_char* const r2 = st.l[NST - 2];
+    lds_char* const r3 = st.l[NST - 1];
     auto area = [=](int row) -> lds_char* {        // 8 rows of 256 bytes in each of the four stages
       const int piece = row >> 3;
       lds_char* const lo = (piece & 1) ? r1 : r0;
@@ -412,8 +434,8 @@ struct Tile3 {
     static_assert(NOUT * NTC <= 4, "four scratch pieces per wave");
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int m = lane & 31, kg = lane >> 5;
-    lds_char* const piece[4] = {st.r[2] + wave * 2048, st.r[3] + wave * 2048, st.l[2] + wave * 2048,
-                                st.l[3] + wave * 2048};
+    lds_char* const piece[4] = {st.r[NST - 2] + wave * 2048, st.r[NST - 1] + wave * 2048,
+                                st.l[NST - 2] + wave * 2048, st.l[NST - 1] + wave * 2048};
     const int woff = m * 64 + kg * 8, wsw = (m >> 2) & 3;
     const int rrow = lane >> 2, rq = lane & 3;
 #pragma unroll
