@@ -53,6 +53,7 @@ WorkspaceLayout make_layout(const dsmoe_desc& d, size_t esize) {
   w.y_perm = take(rows * d.d_model * esize);
   const size_t dec_rows = d.dtype == DSMOE_BF16 ? (size_t)std::min<int64_t>(d.max_tokens, kDecodeMaxTokens) * E : 0;
   w.dec_info = take(32);
+  w.dec_arrivals = take(decode_arrival_slots(d) * 4);
   w.dec_p1 = take(dec_rows * 2 * d.d_ff * 4);
   w.dec_p2 = take(dec_rows * d.d_model * 4);
   w.total = o;
@@ -198,6 +199,8 @@ int32_t dsmoe_set_workspace(dsmoe_ctx* c, void* dptr, size_t bytes) {
   c->workspace_bytes = bytes;
   // the deferred status word starts cleared
   HIP_TRY(c, hipMemsetAsync(c->workspace + c->ws.err_flag, 0, 16, nullptr));
+  // arrival counters of the weight-streaming path: every call leaves them at zero again
+  HIP_TRY(c, hipMemsetAsync(c->workspace + c->ws.dec_arrivals, 0, decode_arrival_slots(c->desc) * 4, nullptr));
   HIP_TRY(c, hipStreamSynchronize(nullptr));
   return DSMOE_OK;
 }

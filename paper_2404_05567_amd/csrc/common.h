@@ -39,6 +39,7 @@ struct WorkspaceLayout {
   size_t y_perm;      // dtype [max_rows][d]
   // weight-streaming (decode) path, bf16 only
   size_t dec_info;    // i32 [8]: rows, active experts, K split of gate/up, K split of down
+  size_t dec_arrivals;   // i32 [decode_arrival_slots]: blocks that have finished a shared result; zero between calls
   size_t dec_p1;      // f32 [decode_row_cap][2 f]      K-chunk partial sums of gate | up
   size_t dec_p2;      // f32 [decode_row_cap][d]        K-chunk partial sums of the down projection
   size_t total;
@@ -63,6 +64,12 @@ struct dsmoe_ctx {
 };
 
 namespace dsmoe {
+
+// arrival counters of the decode path: one per (expert, 64-column slice of the hidden width), plus one
+// per 32-token group of the router
+inline size_t decode_arrival_slots(const dsmoe_desc& d) {
+  return (size_t)d.n_experts * ((d.d_ff + 63) / 64) + 64;
+}
 
 // rows of K-chunk partial sums the decode path may keep (K split times dispatched rows)
 inline int decode_row_cap(const dsmoe_ctx* c) {

@@ -166,9 +166,11 @@ struct Stages3 { lds_char* l[kMaxStages3]; lds_char* r[kMaxStages3]; };
   st.r[3] = (dsmoe::lds_char*)st##R3; st.r[4] = (dsmoe::lds_char*)st##R4; st.r[5] = (dsmoe::lds_char*)st##R5
 
 // NSRC = 2: the wave's two column tiles are the same 32 columns of source 0 (gate) and source 1 (up).
-template <int BM_, int BN_, int NSRC_ = 1, bool L_KMAJOR = false, bool R_KMAJOR = true, bool KTAIL = false, int NST_ = 4>
+// The block's eight waves form a WGM x WGN grid over the tile (WGN_ = 4 or 2).
+template <int BM_, int BN_, int NSRC_ = 1, bool L_KMAJOR = false, bool R_KMAJOR = true, bool KTAIL = false, int NST_ = 4,
+          int WGN_ = 4>
 struct Tile3 {
-  static constexpr int BM = BM_, BN = BN_, NSRC = NSRC_, BK = kBK2, WGM = 2, WGN = 4, NST = NST_;
+  static constexpr int BM = BM_, BN = BN_, NSRC = NSRC_, BK = kBK2, WGN = WGN_, WGM = 8 / WGN_, NST = NST_;
   static_assert(NST >= 4 && NST <= kMaxStages3, "four to six stages");
   static constexpr int WM = BM / WGM, WN = BN / WGN;
   static constexpr int MT = WM / 32, NT = WN / 32;

@@ -17,15 +17,29 @@ namespace dsmoe {
 constexpr int kRouterTokens = 32;   // tokens per block
 constexpr int kRouterRing = 16;     // K slices of X kept in flight per wave
 
+// Wave-wide reductions on the data-parallel-primitive path of the VALU (no LDS round trips): four steps
+// leave each 16-lane row's result in all of its lanes, the four row results are combined as scalars.
+template <int CTRL>
+__device__ __forceinline__ float dpp_f32(float v) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xf, 0xf, false));
+}
+constexpr int kDppSwap1 = 0xB1, kDppSwap2 = 0x4E, kDppRor4 = 0x124, kDppRor8 = 0x128;   // quad_perm / row_ror
+__device__ __forceinline__ float lane_value(float v, int lane) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), lane));
+}
 __device__ __forceinline__ float wave_max(float v) {
-#pragma unroll
-  for (int s = 32; s > 0; s >>= 1) v = fmaxf(v, __shfl_xor(v, s, 64));
-  return v;
+  v = fmaxf(v, dpp_f32<kDppSwap1>(v));
+  v = fmaxf(v, dpp_f32<kDppSwap2>(v));
+  v = fmaxf(v, dpp_f32<kDppRor4>(v));
+  v = fmaxf(v, dpp_f32<kDppRor8>(v));
+  return fmaxf(fmaxf(lane_value(v, 0), lane_value(v, 16)), fmaxf(lane_value(v, 32), lane_value(v, 48)));
 }
 __device__ __forceinline__ float wave_sum(float v) {
-#pragma unroll
-  for (int s = 32; s > 0; s >>= 1) v += __shfl_xor(v, s, 64);
-  return v;
+  v += dpp_f32<kDppSwap1>(v);
+  v += dpp_f32<kDppSwap2>(v);
+  v += dpp_f32<kDppRor4>(v);
+  v += dpp_f32<kDppRor8>(v);
+  return (lane_value(v, 0) + lane_value(v, 16)) + (lane_value(v, 32) + lane_value(v, 48));
 }
 __device__ __forceinline__ unsigned long long wave_max_u64(unsigned long long v) {
 #pragma unroll
@@ -49,9 +63,11 @@ __device__ __forceinline__ unsigned long long select_wave(float p, int lane, int
     }
     return m;
   }
-  int rank = 0;
-  for (int j = 0; j < E; ++j) {
-    const float pj = __shfl(p, j, 64);
+  int rank = 0;   // experts that precede this lane's: larger probability, or equal and lower index
+#pragma unroll
+  for (int j = 0; j < kMaxExperts; ++j) {
+    if (j >= E) break;
+    const float pj = lane_value(p, j);
     rank += (pj > p || (pj == p && j < lane)) ? 1 : 0;
   }
   return __ballot(in && rank < k);
@@ -144,7 +160,9 @@ route_kernel(const T* __restrict__ x, const T* __restrict__ w_r, const T* __rest
 }
 
 
-template <int EP>   // experts padded to 32 or 64
+// EP: experts padded to 32 or 64.  TOK: tokens per block, 32 (a full MFMA tile) or 8 (decode-sized calls: one
+// token per wave in the softmax / selection tail, and four times the blocks).
+template <int EP, int TOK>
 __global__ void __launch_bounds__(kThreads2)
 route_bf16_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ w_r, const bf16_t* __restrict__ b_r,
                   int T_tokens, int d, int E, float* __restrict__ probs, int mode, int k, float eps,
@@ -156,15 +174,15 @@ route_bf16_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ w_r, 
   constexpr int NW = kThreads2 / 64;
   extern __shared__ __align__(16) char smem[];
   char* sW = smem;                                                     // [NW][2][16 * WP]
-  float (*sPart)[kRouterTokens][EP + 1] =
-      reinterpret_cast<float (*)[kRouterTokens][EP + 1]>(smem + NW * 2 * 16 * WP);   // [NW][32][EP + 1]
+  float (*sPart)[TOK][EP + 1] =
+      reinterpret_cast<float (*)[TOK][EP + 1]>(smem + NW * 2 * 16 * WP);             // [NW][TOK][EP + 1]
 
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, r16 = lane & 15;
-  const int t0 = blockIdx.x * kRouterTokens;
+  const int t0 = blockIdx.x * TOK;
   const int S = d / 16;                                                // 16-wide K slices
   const int s_begin = wave * S / NW, s_end = (wave + 1) * S / NW;
 
-  const int trow = min(t0 + (lane & 31), T_tokens - 1);
+  const int trow = min(t0 + min(lane & 31, TOK - 1), T_tokens - 1);
   const bf16_t* xp = x + (size_t)trow * d + (lane >> 5) * 8;           // + 16 s
   // this lane's chunks of a W_r slice: chunk c = lane + 64 i -> row c / CPR, 8 experts from (c % CPR) * 8
   int w_goff[ET], w_loff[ET];
@@ -229,11 +247,12 @@ route_bf16_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ w_r, 
   for (int et = 0; et < ET; ++et)
 #pragma unroll
     for (int i = 0; i < 16; ++i)
-      sPart[wave][lane & 31][et * 32 + (i >> 2) * 8 + (lane >> 5) * 4 + (i & 3)] = acc[et][i];
+      if (TOK == 32 || (lane & 31) < TOK)
+        sPart[wave][lane & 31][et * 32 + (i >> 2) * 8 + (lane >> 5) * 4 + (i & 3)] = acc[et][i];
   __syncthreads();
 
   const float bias = (b_r != nullptr && lane < E) ? to_f32(b_r[lane]) : 0.f;
-  constexpr int TPW = kRouterTokens / NW;
+  constexpr int TPW = TOK / NW;
   for (int tt = wave * TPW; tt < wave * TPW + TPW; ++tt) {
     const int t = t0 + tt;
     if (t >= T_tokens) break;
@@ -258,21 +277,21 @@ route_bf16_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ w_r, 
   }
 }
 
-template <int EP>
+template <int EP, int TOK>
 static hipError_t launch_route_bf16(const dsmoe_ctx* c, const void* x, const void* w_r, const void* b_r, int T_tokens,
                                     float* probs, int mode, int k, float eps, uint64_t* mask, int32_t* cnt_tok,
                                     hipStream_t s) {
   constexpr int NW = kThreads2 / 64;
-  constexpr int lds = NW * 2 * 16 * (EP * 2 + 16) + NW * kRouterTokens * (EP + 1) * 4;
+  constexpr int lds = NW * 2 * 16 * (EP * 2 + 16) + NW * TOK * (EP + 1) * 4;
   static bool attr_set = false;
   if (!attr_set) {
-    if (hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&route_bf16_kernel<EP>),
+    if (hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&route_bf16_kernel<EP, TOK>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, lds))
       return e;
     attr_set = true;
   }
-  const int grid = (T_tokens + kRouterTokens - 1) / kRouterTokens;
-  route_bf16_kernel<EP><<<dim3(grid), dim3(kThreads2), lds, s>>>(
+  const int grid = (T_tokens + TOK - 1) / TOK;
+  route_bf16_kernel<EP, TOK><<<dim3(grid), dim3(kThreads2), lds, s>>>(
       (const bf16_t*)x, (const bf16_t*)w_r, (const bf16_t*)b_r, T_tokens, c->desc.d_model, c->desc.n_experts, probs,
       mode, k, eps, (unsigned long long*)mask, cnt_tok);
   return hipGetLastError();
@@ -311,9 +330,12 @@ hipError_t launch_route(const dsmoe_ctx* c, const void* x, const void* w_r, cons
                         float* probs, int mode, int k, float eps, uint64_t* mask, int32_t* cnt_tok, hipStream_t s) {
   if (T_tokens == 0) return hipSuccess;
   if (c->desc.dtype == DSMOE_BF16) {
+    const bool small = T_tokens <= kDecodeMaxTokens;
     if (c->desc.n_experts <= 32)
-      return launch_route_bf16<32>(c, x, w_r, b_r, T_tokens, probs, mode, k, eps, mask, cnt_tok, s);
-    return launch_route_bf16<64>(c, x, w_r, b_r, T_tokens, probs, mode, k, eps, mask, cnt_tok, s);
+      return small ? launch_route_bf16<32, 8>(c, x, w_r, b_r, T_tokens, probs, mode, k, eps, mask, cnt_tok, s)
+                   : launch_route_bf16<32, 32>(c, x, w_r, b_r, T_tokens, probs, mode, k, eps, mask, cnt_tok, s);
+    return small ? launch_route_bf16<64, 8>(c, x, w_r, b_r, T_tokens, probs, mode, k, eps, mask, cnt_tok, s)
+                 : launch_route_bf16<64, 32>(c, x, w_r, b_r, T_tokens, probs, mode, k, eps, mask, cnt_tok, s);
   }
   return launch_route_t<float>(c, x, w_r, b_r, T_tokens, probs, mode, k, eps, mask, cnt_tok, s);
 }
