@@ -37,36 +37,95 @@ dispatch_hist_kernel(const unsigned long long* __restrict__ mask, int T, int E, 
   }
 }
 
-__global__ void __launch_bounds__(kDB)
+// One block per 256 tokens, 1024 threads: the first four waves hold one token per lane (ballots, scans), then
+// four threads share a token and walk its experts, every probability read of a thread in flight at once.
+constexpr int kScatterThreads = 4 * kDB;
+__global__ void __launch_bounds__(kScatterThreads)
 dispatch_scatter_kernel(const unsigned long long* __restrict__ mask, const float* __restrict__ probs, int T, int E,
                         const int32_t* __restrict__ blk_cnt, const int32_t* __restrict__ blk_tok, long long max_rows,
                         int32_t* __restrict__ expert_off, int32_t* __restrict__ row_token, float* __restrict__ row_weight,
                         int32_t* __restrict__ tok_off, int32_t* __restrict__ tok_rows, int32_t* __restrict__ nnz_out,
                         int32_t* __restrict__ err_flag) {
+  constexpr int NW = kScatterThreads / 64;
   __shared__ int sRowBase[kMaxExperts];    // first row of this block's tokens inside each expert
-  __shared__ int sWave[4][kMaxExperts];    // per-wave expert counts
+  __shared__ int sWave[4][kMaxExperts];    // per-wave expert counts (token waves)
   __shared__ int sWaveTok[4];
   __shared__ int sTokBase, sNnz;
+  __shared__ int sPartTotal[NW][64], sPartBefore[NW][64], sPartTok[NW];
+  __shared__ unsigned long long sBits[4][kMaxExperts];   // per token wave and expert: which tokens selected it
+  __shared__ unsigned long long sMask[kDB];
+  __shared__ int sTokOff[kDB];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int nblk = gridDim.x, b = blockIdx.x;
 
-  if (threadIdx.x < 64) {
+  // column sums of the histogram table: wave w adds blocks w, w + NW, ... (eight reads in flight)
+  {
     int total = 0, before = 0;
-    if (lane < E)
-      for (int bb = 0; bb < nblk; ++bb) {
-        const int c = blk_cnt[(size_t)bb * E + lane];
-        total += c;
-        if (bb < b) before += c;
+    for (int bb0 = wave; bb0 < nblk; bb0 += NW * 8) {
+      int cv[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const int bb = bb0 + NW * u;
+        cv[u] = (bb < nblk && lane < E) ? blk_cnt[(size_t)bb * E + lane] : 0;
       }
-    int incl = total;
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        total += cv[u];
+        if (bb0 + NW * u < b) before += cv[u];
+      }
+    }
+    sPartTotal[wave][lane] = total;
+    sPartBefore[wave][lane] = before;
+    int tb = 0;
+    for (int bb = threadIdx.x; bb < b; bb += kScatterThreads) tb += blk_tok[bb];
+#pragma unroll
+    for (int s = 32; s > 0; s >>= 1) tb += __shfl_xor(tb, s, 64);
+    if (lane == 0) sPartTok[wave] = tb;
+  }
+
+  // token waves: one token per lane
+  const int t = b * kDB + threadIdx.x;
+  int cnt = 0, incl = 0;
+  if (wave < 4) {
+    const unsigned long long m = t < T ? mask[t] : 0ull;
+    int mine = 0;
+    for (int e = 0; e < E; ++e) {
+      const unsigned long long bits = __ballot((m >> e) & 1ull);
+      if (lane == e) {
+        mine = __popcll(bits);
+        sBits[wave][e] = bits;
+      }
+    }
+    sWave[wave][lane] = mine;
+    sMask[threadIdx.x] = m;
+    cnt = __popcll(m);
+    incl = cnt;                            // inclusive scan of the per-token counts inside the wave
 #pragma unroll
     for (int s = 1; s < 64; s <<= 1) {
       const int o = __shfl_up(incl, s, 64);
       if (lane >= s) incl += o;
     }
-    const int nnz = __shfl(incl, 63, 64);
+    if (lane == 63) sWaveTok[wave] = incl;
+  }
+  __syncthreads();
+
+  if (threadIdx.x < 64) {
+    int total = 0, before = 0, tb = 0;
+#pragma unroll
+    for (int w = 0; w < NW; ++w) {
+      total += sPartTotal[w][lane];
+      before += sPartBefore[w][lane];
+      tb += sPartTok[w];
+    }
+    int inc = total;
+#pragma unroll
+    for (int s = 1; s < 64; s <<= 1) {
+      const int o = __shfl_up(inc, s, 64);
+      if (lane >= s) inc += o;
+    }
+    const int nnz = __shfl(inc, 63, 64);
     const bool overflow = (long long)nnz > max_rows;
-    const int off = overflow ? 0 : incl - total;
+    const int off = overflow ? 0 : inc - total;
     if (lane < E) sRowBase[lane] = off + before;
     if (b == 0) {
       if (lane < E) expert_off[lane] = off;
@@ -76,50 +135,46 @@ dispatch_scatter_kernel(const unsigned long long* __restrict__ mask, const float
         if (overflow) err_flag[0] = DSMOE_ERR_CAPACITY;
       }
     }
-    if (lane == 0) sNnz = overflow ? -1 : nnz;
-  } else if (threadIdx.x < 128) {
-    int before = 0;
-    for (int bb = lane; bb < b; bb += 64) before += blk_tok[bb];
-#pragma unroll
-    for (int s = 32; s > 0; s >>= 1) before += __shfl_xor(before, s, 64);
-    if (lane == 0) sTokBase = before;
+    if (lane == 0) {
+      sNnz = overflow ? -1 : nnz;
+      sTokBase = tb;
+    }
   }
-
-  const int t = b * kDB + threadIdx.x;
-  const unsigned long long m = t < T ? mask[t] : 0ull;
-  const unsigned long long lt = (1ull << lane) - 1ull;
-  int mine = 0;
-  for (int e = 0; e < E; ++e) {
-    const int c = __popcll(__ballot((m >> e) & 1ull));
-    if (lane == e) mine = c;
-  }
-  sWave[wave][lane] = mine;
-  // exclusive scan of the per-token counts inside the wave
-  const int cnt = __popcll(m);
-  int incl = cnt;
-#pragma unroll
-  for (int s = 1; s < 64; s <<= 1) {
-    const int o = __shfl_up(incl, s, 64);
-    if (lane >= s) incl += o;
-  }
-  if (lane == 63) sWaveTok[wave] = incl;
   __syncthreads();
 
   const bool overflow = sNnz < 0;
-  int tbase = overflow ? 0 : sTokBase + incl - cnt;
-  for (int w = 0; w < wave; ++w) tbase += overflow ? 0 : sWaveTok[w];
-  if (t < T) tok_off[t] = tbase;
-  if (t == T - 1) tok_off[T] = overflow ? 0 : sNnz;
+  if (wave < 4) {
+    int tbase = overflow ? 0 : sTokBase + incl - cnt;
+    for (int w = 0; w < wave; ++w) tbase += overflow ? 0 : sWaveTok[w];
+    sTokOff[threadIdx.x] = tbase;
+    if (t < T) tok_off[t] = tbase;
+    if (t == T - 1) tok_off[T] = overflow ? 0 : sNnz;
+  }
   if (overflow) return;
+  __syncthreads();
 
-  for (int e = 0; e < E; ++e) {
-    const unsigned long long bits = __ballot((m >> e) & 1ull);
-    if ((m >> e) & 1ull) {
-      int row = sRowBase[e] + __popcll(bits & lt);
-      for (int w = 0; w < wave; ++w) row += sWave[w][e];
-      row_token[row] = t;
-      row_weight[row] = probs[(size_t)t * E + e];
-      tok_rows[tbase + __popcll(m & ((1ull << e) - 1ull))] = row;
+  // Thread (token tl, quarter q) owns experts q, q + 4, ...  A pair's row is the block's base inside the
+  // expert plus the number of earlier tokens of the block that selected the expert (from the ballots).
+  const int tl = threadIdx.x >> 2, q = threadIdx.x & 3, tg = b * kDB + tl;
+  const unsigned long long mt = sMask[tl];    // 0 beyond T
+  float pv[kMaxExperts / 4];
+#pragma unroll
+  for (int j = 0; j < kMaxExperts / 4; ++j) {
+    const int e = q + 4 * j;
+    pv[j] = (e < E && ((mt >> e) & 1ull)) ? probs[(size_t)tg * E + e] : 0.f;
+  }
+  const int tw = tl >> 6;
+  const unsigned long long below = (1ull << (tl & 63)) - 1ull;
+  const int tbase = sTokOff[tl];
+#pragma unroll
+  for (int j = 0; j < kMaxExperts / 4; ++j) {
+    const int e = q + 4 * j;
+    if (e < E && ((mt >> e) & 1ull)) {
+      int row = sRowBase[e] + __popcll(sBits[tw][e] & below);
+      for (int w = 0; w < tw; ++w) row += sWave[w][e];
+      row_token[row] = tg;
+      row_weight[row] = pv[j];
+      tok_rows[tbase + __popcll(mt & ((1ull << e) - 1ull))] = row;
     }
   }
 }
@@ -158,7 +213,7 @@ hipError_t launch_dispatch(const dsmoe_ctx* c, const void* x, const float* probs
                      blk_cnt, blk_tok);
   hipError_t err = hipGetLastError();
   if (err != hipSuccess) return err;
-  hipLaunchKernelGGL(dispatch_scatter_kernel, dim3(nblk), dim3(kDB), 0, s, (const unsigned long long*)mask, probs, T,
+  hipLaunchKernelGGL(dispatch_scatter_kernel, dim3(nblk), dim3(kScatterThreads), 0, s, (const unsigned long long*)mask, probs, T,
                      E, blk_cnt, blk_tok, (long long)c->desc.max_rows, expert_off, row_token, row_weight, tok_off,
                      tok_rows, nnz, err_flag);
   err = hipGetLastError();

@@ -330,12 +330,15 @@ hipError_t launch_route(const dsmoe_ctx* c, const void* x, const void* w_r, cons
                         float* probs, int mode, int k, float eps, uint64_t* mask, int32_t* cnt_tok, hipStream_t s) {
   if (T_tokens == 0) return hipSuccess;
   if (c->desc.dtype == DSMOE_BF16) {
-    const bool small = T_tokens <= kDecodeMaxTokens;
+    // tokens per block: as few as still give at most one block per CU (a shorter selection tail); a full
+    // tile for large calls, since every block reads all of W_r and issues the same loads whatever its tokens
+    const int tok = T_tokens <= 8 * c->n_cu ? 8 : T_tokens <= 16 * c->n_cu ? 16 : 32;
+#define DSMOE_ROUTE_BF16(EP, TOK) \
+  launch_route_bf16<EP, TOK>(c, x, w_r, b_r, T_tokens, probs, mode, k, eps, mask, cnt_tok, s)
     if (c->desc.n_experts <= 32)
-      return small ? launch_route_bf16<32, 8>(c, x, w_r, b_r, T_tokens, probs, mode, k, eps, mask, cnt_tok, s)
-                   : launch_route_bf16<32, 32>(c, x, w_r, b_r, T_tokens, probs, mode, k, eps, mask, cnt_tok, s);
-    return small ? launch_route_bf16<64, 8>(c, x, w_r, b_r, T_tokens, probs, mode, k, eps, mask, cnt_tok, s)
-                 : launch_route_bf16<64, 32>(c, x, w_r, b_r, T_tokens, probs, mode, k, eps, mask, cnt_tok, s);
+      return tok == 8 ? DSMOE_ROUTE_BF16(32, 8) : tok == 16 ? DSMOE_ROUTE_BF16(32, 16) : DSMOE_ROUTE_BF16(32, 32);
+    return tok == 8 ? DSMOE_ROUTE_BF16(64, 8) : tok == 16 ? DSMOE_ROUTE_BF16(64, 16) : DSMOE_ROUTE_BF16(64, 32);
+#undef DSMOE_ROUTE_BF16
   }
   return launch_route_t<float>(c, x, w_r, b_r, T_tokens, probs, mode, k, eps, mask, cnt_tok, s);
 }
