@@ -235,6 +235,9 @@ def main():
     ap.add_argument("--workloads", default="c2,c3,c4,c5",
                     help="comma-separated subset of c2,c3,c4,c5 (c2 is the headline and always runs)")
     ap.add_argument("--cpu-passes", type=int, default=20, help="0 skips the CPU baseline")
+    ap.add_argument("--copy-calibration", type=int, default=0, metavar="MiB",
+                    help="also run three plain device copies of this many MiB (a kernel of known HBM traffic, "
+                         "used to scale rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU (no collectives, no sharding); use --gpus 1")
@@ -247,6 +250,14 @@ def main():
     dsmoe.load_library()   # no fallback: raises if the HIP library is missing
     wl = set(args.workloads.split(","))
     b = Bench()
+
+    if args.copy_calibration > 0:
+        src = torch.empty(args.copy_calibration << 20, dtype=torch.uint8, device="cuda:0").fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     head, inp, cfg = b.sparse_prefill("c2", args.steps, args.warmup, keep_inputs=True)
     side_steps = max(5, min(args.steps, 20))

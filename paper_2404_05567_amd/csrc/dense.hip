@@ -43,22 +43,26 @@ SavedLayout saved_layout(const dsmoe_ctx* c, int T) {
 
 constexpr int kWrTokens = 256;   // tokens per slab of the router weight-gradient kernel
 
-struct ScratchLayout { size_t zeros, dU, dG, dS_part, dZ, dZt, WrP, dWr_part, total; int ntb, nsplit, EP; };
+// dU and dG are [T][E f + EP] matrices: the EP pad columns of dG hold dZ in the storage type, so that the
+// router term of dX is one more K segment of the dG rows; W_r is repacked as [d][f] (first EP columns used)
+// so that its rows have the pitch of the expert weights' rows.
+struct ScratchLayout { size_t zeros, dU, dG, dS_part, dZ, WrP, dWr_part, total; int ntb, nsplit, EP; size_t ldg; };
 ScratchLayout scratch_layout(const dsmoe_ctx* c, int T) {
-  const size_t E = c->desc.n_experts, n = (size_t)T * E, nf = n * c->desc.d_ff * c->esize;
+  const size_t E = c->desc.n_experts, n = (size_t)T * E;
   const int bn1 = c->desc.dtype == DSMOE_BF16 ? DenseTiles<bf16_t>::BN1 : DenseTiles<float>::BN1;
   ScratchLayout l;
   l.ntb = (c->desc.d_ff + bn1 - 1) / bn1;
   l.nsplit = std::max(1, (T + kWrTokens - 1) / kWrTokens);
+  l.EP = (c->desc.n_experts + 31) / 32 * 32;   // the router term of dX runs through the MFMA core: K padded to 32
+  l.ldg = E * c->desc.d_ff + l.EP;
+  const size_t nf = (size_t)T * l.ldg * c->esize;
   size_t o = 0;
   l.zeros = o; o = al256(o + 256);   // read in place of token rows past T by the token-contracted products
   l.dU = o; o = al256(o + nf);
   l.dG = o; o = al256(o + nf);
   l.dS_part = o; o = al256(o + n * l.ntb * 4);
   l.dZ = o; o = al256(o + n * 4);
-  l.EP = (c->desc.n_experts + 31) / 32 * 32;   // the router term of dX runs through the MFMA core: K padded to 32
-  l.dZt = o; o = al256(o + (size_t)T * l.EP * c->esize);
-  l.WrP = o; o = al256(o + (size_t)c->desc.d_model * l.EP * c->esize);
+  l.WrP = o; o = al256(o + (size_t)c->desc.d_model * c->desc.d_ff * c->esize);
   l.dWr_part = o; o = al256(o + (size_t)l.nsplit * c->desc.d_model * E * 4);
   l.total = o;
   return l;
@@ -140,7 +144,7 @@ template <typename T>
 __global__ void __launch_bounds__((Gemm<T, DenseTiles<T>::BM, DenseTiles<T>::BN1, 1, false, false>::THREADS))
 dense_bwd_dh_kernel(const T* __restrict__ d_out, const T* __restrict__ w_down, const float* __restrict__ S,
                     const T* __restrict__ G, const T* __restrict__ U, T* __restrict__ dU, T* __restrict__ dG,
-                    float* __restrict__ dS_part, int Tn, int d, int f, int E) {
+                    float* __restrict__ dS_part, int Tn, int d, int f, int E, size_t ldg) {
   typedef Gemm<T, DenseTiles<T>::BM, DenseTiles<T>::BN1, 1, false, false> GM;
   DSMOE_GEMM_STAGES(GM, st);
   __shared__ float red[GM::WAVES_N][GM::BM];
@@ -173,7 +177,7 @@ dense_bwd_dh_kernel(const T* __restrict__ d_out, const T* __restrict__ w_down, c
       const int t = t0 + m, col = n0 + n;
       if (t >= Tn || col >= f) return;
       const float s = S[(size_t)t * E + e];
-      const size_t o = (size_t)t * EF + (size_t)e * f + col;
+      const size_t o = (size_t)t * EF + (size_t)e * f + col, od = (size_t)t * ldg + (size_t)e * f + col;
       float g[GM::CHUNK], u[GM::CHUNK], du[GM::CHUNK], dg[GM::CHUNK];
       load_chunk(G + o, g);
       load_chunk(U + o, u);
@@ -185,8 +189,8 @@ dense_bwd_dh_kernel(const T* __restrict__ d_out, const T* __restrict__ w_down, c
         du[i] = dh * sl;
         dg[i] = dh * u[i] * (sg * (1.f + g[i] * (1.f - sg)));
       }
-      store_chunk(dU + o, du);
-      store_chunk(dG + o, dg);
+      store_chunk(dU + od, du);
+      store_chunk(dG + od, dg);
     });
     flush();
     __syncthreads();
@@ -237,11 +241,10 @@ template <typename T>
 __global__ void __launch_bounds__((Gemm<T, DenseTiles<T>::BM, DenseTiles<T>::BN2, 2, true, true, true>::THREADS))
 dense_bwd_dwgu_kernel(const T* __restrict__ x, const T* __restrict__ dG, const T* __restrict__ dU,
                       float* __restrict__ dw_gate, float* __restrict__ dw_up, int Tn, int d, int f, int E,
-                      const void* __restrict__ zeros) {
+                      size_t ldg, const void* __restrict__ zeros) {
   typedef Gemm<T, DenseTiles<T>::BM, DenseTiles<T>::BN2, 2, true, true, true> GM;
   DSMOE_GEMM_STAGES(GM, st);
   const int n_mt = (d + GM::BM - 1) / GM::BM, n_nt = (f + GM::BN - 1) / GM::BN;
-  const size_t EF = (size_t)E * f;
   TileWalker tw;
   tw.init(E * n_mt * n_nt);
   int idx;
@@ -252,7 +255,7 @@ dense_bwd_dwgu_kernel(const T* __restrict__ x, const T* __restrict__ dG, const T
     GM::l_cols(L, x + m0, d, d - m0, Tn, zeros);
     typename GM::RSrc R;
     const T* const base[2] = {dG + (size_t)e * f + n0, dU + (size_t)e * f + n0};
-    GM::r_cols(R, base, EF, f - n0, Tn, zeros);
+    GM::r_cols(R, base, ldg, f - n0, Tn, zeros);
     typename GM::Acc acc;
     GM::zero(acc);
     GM::mainloop(acc, L, R, (Tn + GM::BK - 1) / GM::BK, 1 << 30, st);
@@ -269,12 +272,13 @@ dense_bwd_dwgu_kernel(const T* __restrict__ x, const T* __restrict__ dG, const T
 template <typename T>
 __global__ void __launch_bounds__((Gemm<T, DenseTiles<T>::BM, DenseTiles<T>::BN1, 1, false, false>::THREADS))
 dense_bwd_dx_kernel(const T* __restrict__ dU, const T* __restrict__ dG, const T* __restrict__ w_up,
-                    const T* __restrict__ w_gate, const T* __restrict__ dZt, const T* __restrict__ w_rp,
-                    T* __restrict__ dx, int Tn, int d, int f, int E, int EP) {
+                    const T* __restrict__ w_gate, const T* __restrict__ w_rp, T* __restrict__ dx, int Tn, int d, int f,
+                    int E, int EP, size_t ldg) {
   typedef Gemm<T, DenseTiles<T>::BM, DenseTiles<T>::BN1, 1, false, false> GM;
   DSMOE_GEMM_STAGES(GM, st);
   const int n_mt = (Tn + GM::BM - 1) / GM::BM, n_nt = (d + GM::BN - 1) / GM::BN;
   const size_t EF = (size_t)E * f;
+  const T* dZt = dG + EF;   // the pad columns of dG
   TileWalker tw;
   tw.init(n_mt * n_nt);
   int idx;
@@ -283,22 +287,40 @@ dense_bwd_dx_kernel(const T* __restrict__ dU, const T* __restrict__ dG, const T*
     const int t0 = mt * GM::BM, n0 = nt * GM::BN;
     typename GM::Acc acc;
     GM::zero(acc);
-#pragma unroll 1
-    for (int part = 0; part < 3; ++part) {
+    if constexpr (std::is_same<T, bf16_t>::value) {
+      // One K loop over 2 E + 1 segments: dU_j W_up[j]^T (j < E), dG_j W_gate[j]^T, then the router term
+      // dZ W_r^T.  The token side runs on from dU into dG (segment E) and on into dG's pad columns; the weight
+      // side runs on from W_up into W_gate and then into the repacked W_r: the row pitches are the same, so
+      // each switch is a uniform address offset.
       typename GM::LSrc L;
       typename GM::RSrc R;
-      if (part < 2) {
-        // K runs over (expert, hidden unit): one segment of f per expert on both sides
-        const T* a = part ? dG : dU;
-        const T* w = part ? w_gate : w_up;
-        GM::l_rows(L, min(GM::BM, Tn - t0), (size_t)f * sizeof(T), [&](int r) { return a + (size_t)(t0 + r) * EF; });
-        GM::r_rows(R, min(GM::BN, d - n0), (size_t)d * f * sizeof(T), [&](int r) { return w + (size_t)(n0 + r) * f; });
-        GM::mainloop(acc, L, R, (int)(EF / GM::BK), f / GM::BK, st);
-      } else {
-        // router path: K runs over the (padded) experts
-        GM::l_rows(L, min(GM::BM, Tn - t0), 0, [&](int r) { return dZt + (size_t)(t0 + r) * EP; });
-        GM::r_rows(R, min(GM::BN, d - n0), 0, [&](int r) { return w_rp + (size_t)(n0 + r) * EP; });
-        GM::mainloop(acc, L, R, EP / GM::BK, 1 << 30, st);
+      const long long segL = (long long)f * sizeof(T), segR = (long long)d * f * sizeof(T);
+      GM::l_rows(L, min(GM::BM, Tn - t0), (size_t)segL, [&](int r) { return dU + (size_t)(t0 + r) * ldg; });
+      GM::r_rows(R, min(GM::BN, d - n0), (size_t)segR, [&](int r) { return w_up + (size_t)(n0 + r) * f; });
+      const long long dL = (const char*)dG - (const char*)dU, dR1 = (const char*)w_gate - (const char*)w_up,
+                      dR2 = (const char*)w_rp - (const char*)w_up;
+      L.set_jump(0, E, dL - E * segL);
+      R.set_jump(0, E, dR1 - E * segR);
+      R.set_jump(1, 2 * E, dR2 - dR1 - E * segR);
+      GM::mainloop(acc, L, R, 2 * (int)(EF / GM::BK) + EP / GM::BK, f / GM::BK, st);
+    } else {
+#pragma unroll 1
+      for (int part = 0; part < 3; ++part) {
+        typename GM::LSrc L;
+        typename GM::RSrc R;
+        if (part < 2) {
+          // K runs over (expert, hidden unit): one segment of f per expert on both sides
+          const T* a = part ? dG : dU;
+          const T* w = part ? w_gate : w_up;
+          GM::l_rows(L, min(GM::BM, Tn - t0), (size_t)f * sizeof(T), [&](int r) { return a + (size_t)(t0 + r) * ldg; });
+          GM::r_rows(R, min(GM::BN, d - n0), (size_t)d * f * sizeof(T), [&](int r) { return w + (size_t)(n0 + r) * f; });
+          GM::mainloop(acc, L, R, (int)(EF / GM::BK), f / GM::BK, st);
+        } else {
+          // router path: K runs over the (padded) experts
+          GM::l_rows(L, min(GM::BM, Tn - t0), 0, [&](int r) { return dZt + (size_t)(t0 + r) * ldg; });
+          GM::r_rows(R, min(GM::BN, d - n0), 0, [&](int r) { return w_rp + (size_t)(n0 + r) * f; });
+          GM::mainloop(acc, L, R, EP / GM::BK, 1 << 30, st);
+        }
       }
     }
     GM::for_each_chunk(acc, st, [&](int m, int n, const float (&v)[1][GM::CHUNK]) {
@@ -313,7 +335,7 @@ dense_bwd_dx_kernel(const T* __restrict__ dU, const T* __restrict__ dG, const T*
 template <typename T>
 __global__ void __launch_bounds__(kThreads)
 dense_softmax_bwd_kernel(const float* __restrict__ S, const float* __restrict__ dS_part, int ntb, int Tn, int E, int EP,
-                         float* __restrict__ dZ, T* __restrict__ dZt, unsigned* __restrict__ zeros) {
+                         float* __restrict__ dZ, T* __restrict__ dZt, size_t ldz, unsigned* __restrict__ zeros) {
   if (blockIdx.x == 0 && threadIdx.x < 64) zeros[threadIdx.x] = 0u;   // the zero page of the later kernels
   const int lane = threadIdx.x & 63;
   const int t = blockIdx.x * 4 + (threadIdx.x >> 6);
@@ -328,15 +350,15 @@ dense_softmax_bwd_kernel(const float* __restrict__ S, const float* __restrict__ 
   for (int o = 32; o > 0; o >>= 1) dot += __shfl_xor(dot, o, 64);
   const float dz = s * (ds - dot);
   if (lane < E) dZ[(size_t)t * E + lane] = dz;
-  if (lane < EP) dZt[(size_t)t * EP + lane] = (T)(lane < E ? dz : 0.f);
+  if (lane < EP) dZt[(size_t)t * ldz + lane] = (T)(lane < E ? dz : 0.f);
 }
 
 // ---- router weight gradient: partial dW_r = X^T dZ over a slab of tokens, through the MFMA core ---------------
 // (dZ in the storage type, padded to EP columns); the slabs are added in order by the reduce kernel.
 template <typename T>
 __global__ void __launch_bounds__((Gemm<T, DenseTiles<T>::BM, DenseTiles<T>::BN1, 1, true, true, true>::THREADS))
-dense_router_dw_kernel(const T* __restrict__ x, const T* __restrict__ dZt, int Tn, int d, int E, int EP, int nsplit,
-                       float* __restrict__ dWr_part, const void* __restrict__ zeros) {
+dense_router_dw_kernel(const T* __restrict__ x, const T* __restrict__ dZt, size_t ldz, int Tn, int d, int E, int EP,
+                       int nsplit, float* __restrict__ dWr_part, const void* __restrict__ zeros) {
   typedef Gemm<T, DenseTiles<T>::BM, DenseTiles<T>::BN1, 1, true, true, true> GM;
   DSMOE_GEMM_STAGES(GM, st);
   const int n_mt = (d + GM::BM - 1) / GM::BM;
@@ -349,8 +371,8 @@ dense_router_dw_kernel(const T* __restrict__ x, const T* __restrict__ dZt, int T
     typename GM::LSrc L;
     GM::l_cols(L, x + (size_t)k0 * d + m0, d, d - m0, kv, zeros);
     typename GM::RSrc R;
-    const T* const base[1] = {dZt + (size_t)k0 * EP};
-    GM::r_cols(R, base, EP, EP, kv, zeros);
+    const T* const base[1] = {dZt + (size_t)k0 * ldz};
+    GM::r_cols(R, base, ldz, EP, kv, zeros);
     typename GM::Acc acc;
     GM::zero(acc);
     GM::mainloop(acc, L, R, (kv + GM::BK - 1) / GM::BK, 1 << 30, st);
@@ -387,14 +409,14 @@ dense_router_db_kernel(const float* __restrict__ dZ, int Tn, int E, float* __res
   if (threadIdx.x == 0) db_r[e] = sSum[0];
 }
 
-// w_rp[i][0..EP) = w_r[i][0..E) followed by zeros
+// w_rp[i][0..EP) = w_r[i][0..E) followed by zeros; rows of pitch ld
 template <typename T>
 __global__ void __launch_bounds__(kThreads)
-dense_pad_wr_kernel(const T* __restrict__ w_r, int d, int E, int EP, T* __restrict__ w_rp) {
+dense_pad_wr_kernel(const T* __restrict__ w_r, int d, int E, int EP, int ld, T* __restrict__ w_rp) {
   const int i = blockIdx.x * kThreads + threadIdx.x;
   if (i >= d * EP) return;
   const int row = i / EP, e = i % EP;
-  w_rp[i] = e < E ? w_r[(size_t)row * E + e] : (T)0.f;
+  w_rp[(size_t)row * ld + e] = e < E ? w_r[(size_t)row * E + e] : (T)0.f;
 }
 
 template <typename K>
@@ -446,7 +468,7 @@ hipError_t dense_bwd_t(const dsmoe_ctx* c, const void* x, const void* w_r, const
   T* dG = reinterpret_cast<T*>(scratch + sc.dG);
   float* dS_part = reinterpret_cast<float*>(scratch + sc.dS_part);
   float* dZ = reinterpret_cast<float*>(scratch + sc.dZ);
-  T* dZt = reinterpret_cast<T*>(scratch + sc.dZt);
+  T* dZt = dG + (size_t)E * f;   // the pad columns of dG, row pitch sc.ldg
   T* w_rp = reinterpret_cast<T*>(scratch + sc.WrP);
   float* dWr_part = reinterpret_cast<float*>(scratch + sc.dWr_part);
   auto cdiv = [](long a, long b) { return (a + b - 1) / b; };
@@ -463,19 +485,19 @@ hipError_t dense_bwd_t(const dsmoe_ctx* c, const void* x, const void* w_r, const
 
   long tiles = E * cdiv(Tn, DT::BM) * cdiv(f, DT::BN1);
   dense_bwd_dh_kernel<T><<<dim3(grid_for(c, tiles, bpc)), dim3(GRR::THREADS), GRR::LDS_BYTES, s>>>(
-      (const T*)d_out, (const T*)w_down, S, G, U, dU, dG, dS_part, Tn, d, f, E);
+      (const T*)d_out, (const T*)w_down, S, G, U, dU, dG, dS_part, Tn, d, f, E, sc.ldg);
   if (hipError_t e = hipGetLastError()) return e;
 
-  dense_softmax_bwd_kernel<T><<<dim3((Tn + 3) / 4), dim3(kThreads), 0, s>>>(S, dS_part, sc.ntb, Tn, E, sc.EP, dZ, dZt,
-                                                                                  reinterpret_cast<unsigned*>(scratch + sc.zeros));
+  dense_softmax_bwd_kernel<T><<<dim3((Tn + 3) / 4), dim3(kThreads), 0, s>>>(
+      S, dS_part, sc.ntb, Tn, E, sc.EP, dZ, dZt, sc.ldg, reinterpret_cast<unsigned*>(scratch + sc.zeros));
   if (hipError_t e = hipGetLastError()) return e;
 
-  dense_pad_wr_kernel<T><<<dim3((d * sc.EP + kThreads - 1) / kThreads), dim3(kThreads), 0, s>>>((const T*)w_r, d, E, sc.EP,
-                                                                                               w_rp);
+  dense_pad_wr_kernel<T><<<dim3((d * sc.EP + kThreads - 1) / kThreads), dim3(kThreads), 0, s>>>(
+      (const T*)w_r, d, E, sc.EP, f, w_rp);
   if (hipError_t e = hipGetLastError()) return e;
   tiles = cdiv(d, DT::BM) * sc.nsplit;
   dense_router_dw_kernel<T><<<dim3(grid_for(c, tiles, bpc)), dim3(GCC1::THREADS), GCC1::LDS_BYTES, s>>>(
-      (const T*)x, dZt, Tn, d, E, sc.EP, sc.nsplit, dWr_part, scratch + sc.zeros);
+      (const T*)x, dZt, sc.ldg, Tn, d, E, sc.EP, sc.nsplit, dWr_part, scratch + sc.zeros);
   if (hipError_t e = hipGetLastError()) return e;
   dense_router_dw_reduce_kernel<<<dim3((d * E + kThreads - 1) / kThreads), dim3(kThreads), 0, s>>>(dWr_part, sc.nsplit,
                                                                                                   d * E, dw_r);
@@ -492,12 +514,12 @@ hipError_t dense_bwd_t(const dsmoe_ctx* c, const void* x, const void* w_r, const
 
   tiles = E * cdiv(d, DT::BM) * cdiv(f, DT::BN2);
   dense_bwd_dwgu_kernel<T><<<dim3(grid_for(c, tiles, bpc)), dim3(GCC2::THREADS), GCC2::LDS_BYTES, s>>>(
-      (const T*)x, dG, dU, dw_gate, dw_up, Tn, d, f, E, scratch + sc.zeros);
+      (const T*)x, dG, dU, dw_gate, dw_up, Tn, d, f, E, sc.ldg, scratch + sc.zeros);
   if (hipError_t e = hipGetLastError()) return e;
 
   tiles = cdiv(Tn, DT::BM) * cdiv(d, DT::BN1);
   dense_bwd_dx_kernel<T><<<dim3(grid_for(c, tiles, bpc)), dim3(GRR::THREADS), GRR::LDS_BYTES, s>>>(
-      dU, dG, (const T*)w_up, (const T*)w_gate, dZt, w_rp, (T*)dx, Tn, d, f, E, sc.EP);
+      dU, dG, (const T*)w_up, (const T*)w_gate, w_rp, (T*)dx, Tn, d, f, E, sc.EP, sc.ldg);
   return hipGetLastError();
 }
 

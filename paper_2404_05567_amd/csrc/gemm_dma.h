@@ -58,11 +58,17 @@ struct DRows {
   static constexpr int NI = CPW;
   const char* p[CPW];   // this lane's piece of each of its chunks, K segment 0, step 0
   size_t seg_stride;    // bytes between K segments
+  // K segments may continue in another matrix with the same row pitch: from segment brk[i] on, jump[i] bytes
+  // are added to every address (uniform values: the switch costs scalar instructions only)
+  int brk[2];
+  long long jump[2];
 
   // row_base(r): address of element [row r][k = 0]; rows >= valid re-read row valid - 1
   template <class F>
   __device__ __forceinline__ void init(int valid, size_t seg_stride_bytes, F row_base) {
     seg_stride = seg_stride_bytes;
+    brk[0] = brk[1] = 0x7fffffff;
+    jump[0] = jump[1] = 0;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
 #pragma unroll
     for (int i = 0; i < CPW; ++i) {
@@ -71,8 +77,14 @@ struct DRows {
       p[i] = reinterpret_cast<const char*>(row_base(min(r, valid - 1))) + kc * 16;
     }
   }
+  // segments >= at continue at (address of segment `at` in the new matrix) = old address + bytes
+  __device__ __forceinline__ void set_jump(int i, int at, long long bytes) {
+    brk[i] = at;
+    jump[i] = bytes;
+  }
   __device__ __forceinline__ void issue(lds_char* stage, int seg, int kin) const {
-    const size_t off = (size_t)seg * seg_stride + (size_t)kin * 64;
+    const long long off = (long long)seg * (long long)seg_stride + (long long)kin * 64 +
+                          (seg >= brk[0] ? jump[0] : 0ll) + (seg >= brk[1] ? jump[1] : 0ll);
     lds_char* dst = stage + (threadIdx.x >> 6) * (CPW * 1024);
 #pragma unroll
     for (int i = 0; i < CPW; ++i) dma16(p[i] + off, dst + i * 1024);
