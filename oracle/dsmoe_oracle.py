@@ -106,6 +106,11 @@ def threshold_topk_k(S, eps: float) -> int:
     return int(min(max(np.floor(mean + 0.5), 1), M.shape[1]))
 
 
+def select_threshold_topk(S, eps: float) -> np.ndarray:
+    """Threshold-TopK selection (Sec. 4.3): top-K with the K that the threshold gives on this batch."""
+    return select_topk(S, threshold_topk_k(S, eps))
+
+
 # --------------------------------------------------------------------------------------------------
 # Dispatch bookkeeping ("duplication of intermediate tokens", Sec. 4.4): the grouping of
 # (token, expert) pairs by expert.  Canonical order: experts ascending, tokens ascending inside an
@@ -333,3 +338,13 @@ def mi_loss_grad(S) -> np.ndarray:
     S = _f64(S)
     p = S.mean(axis=0)
     return (np.log(p)[None, :] - np.log(S)) / S.shape[0]
+
+
+def mi_backward(X, W_r, b_r, alpha: float):
+    """Gradients of alpha * L_MI(softmax(X W_r + b_r)) w.r.t. X, W_r and b_r: the term the total loss
+    L = L_LM + alpha L_MI (Sec. 3.2, Eq. 6) adds to the router's gradients.  Chain rule only: the
+    gradient w.r.t. the scores goes through the softmax (Eq. 1) and the linear router."""
+    X = _f64(X)
+    S = route(X, W_r, b_r)
+    dZ = softmax_backward(S, alpha * mi_loss_grad(S))
+    return dZ @ _f64(W_r).T, X.T @ dZ, dZ.sum(axis=0)

@@ -437,3 +437,40 @@ def test_mi_loss_grad_against_finite_differences():
         Sp[idx] += h
         Sm[idx] -= h
         assert abs((orc.mi_loss(Sp) - orc.mi_loss(Sm)) / (2 * h) - an[idx]) < 1e-6
+
+
+def test_mi_backward_against_finite_differences_of_the_router():
+    # alpha * L_MI as a function of the router's parameters and input, differentiated numerically
+    g = np.random.default_rng(21)
+    T, d, E, alpha = 6, 5, 4, 0.7
+    X, w_r, b_r = g.standard_normal((T, d)), 0.5 * g.standard_normal((d, E)), 0.3 * g.standard_normal(E)
+    loss = lambda X_, w_, b_: alpha * orc.mi_loss(orc.route(X_, w_, b_))
+    dX, dW, db = orc.mi_backward(X, w_r, b_r, alpha)
+    h = 1e-6
+    for arr, grad, pos in ((X, dX, 0), (w_r, dW, 1), (b_r, db, 2)):
+        for idx in np.ndindex(*arr.shape):
+            args_p, args_m = [X.copy(), w_r.copy(), b_r.copy()], [X.copy(), w_r.copy(), b_r.copy()]
+            args_p[pos][idx] += h
+            args_m[pos][idx] -= h
+            num = (loss(*args_p) - loss(*args_m)) / (2 * h)
+            assert abs(num - grad[idx]) < 1e-7, (pos, idx, num, grad[idx])
+
+
+def test_mi_backward_vanishes_for_a_constant_router():
+    # W_r = 0: every token has the same scores, p = S, so log p - log S = 0 and nothing flows back
+    X = np.random.default_rng(3).standard_normal((7, 5))
+    dX, dW, db = orc.mi_backward(X, np.zeros((5, 4)), np.array([0.3, -0.2, 0.0, 0.1]), 1.0)
+    assert np.abs(dX).max() < 1e-15 and np.abs(dW).max() < 1e-15 and np.abs(db).max() < 1e-15
+
+
+def test_threshold_topk_selection_is_topk_at_the_batch_mean_count():
+    # hand case: counts above 0.25 are (2, 1, 3) -> mean 2 -> top-2 of every token
+    S = np.array([[0.40, 0.30, 0.20, 0.10],
+                  [0.70, 0.10, 0.10, 0.10],
+                  [0.30, 0.28, 0.26, 0.16]])
+    M = orc.select_threshold_topk(S, 0.25)
+    np.testing.assert_array_equal(M, np.array([[1, 1, 0, 0], [1, 1, 0, 0], [1, 1, 0, 0]], dtype=bool))
+    # rounding half up: counts (1, 2) -> mean 1.5 -> K = 2
+    S2 = np.array([[0.60, 0.20, 0.15, 0.05], [0.45, 0.40, 0.10, 0.05]])
+    assert orc.threshold_topk_k(S2, 0.25) == 2
+    assert orc.select_threshold_topk(S2, 0.25).sum(axis=1).tolist() == [2, 2]
