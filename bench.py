@@ -153,9 +153,18 @@ class Bench:
             fwd()
             bwd()
 
+        def bwd_mi():   # total loss with the mutual-information load-balance term (Eq. 6)
+            layer.dense_bwd(w["x"], w["w_r"], w["w_gate"], w["w_up"], w["w_down"], bufs["saved"], w["d_out"],
+                            buffers=bufs, mi_alpha=0.01)
+
+        def mi_loss():
+            layer.mi_loss(bufs["probs"])
+
         ms = self.timed(both, steps, warmup)
         ms_f = self.timed(fwd, steps, 1)
         ms_b = self.timed(bwd, steps, 1)
+        ms_bmi = self.timed(bwd_mi, steps, 1)
+        ms_mi = self.timed(mi_loss, steps, 1)
         assert torch.isfinite(bufs["dx"].float()).all()
         unit = 2.0 * cfg.T * cfg.d * cfg.E * cfg.f          # one T x d x (E f) product
         flops_f, flops_b = 3 * unit, 6 * unit
@@ -166,6 +175,7 @@ class Bench:
             "frac_of_bf16_peak": (flops_f + flops_b) / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
             "fwd_frac_of_bf16_peak": flops_f / (ms_f * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
             "bwd_frac_of_bf16_peak": flops_b / (ms_b * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+            "bwd_with_mi_loss_term_ms": ms_bmi, "mi_loss_ms": ms_mi,
         }
 
     # ---- decode sizes (c3) --------------------------------------------------------------------------

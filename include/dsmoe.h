@@ -37,7 +37,7 @@ extern "C" {
 typedef struct dsmoe_ctx dsmoe_ctx;
 
 typedef enum { DSMOE_F32 = 0, DSMOE_BF16 = 1 } dsmoe_dtype;
-typedef enum { DSMOE_SEL_TOPK = 0, DSMOE_SEL_THRESHOLD = 1 } dsmoe_sel_mode;
+typedef enum { DSMOE_SEL_TOPK = 0, DSMOE_SEL_THRESHOLD = 1, DSMOE_SEL_THRESHOLD_TOPK = 2 } dsmoe_sel_mode;
 
 typedef enum {
   DSMOE_OK = 0,
@@ -86,7 +86,9 @@ int32_t dsmoe_route(dsmoe_ctx* ctx, const void* x, const void* w_r, const void* 
  * above a threshold eps).  TOPK keeps the k highest probabilities, equal values going to the lower
  * expert index.  THRESHOLD keeps {e : probs[t,e] > eps} (raw probability, strict; the paper's
  * normalised threshold of Sec. 4.2 is eps * E) and falls back to the arg-max expert (lowest index)
- * when that set is empty.
+ * when that set is empty.  THRESHOLD_TOPK (Sec. 4.3 "Threshold-TopK"): the threshold rule gives every
+ * token a count; K = the batch mean of the counts rounded half up, clamped to [1, E], computed on the
+ * device; every token then keeps its top K (k is ignored; needs the workspace).
  * probs: fp32 [T,E]; mask: u64 [T], bit e set <=> expert e selected (written);
  * cnt_tok: i32 [T] number of selected experts (written; may be NULL). */
 int32_t dsmoe_select(dsmoe_ctx* ctx, const float* probs, int32_t T, int32_t mode, int32_t k, float eps,
@@ -148,6 +150,23 @@ int32_t dsmoe_dense_bwd(dsmoe_ctx* ctx, const void* x, const void* w_r, const vo
                         const void* w_up, const void* w_down, const void* saved, const void* d_out,
                         int32_t T, void* scratch, void* dx, float* dw_r, float* db_r, float* dw_gate,
                         float* dw_up, float* dw_down, void* stream);
+
+/* Mutual-information load-balance loss of the router (Sec. 3.2, Eq. 4-6):
+ *   L_MI = -H(e) + (1/T) sum_t H(e | x_t),  H(e) = -sum_i p_i log p_i with p_i the batch mean of
+ *   probs[:,i],  H(e | x_t) = -sum_i probs[t,i] log probs[t,i]  (0 log 0 = 0).
+ * probs: fp32 [T,E] (T >= 1).  Written: loss, device fp32 [1] (may be NULL); p_mean, device fp32 [E], the
+ * batch means p_i (may be NULL; not both).  Needs the workspace.  Two-stage reduction in a fixed order. */
+int32_t dsmoe_mi_loss(dsmoe_ctx* ctx, const float* probs, int32_t T, float* loss, float* p_mean,
+                      void* stream);
+
+/* dsmoe_dense_bwd for the total loss L = L_LM + mi_alpha * L_MI (Sec. 3.2, Eq. 6): the score gradient
+ * of Eq. 3 gets the term mi_alpha * dL_MI/dS[t,i] = mi_alpha * (log p_i - log S[t,i]) / T before the
+ * softmax backward, so dx, dw_r and db_r include the load-balance term; the expert-weight gradients do
+ * not depend on it.  mi_alpha = 0 is dsmoe_dense_bwd.  Same arguments, buffers and error behaviour. */
+int32_t dsmoe_dense_bwd_mi(dsmoe_ctx* ctx, const void* x, const void* w_r, const void* w_gate,
+                           const void* w_up, const void* w_down, const void* saved, const void* d_out,
+                           int32_t T, void* scratch, void* dx, float* dw_r, float* db_r, float* dw_gate,
+                           float* dw_up, float* dw_down, float mi_alpha, void* stream);
 
 /* Kernel timing for benchmarks (not part of the layer's definition).  While enabled, every call that
  * runs the expert FFN (dsmoe_expert_ffn, dsmoe_sparse_fwd) brackets its two grouped-GEMM kernels with

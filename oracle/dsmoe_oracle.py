@@ -95,6 +95,8 @@ def select(S, mode: str, k: int = 0, eps: float = 0.0) -> np.ndarray:
         return select_topk(S, k)
     if mode == "threshold":
         return select_threshold(S, eps)
+    if mode == "threshold_topk":
+        return select_threshold_topk(S, eps)
     raise ValueError(mode)
 
 

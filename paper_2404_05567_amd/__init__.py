@@ -14,14 +14,15 @@ _PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_PKG, "libdsmoe.so")
 
 F32, BF16 = 0, 1
-SEL_TOPK, SEL_THRESHOLD = 0, 1
+SEL_TOPK, SEL_THRESHOLD, SEL_THRESHOLD_TOPK = 0, 1, 2
 OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_CAPACITY, ERR_HIP, ERR_NOT_IMPL = 0, -1, -2, -3, -4, -5, -6
 
 EXPORTS = [
     "dsmoe_create", "dsmoe_destroy", "dsmoe_last_error", "dsmoe_workspace_bytes", "dsmoe_set_workspace",
     "dsmoe_poll_error", "dsmoe_route", "dsmoe_select", "dsmoe_dispatch", "dsmoe_expert_ffn", "dsmoe_combine",
     "dsmoe_sparse_fwd", "dsmoe_sparse_fwd_routing", "dsmoe_dense_saved_bytes", "dsmoe_dense_fwd",
-    "dsmoe_dense_bwd_scratch_bytes", "dsmoe_dense_bwd", "dsmoe_profile_enable", "dsmoe_profile_read",
+    "dsmoe_dense_bwd_scratch_bytes", "dsmoe_dense_bwd", "dsmoe_mi_loss", "dsmoe_dense_bwd_mi",
+    "dsmoe_profile_enable", "dsmoe_profile_read",
 ]
 
 
@@ -67,6 +68,8 @@ def load_library() -> ctypes.CDLL:
         "dsmoe_dense_fwd": (c_int32, [P, P, P, P, P, P, P, c_int32, P, P, P, P]),
         "dsmoe_dense_bwd_scratch_bytes": (c_int32, [P, c_int32, POINTER(c_size_t)]),
         "dsmoe_dense_bwd": (c_int32, [P, P, P, P, P, P, P, P, c_int32, P, P, P, P, P, P, P, P]),
+        "dsmoe_mi_loss": (c_int32, [P, P, c_int32, P, P, P]),
+        "dsmoe_dense_bwd_mi": (c_int32, [P, P, P, P, P, P, P, P, c_int32, P, P, P, P, P, P, P, c_float, P]),
         "dsmoe_profile_enable": (c_int32, [P, c_int32]),
         "dsmoe_profile_read": (c_int32, [P, POINTER(c_int32), POINTER(c_float), POINTER(c_float)]),
     }
@@ -236,7 +239,15 @@ class Layer:
                                              _ptr(w_down), T, _ptr(out), _ptr(probs), _ptr(saved), _stream()))
         return out, probs, saved
 
-    def dense_bwd(self, x, w_r, w_gate, w_up, w_down, saved, d_out, with_bias_grad=False, buffers=None):
+    def mi_loss(self, probs):
+        """(loss fp32 [1], p_mean fp32 [E]) of the router scores probs [T,E], both on the device."""
+        t = self.torch
+        loss, p_mean = self._empty((1,), t.float32), self._empty((self.E,), t.float32)
+        self._check(self.lib.dsmoe_mi_loss(self.ctx, _ptr(probs), probs.shape[0], _ptr(loss), _ptr(p_mean), _stream()))
+        return loss, p_mean
+
+    def dense_bwd(self, x, w_r, w_gate, w_up, w_down, saved, d_out, with_bias_grad=False, buffers=None,
+                  mi_alpha: float = 0.0):
         T = x.shape[0]
         t = self.torch
         if buffers is not None:
@@ -250,8 +261,11 @@ class Layer:
                      dw_gate=self._empty((self.E, self.d, self.f), t.float32),
                      dw_up=self._empty((self.E, self.d, self.f), t.float32),
                      dw_down=self._empty((self.E, self.f, self.d), t.float32))
-        self._check(self.lib.dsmoe_dense_bwd(self.ctx, _ptr(x), _ptr(w_r), _ptr(w_gate), _ptr(w_up), _ptr(w_down),
-                                             _ptr(saved), _ptr(d_out), T, _ptr(scratch), _ptr(g["dx"]),
-                                             _ptr(g["dw_r"]), _ptr(g["db_r"]), _ptr(g["dw_gate"]), _ptr(g["dw_up"]),
-                                             _ptr(g["dw_down"]), _stream()))
+        args = (self.ctx, _ptr(x), _ptr(w_r), _ptr(w_gate), _ptr(w_up), _ptr(w_down), _ptr(saved), _ptr(d_out), T,
+                _ptr(scratch), _ptr(g["dx"]), _ptr(g["dw_r"]), _ptr(g["db_r"]), _ptr(g["dw_gate"]), _ptr(g["dw_up"]),
+                _ptr(g["dw_down"]))
+        if mi_alpha != 0.0:
+            self._check(self.lib.dsmoe_dense_bwd_mi(*args, c_float(mi_alpha), _stream()))
+        else:
+            self._check(self.lib.dsmoe_dense_bwd(*args, _stream()))
         return g

@@ -51,6 +51,8 @@ WorkspaceLayout make_layout(const dsmoe_desc& d, size_t esize) {
   w.tok_rows = take(rows * 4);
   w.nnz = take(4);
   w.y_perm = take(rows * d.d_model * esize);
+  w.stat_part = take((size_t)kStatMaxBlocks * 128 * 4);
+  w.k_dev = take(4);
   const size_t dec_rows = d.dtype == DSMOE_BF16 ? (size_t)std::min<int64_t>(d.max_tokens, kDecodeMaxTokens) * E : 0;
   w.dec_info = take(32);
   w.dec_arrivals = take(decode_arrival_slots(d) * 4);
@@ -74,7 +76,7 @@ int32_t check_select_args(dsmoe_ctx* c, int32_t mode, int32_t k, float eps) {
   if (mode == DSMOE_SEL_TOPK) {
     if (k < 1 || k > c->desc.n_experts)
       return fail(c, DSMOE_ERR_INVALID_ARG, "k = %d outside [1, %d]", k, c->desc.n_experts);
-  } else if (mode == DSMOE_SEL_THRESHOLD) {
+  } else if (mode == DSMOE_SEL_THRESHOLD || mode == DSMOE_SEL_THRESHOLD_TOPK) {
     if (!(eps >= 0.f) || std::isinf(eps)) return fail(c, DSMOE_ERR_INVALID_ARG, "eps must be finite and >= 0");
   } else {
     return fail(c, DSMOE_ERR_INVALID_ARG, "unknown selection mode %d", mode);
@@ -231,12 +233,22 @@ int32_t dsmoe_route(dsmoe_ctx* c, const void* x, const void* w_r, const void* b_
 
 int32_t dsmoe_select(dsmoe_ctx* c, const float* probs, int32_t T, int32_t mode, int32_t k, float eps,
                      uint64_t* mask, int32_t* cnt_tok, void* stream) {
-  if (int32_t rc = check_call(c, T, false)) return rc;
+  if (int32_t rc = check_call(c, T, mode == DSMOE_SEL_THRESHOLD_TOPK)) return rc;
   if (int32_t rc = check_select_args(c, mode, k, eps)) return rc;
   if (T == 0) return DSMOE_OK;
   REQUIRE_PTR(c, probs); REQUIRE_PTR(c, mask);
   if (cnt_tok && (reinterpret_cast<uintptr_t>(cnt_tok) & 3u)) return fail(c, DSMOE_ERR_INVALID_ARG, "cnt_tok misaligned");
-  HIP_TRY(c, launch_select(c, probs, T, mode, k, eps, mask, cnt_tok, static_cast<hipStream_t>(stream)));
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if (mode == DSMOE_SEL_THRESHOLD_TOPK) {
+    // threshold counts -> K on the device -> top-K; the counts of the first pass live in the workspace
+    int32_t* cnt_ws = reinterpret_cast<int32_t*>(c->workspace + c->ws.cnt_tok);
+    int32_t* k_dev = reinterpret_cast<int32_t*>(c->workspace + c->ws.k_dev);
+    HIP_TRY(c, launch_select(c, probs, T, DSMOE_SEL_THRESHOLD, 0, eps, mask, cnt_ws, s));
+    HIP_TRY(c, launch_threshold_topk_k(c, cnt_ws, T, k_dev, s));
+    HIP_TRY(c, launch_select(c, probs, T, DSMOE_SEL_TOPK, 1, 0.f, mask, cnt_tok, s, k_dev));
+    return DSMOE_OK;
+  }
+  HIP_TRY(c, launch_select(c, probs, T, mode, k, eps, mask, cnt_tok, s));
   return DSMOE_OK;
 }
 
@@ -304,7 +316,14 @@ int32_t dsmoe_sparse_fwd(dsmoe_ctx* c, const void* x, const void* w_r, const voi
   int32_t* tok_rows = reinterpret_cast<int32_t*>(w + c->ws.tok_rows);
   int32_t* nnz = reinterpret_cast<int32_t*>(w + c->ws.nnz);
   void* y_perm = w + c->ws.y_perm;
-  HIP_TRY(c, launch_route(c, x, w_r, b_r, T, probs, mode, k, eps, mask, cnt_tok, s));
+  if (mode == DSMOE_SEL_THRESHOLD_TOPK) {
+    int32_t* k_dev = reinterpret_cast<int32_t*>(w + c->ws.k_dev);
+    HIP_TRY(c, launch_route(c, x, w_r, b_r, T, probs, DSMOE_SEL_THRESHOLD, 0, eps, mask, cnt_tok, s));
+    HIP_TRY(c, launch_threshold_topk_k(c, cnt_tok, T, k_dev, s));
+    HIP_TRY(c, launch_select(c, probs, T, DSMOE_SEL_TOPK, 1, 0.f, mask, cnt_tok, s, k_dev));
+  } else {
+    HIP_TRY(c, launch_route(c, x, w_r, b_r, T, probs, mode, k, eps, mask, cnt_tok, s));
+  }
   if (c->desc.dtype == DSMOE_BF16 && T <= kDecodeMaxTokens) {
     // decode-sized batch: weight-streaming kernels that derive the dispatch from the masks themselves
     HIP_TRY(c, launch_decode_fwd(c, x, w_gate, w_up, w_down, T, out, s));
@@ -361,11 +380,12 @@ int32_t dsmoe_dense_fwd(dsmoe_ctx* c, const void* x, const void* w_r, const void
   return DSMOE_OK;
 }
 
-int32_t dsmoe_dense_bwd(dsmoe_ctx* c, const void* x, const void* w_r, const void* w_gate, const void* w_up,
-                        const void* w_down, const void* saved, const void* d_out, int32_t T, void* scratch,
-                        void* dx, float* dw_r, float* db_r, float* dw_gate, float* dw_up, float* dw_down,
-                        void* stream) {
+int32_t dsmoe_dense_bwd_mi(dsmoe_ctx* c, const void* x, const void* w_r, const void* w_gate, const void* w_up,
+                           const void* w_down, const void* saved, const void* d_out, int32_t T, void* scratch,
+                           void* dx, float* dw_r, float* db_r, float* dw_gate, float* dw_up, float* dw_down,
+                           float mi_alpha, void* stream) {
   if (int32_t rc = check_call(c, T, false)) return rc;
+  if (!std::isfinite(mi_alpha)) return fail(c, DSMOE_ERR_INVALID_ARG, "mi_alpha must be finite");
   REQUIRE_PTR(c, dw_r); OPTIONAL_PTR(c, db_r); REQUIRE_PTR(c, dw_gate); REQUIRE_PTR(c, dw_up); REQUIRE_PTR(c, dw_down);
   if (T == 0) {   // no tokens: every weight gradient is zero
     hipStream_t s = static_cast<hipStream_t>(stream);
@@ -380,9 +400,29 @@ int32_t dsmoe_dense_bwd(dsmoe_ctx* c, const void* x, const void* w_r, const void
   REQUIRE_PTR(c, x); REQUIRE_PTR(c, w_r); REQUIRE_PTR(c, w_gate); REQUIRE_PTR(c, w_up); REQUIRE_PTR(c, w_down);
   REQUIRE_PTR(c, saved); REQUIRE_PTR(c, d_out); REQUIRE_PTR(c, scratch); REQUIRE_PTR(c, dx);
   hipError_t e = launch_dense_bwd(c, x, w_r, w_gate, w_up, w_down, saved, d_out, T, scratch, dx, dw_r, db_r,
-                                  dw_gate, dw_up, dw_down, static_cast<hipStream_t>(stream));
+                                  dw_gate, dw_up, dw_down, mi_alpha, static_cast<hipStream_t>(stream));
   if (e == hipErrorNotSupported) return fail(c, DSMOE_ERR_NOT_IMPL, "dense backward not implemented");
   HIP_TRY(c, e);
+  return DSMOE_OK;
+}
+
+int32_t dsmoe_dense_bwd(dsmoe_ctx* c, const void* x, const void* w_r, const void* w_gate, const void* w_up,
+                        const void* w_down, const void* saved, const void* d_out, int32_t T, void* scratch,
+                        void* dx, float* dw_r, float* db_r, float* dw_gate, float* dw_up, float* dw_down,
+                        void* stream) {
+  return dsmoe_dense_bwd_mi(c, x, w_r, w_gate, w_up, w_down, saved, d_out, T, scratch, dx, dw_r, db_r, dw_gate, dw_up,
+                            dw_down, 0.f, stream);
+}
+
+int32_t dsmoe_mi_loss(dsmoe_ctx* c, const float* probs, int32_t T, float* loss, float* p_mean, void* stream) {
+  if (int32_t rc = check_call(c, T, true)) return rc;
+  if (T == 0) return fail(c, DSMOE_ERR_INVALID_ARG, "the loss is a mean over tokens: T must be >= 1");
+  REQUIRE_PTR(c, probs);
+  if (!loss && !p_mean) return fail(c, DSMOE_ERR_INVALID_ARG, "nothing to write: loss and p_mean are both null");
+  if ((reinterpret_cast<uintptr_t>(loss) | reinterpret_cast<uintptr_t>(p_mean)) & 3u)
+    return fail(c, DSMOE_ERR_INVALID_ARG, "loss / p_mean misaligned");
+  HIP_TRY(c, launch_mi_loss(c, probs, T, reinterpret_cast<float*>(c->workspace + c->ws.stat_part), p_mean, loss,
+                            static_cast<hipStream_t>(stream)));
   return DSMOE_OK;
 }
 

@@ -37,6 +37,8 @@ struct WorkspaceLayout {
   size_t tok_rows;    // i32 [max_rows]
   size_t nnz;         // i32 [1]
   size_t y_perm;      // dtype [max_rows][d]
+  size_t stat_part;   // f32 [256][128]: per-block partial sums of the score statistics
+  size_t k_dev;       // i32 [1]: K of Threshold-TopK selection
   // weight-streaming (decode) path, bf16 only
   size_t dec_info;    // i32 [8]: rows, active experts, K split of gate/up, K split of down
   size_t dec_arrivals;   // i32 [decode_arrival_slots]: blocks that have finished a shared result; zero between calls
@@ -82,7 +84,13 @@ hipError_t launch_route(const dsmoe_ctx* c, const void* x, const void* w_r, cons
                         float* probs, int mode /* <0: no selection */, int k, float eps, uint64_t* mask,
                         int32_t* cnt_tok, hipStream_t s);
 hipError_t launch_select(const dsmoe_ctx* c, const float* probs, int T, int mode, int k, float eps,
-                         uint64_t* mask, int32_t* cnt_tok, hipStream_t s);
+                         uint64_t* mask, int32_t* cnt_tok, hipStream_t s, const int32_t* k_dev = nullptr);
+// router_stats.hip
+constexpr int kStatMaxBlocks = 256;
+int mi_blocks(int T);   // rows of 128 floats that launch_mi_loss needs in `part` (at most kStatMaxBlocks)
+hipError_t launch_mi_loss(const dsmoe_ctx* c, const float* S, int T, float* part, float* p_mean, float* loss,
+                          hipStream_t s);
+hipError_t launch_threshold_topk_k(const dsmoe_ctx* c, const int32_t* cnt_tok, int T, int32_t* k_out, hipStream_t s);
 // dispatch.hip
 hipError_t launch_dispatch(const dsmoe_ctx* c, const void* x, const float* probs, const uint64_t* mask, int T,
                            int32_t* expert_off, int32_t* row_token, float* row_weight, int32_t* tok_off,
@@ -109,6 +117,6 @@ hipError_t launch_dense_fwd(const dsmoe_ctx* c, const void* x, const void* w_r, 
 hipError_t launch_dense_bwd(const dsmoe_ctx* c, const void* x, const void* w_r, const void* w_gate,
                             const void* w_up, const void* w_down, const void* saved, const void* d_out, int T,
                             void* scratch, void* dx, float* dw_r, float* db_r, float* dw_gate, float* dw_up,
-                            float* dw_down, hipStream_t s);
+                            float* dw_down, float mi_alpha, hipStream_t s);
 
 }  // namespace dsmoe

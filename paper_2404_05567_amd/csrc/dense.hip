@@ -46,7 +46,7 @@ constexpr int kWrTokens = 256;   // tokens per slab of the router weight-gradien
 // dU and dG are [T][E f + EP] matrices: the EP pad columns of dG hold dZ in the storage type, so that the
 // router term of dX is one more K segment of the dG rows; W_r is repacked as [d][f] (first EP columns used)
 // so that its rows have the pitch of the expert weights' rows.
-struct ScratchLayout { size_t zeros, dU, dG, dS_part, dZ, WrP, dWr_part, total; int ntb, nsplit, EP; size_t ldg; };
+struct ScratchLayout { size_t zeros, dU, dG, dS_part, dZ, WrP, dWr_part, mi_part, p_mean, total; int ntb, nsplit, EP; size_t ldg; };
 ScratchLayout scratch_layout(const dsmoe_ctx* c, int T) {
   const size_t E = c->desc.n_experts, n = (size_t)T * E;
   const int bn1 = c->desc.dtype == DSMOE_BF16 ? DenseTiles<bf16_t>::BN1 : DenseTiles<float>::BN1;
@@ -64,6 +64,8 @@ ScratchLayout scratch_layout(const dsmoe_ctx* c, int T) {
   l.dZ = o; o = al256(o + n * 4);
   l.WrP = o; o = al256(o + (size_t)c->desc.d_model * c->desc.d_ff * c->esize);
   l.dWr_part = o; o = al256(o + (size_t)l.nsplit * c->desc.d_model * E * 4);
+  l.mi_part = o; o = al256(o + (size_t)kStatMaxBlocks * 128 * 4);   // score statistics for the MI-loss gradient
+  l.p_mean = o; o = al256(o + 64 * 4);
   l.total = o;
   return l;
 }
@@ -335,7 +337,8 @@ dense_bwd_dx_kernel(const T* __restrict__ dU, const T* __restrict__ dG, const T*
 template <typename T>
 __global__ void __launch_bounds__(kThreads)
 dense_softmax_bwd_kernel(const float* __restrict__ S, const float* __restrict__ dS_part, int ntb, int Tn, int E, int EP,
-                         float* __restrict__ dZ, T* __restrict__ dZt, size_t ldz, unsigned* __restrict__ zeros) {
+                         float* __restrict__ dZ, T* __restrict__ dZt, size_t ldz, unsigned* __restrict__ zeros,
+                         const float* __restrict__ p_mean, float alpha_over_T) {
   if (blockIdx.x == 0 && threadIdx.x < 64) zeros[threadIdx.x] = 0u;   // the zero page of the later kernels
   const int lane = threadIdx.x & 63;
   const int t = blockIdx.x * 4 + (threadIdx.x >> 6);
@@ -344,6 +347,9 @@ dense_softmax_bwd_kernel(const float* __restrict__ S, const float* __restrict__ 
   if (lane < E) {
     s = S[(size_t)t * E + lane];
     for (int j = 0; j < ntb; ++j) ds += dS_part[((size_t)t * E + lane) * ntb + j];
+    // gradient of alpha * L_MI w.r.t. the score (Eq. 4-6): alpha (log p_i - log S[t,i]) / T; a score that
+    // underflowed to 0 gets none (its factor S in the softmax backward is 0 anyway)
+    if (p_mean != nullptr && s > 0.f) ds += alpha_over_T * (logf(p_mean[lane]) - logf(s));
   }
   float dot = s * ds;
 #pragma unroll
@@ -451,7 +457,8 @@ hipError_t dense_fwd_t(const dsmoe_ctx* c, const void* x, const void* w_gate, co
 template <typename T>
 hipError_t dense_bwd_t(const dsmoe_ctx* c, const void* x, const void* w_r, const void* w_gate, const void* w_up,
                        const void* w_down, const char* saved, const void* d_out, int Tn, char* scratch, void* dx,
-                       float* dw_r, float* db_r, float* dw_gate, float* dw_up, float* dw_down, hipStream_t s) {
+                       float* dw_r, float* db_r, float* dw_gate, float* dw_up, float* dw_down, float mi_alpha,
+                       hipStream_t s) {
   typedef DenseTiles<T> DT;
   typedef Gemm<T, DT::BM, DT::BN1, 1, false, false> GRR;
   typedef Gemm<T, DT::BM, DT::BN1, 1, true, true, true> GCC1;
@@ -488,8 +495,15 @@ hipError_t dense_bwd_t(const dsmoe_ctx* c, const void* x, const void* w_r, const
       (const T*)d_out, (const T*)w_down, S, G, U, dU, dG, dS_part, Tn, d, f, E, sc.ldg);
   if (hipError_t e = hipGetLastError()) return e;
 
+  const float* p_mean = nullptr;
+  if (mi_alpha != 0.f) {   // batch means of the scores for the gradient of the MI loss
+    float* pm = reinterpret_cast<float*>(scratch + sc.p_mean);
+    if (hipError_t e = launch_mi_loss(c, S, Tn, reinterpret_cast<float*>(scratch + sc.mi_part), pm, nullptr, s)) return e;
+    p_mean = pm;
+  }
   dense_softmax_bwd_kernel<T><<<dim3((Tn + 3) / 4), dim3(kThreads), 0, s>>>(
-      S, dS_part, sc.ntb, Tn, E, sc.EP, dZ, dZt, sc.ldg, reinterpret_cast<unsigned*>(scratch + sc.zeros));
+      S, dS_part, sc.ntb, Tn, E, sc.EP, dZ, dZt, sc.ldg, reinterpret_cast<unsigned*>(scratch + sc.zeros), p_mean,
+      mi_alpha / (float)Tn);
   if (hipError_t e = hipGetLastError()) return e;
 
   dense_pad_wr_kernel<T><<<dim3((d * sc.EP + kThreads - 1) / kThreads), dim3(kThreads), 0, s>>>(
@@ -548,12 +562,13 @@ hipError_t launch_dense_fwd(const dsmoe_ctx* c, const void* x, const void* w_r, 
 
 hipError_t launch_dense_bwd(const dsmoe_ctx* c, const void* x, const void* w_r, const void* w_gate, const void* w_up,
                             const void* w_down, const void* saved, const void* d_out, int T, void* scratch, void* dx,
-                            float* dw_r, float* db_r, float* dw_gate, float* dw_up, float* dw_down, hipStream_t s) {
+                            float* dw_r, float* db_r, float* dw_gate, float* dw_up, float* dw_down, float mi_alpha,
+                            hipStream_t s) {
   if (c->desc.dtype == DSMOE_BF16)
     return dense_bwd_t<bf16_t>(c, x, w_r, w_gate, w_up, w_down, (const char*)saved, d_out, T, (char*)scratch, dx, dw_r,
-                               db_r, dw_gate, dw_up, dw_down, s);
+                               db_r, dw_gate, dw_up, dw_down, mi_alpha, s);
   return dense_bwd_t<float>(c, x, w_r, w_gate, w_up, w_down, (const char*)saved, d_out, T, (char*)scratch, dx, dw_r,
-                            db_r, dw_gate, dw_up, dw_down, s);
+                            db_r, dw_gate, dw_up, dw_down, mi_alpha, s);
 }
 
 }  // namespace dsmoe

@@ -299,7 +299,8 @@ static hipError_t launch_route_bf16(const dsmoe_ctx* c, const void* x, const voi
 
 __global__ void __launch_bounds__(kThreads)
 select_kernel(const float* __restrict__ probs, int T_tokens, int E, int mode, int k, float eps,
-              unsigned long long* __restrict__ mask, int32_t* __restrict__ cnt_tok) {
+              unsigned long long* __restrict__ mask, int32_t* __restrict__ cnt_tok, const int32_t* __restrict__ k_dev) {
+  if (k_dev != nullptr) k = k_dev[0];   // K computed on the device (Threshold-TopK)
   const int lane = threadIdx.x & 63;
   const int t = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (t >= T_tokens) return;
@@ -344,10 +345,10 @@ hipError_t launch_route(const dsmoe_ctx* c, const void* x, const void* w_r, cons
 }
 
 hipError_t launch_select(const dsmoe_ctx* c, const float* probs, int T_tokens, int mode, int k, float eps,
-                         uint64_t* mask, int32_t* cnt_tok, hipStream_t s) {
+                         uint64_t* mask, int32_t* cnt_tok, hipStream_t s, const int32_t* k_dev) {
   if (T_tokens == 0) return hipSuccess;
   hipLaunchKernelGGL(select_kernel, dim3((T_tokens + 3) / 4), dim3(kThreads), 0, s, probs, T_tokens,
-                     c->desc.n_experts, mode, k, eps, (unsigned long long*)mask, cnt_tok);
+                     c->desc.n_experts, mode, k, eps, (unsigned long long*)mask, cnt_tok, k_dev);
   return hipGetLastError();
 }
 

@@ -15,6 +15,11 @@ TAU = 1e-3
 
 
 def unsafe_tokens(S, mode, k, eps, tau=TAU):
+    if mode == "threshold_topk":
+        # both decisions must be safe: the counts that give K, and the top-K at that K
+        a = unsafe_tokens(S, "threshold", 0, eps, tau)
+        b = unsafe_tokens(S, "topk", orc.threshold_topk_k(S, eps), 0.0, tau)
+        return np.union1d(a, b)
     if mode == "threshold":
         return np.nonzero((np.abs(S - eps) < tau * eps).any(axis=1))[0]
     E = S.shape[1]

@@ -207,3 +207,69 @@ def test_c4_full_size_dense_training(torch, dsmoe):
             assert e <= tol
     for k in ("dx", "dw_r", "dw_gate", "dw_up", "dw_down"):
         assert bool(torch.isfinite(g[k].float()).all()), k
+
+
+# --------------------------------------------------------------------------------------------------
+# mutual-information load-balance loss (Sec. 3.2, Eq. 4-6) and its gradient through the router
+# --------------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("T,E", [(1, 8), (128, 8), (777, 32), (8192, 32), (5000, 64)])
+def test_mi_loss_matches_the_checker(torch, dsmoe, T, E):
+    say(f"[case] mi_loss T={T} E={E}")
+    g = np.random.default_rng(100 + T + E)
+    Z = g.standard_normal((T, E)) * 1.5
+    S = orc.softmax_rows(Z).astype(np.float32)
+    layer = dsmoe.Layer(64, 64, E, "f32", max_tokens=T)
+    loss, p_mean = layer.mi_loss(torch.from_numpy(S).to("cuda:0"))
+    torch.cuda.synchronize()
+    ref = orc.mi_loss(S)
+    got = float(loss.cpu()[0])
+    say(f"  loss {got:.7f} ref {ref:.7f}")
+    assert abs(got - ref) <= 1e-5 * max(1.0, abs(ref))
+    np.testing.assert_allclose(p_mean.cpu().numpy(), S.astype(np.float64).mean(axis=0), rtol=1e-5)
+
+
+def test_mi_loss_closed_forms_on_the_gpu(torch, dsmoe):
+    E, T = 8, 64
+    layer = dsmoe.Layer(64, 64, E, "f32", max_tokens=T)
+    uniform = torch.full((T, E), 1.0 / E, dtype=torch.float32, device="cuda:0")
+    onehot = torch.zeros((T, E), dtype=torch.float32, device="cuda:0")
+    onehot[torch.arange(T), torch.arange(T) % E] = 1.0       # balanced one-hot: exercises 0 log 0 = 0
+    collapsed = torch.zeros((T, E), dtype=torch.float32, device="cuda:0")
+    collapsed[:, 3] = 1.0
+    for S, want in ((uniform, 0.0), (onehot, -np.log(E)), (collapsed, 0.0)):
+        loss, _ = layer.mi_loss(S)
+        torch.cuda.synchronize()
+        assert abs(float(loss.cpu()[0]) - want) <= 1e-6, (float(loss.cpu()[0]), want)
+
+
+@pytest.mark.parametrize("name,T", [("c1", 128), ("c4", 300)])
+def test_dense_backward_with_the_mi_loss_term(torch, dsmoe, name, T):
+    """Total loss L_LM + alpha L_MI (Eq. 6): dx, dW_r and db_r gain the load-balance term, the expert-weight
+    gradients do not change."""
+    base = gen.CONFIGS[name]
+    cfg = base if name == "c1" else base.with_(name="c4_small", T=T, d=512, f=128, router_std=1.5 / np.sqrt(512))
+    tol = TOL[cfg.dtype]
+    inp = gen.make_layer(cfg, 3, with_grad=True)
+    w = to_dev(torch, inp)
+    layer = dsmoe.Layer(cfg.d, cfg.f, cfg.E, cfg.dtype, max_tokens=cfg.T)
+    gr = orc.dense_backward(inp.x, inp.w_r, inp.b_r, inp.w_gate, inp.w_up, inp.w_down, inp.d_out)
+    # the weight of the term is chosen so that it matters in the router gradient (half of the largest entry of
+    # the language-model part), or the test would check nothing; the gradient is linear in alpha
+    unit = orc.mi_backward(inp.x, inp.w_r, inp.b_r, 1.0)[1]
+    alpha = float(np.float32(0.5 * np.abs(gr.dW_r).max() / np.abs(unit).max()))
+    say(f"[case] dense backward + MI term {cfg.name} T={cfg.T} alpha={alpha:.4g}")
+    mdx, mdw, mdb = orc.mi_backward(inp.x, inp.w_r, inp.b_r, alpha)
+
+    _, _, saved = layer.dense_fwd(w["x"], w["w_r"], w["b_r"], w["w_gate"], w["w_up"], w["w_down"], save=True)
+    g = layer.dense_bwd(w["x"], w["w_r"], w["w_gate"], w["w_up"], w["w_down"], saved, w["d_out"],
+                        with_bias_grad=True, mi_alpha=alpha)
+    torch.cuda.synchronize()
+    for key, ref in (("dx", gr.dX + mdx), ("dw_r", gr.dW_r + mdw), ("db_r", gr.db_r + mdb),
+                     ("dw_gate", gr.dW_gate), ("dw_up", gr.dW_up), ("dw_down", gr.dW_down)):
+        err = helpers.rel_err(host(g[key]), ref)
+        say(f"  {key} rel err {err:.3e}")
+        assert err <= tol, key
+    # alpha = 0 is the plain backward
+    g0 = layer.dense_bwd(w["x"], w["w_r"], w["w_gate"], w["w_up"], w["w_down"], saved, w["d_out"], with_bias_grad=True)
+    torch.cuda.synchronize()
+    assert helpers.rel_err(host(g0["dw_r"]), gr.dW_r) <= tol

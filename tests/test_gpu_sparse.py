@@ -49,7 +49,7 @@ def weights_to_dev(torch, inp):
 
 
 def mode_code(dsmoe, mode):
-    return dsmoe.SEL_TOPK if mode == "topk" else dsmoe.SEL_THRESHOLD
+    return {"topk": dsmoe.SEL_TOPK, "threshold": dsmoe.SEL_THRESHOLD, "threshold_topk": dsmoe.SEL_THRESHOLD_TOPK}[mode]
 
 
 def mask_to_bool(mask_i64, E):
@@ -173,6 +173,22 @@ def test_ragged_multi_tile(torch, dsmoe, dtype, mode, k, eps):
     cfg = gen.LayerConfig("ragged", 11, T=777, d=320, E=16, f=192, dtype=dtype, mode=mode, k=k, eps=eps,
                           router_std=0.08)
     run_staged_and_check(torch, dsmoe, conditioned(cfg, mode, k, eps), mode, k, eps)
+
+
+@pytest.mark.parametrize("name,T,dtype,eps", [("c1", 128, "f32", 0.11), ("c2", 300, "bf16", 0.02),
+                                              ("c2", 32, "bf16", 0.02), ("c2", 128, "bf16", 0.05)])
+def test_threshold_topk_selection(torch, dsmoe, name, T, dtype, eps):
+    """Sec. 4.3: K = batch mean of the threshold counts (rounded half up), then top-K; staged and fused,
+    prefill-sized and decode-sized."""
+    base = gen.CONFIGS[name]
+    d = base.d if name == "c1" else 512
+    cfg = base.with_(name=f"ttk_{name}_{T}", index=12, T=T, d=d, f=base.f if name == "c1" else 128, dtype=dtype,
+                     mode="threshold", eps=eps, router_std=base.router_std if name == "c1" else 1.5 / np.sqrt(d))
+    inp = conditioned(cfg, "threshold_topk", 0, eps)
+    K = orc.threshold_topk_k(orc.route(inp.x, inp.w_r, inp.b_r), eps)
+    say(f"  Threshold-TopK: K = {K}")
+    assert 1 <= K < cfg.E
+    run_staged_and_check(torch, dsmoe, inp, "threshold_topk", 0, eps)
 
 
 def test_skewed_router_bias_empty_and_hot_experts(torch, dsmoe):
