@@ -31,16 +31,6 @@ __device__ __forceinline__ void init_rows(SrcRows<T, ROWS>& s, int valid, size_t
     s.p[i] = reinterpret_cast<const char*>(row_base(r)) + (threadIdx.x & 7) * 16;
   }
 }
-template <int ROWS, class F>
-__device__ __forceinline__ void init_rows(LRows2<ROWS>& s, int valid, size_t seg_stride_bytes, F row_base) {
-  s.seg_stride = seg_stride_bytes;
-#pragma unroll
-  for (int i = 0; i < LRows2<ROWS>::NV; ++i) {
-    const int r = min((int)(threadIdx.x >> 2) + 128 * i, valid - 1);
-    s.p[i] = reinterpret_cast<const char*>(row_base(r)) + (threadIdx.x & 3) * 16;
-  }
-}
-
 // base: element [k = 0][first row of the tile]; ld: elements between consecutive k;
 // rows_valid: rows of the matrix that exist from the tile's first row on; k_valid: extent of K.
 template <typename T, int ROWS>
@@ -59,6 +49,7 @@ struct Gemm;
 #define DSMOE_GEMM_STAGES(GM, st)                                                                            \
   extern __shared__ __align__(16) char dsmoe_dyn_smem[];                                                     \
   DSMOE_STAGE_ARRAYS(st, 4, GM::ST_L, GM::ST_R);                                                             \
+  (void)st##L4; (void)st##L5; (void)st##R4; (void)st##R5; /* placeholders of the four-stage form */          \
   typename GM::Stages st =                                                                                   \
       GM::make_stages(st##L0, st##L1, st##L2, st##L3, st##R0, st##R1, st##R2, st##R3, dsmoe_dyn_smem)
 

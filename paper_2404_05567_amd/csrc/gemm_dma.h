@@ -24,9 +24,42 @@
 
 #include <type_traits>
 
-#include "gemm_bf16.h"
+#include "gemm_core.h"
 
 namespace dsmoe {
+
+constexpr int kThreads2 = 512;   // threads per block of the bf16 kernels
+constexpr int kBK2 = 32;         // K elements per step
+
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+
+// Transposing LDS read (ds_read_b64_tr_b16): inside a group of 16 lanes, lane r addresses element
+// [k0 + r/4][n0 + 4*(r%4)] of a [k][n] tile and receives the column [k0 .. k0+3][n0 + r].
+__device__ __forceinline__ u32x2 lds_read_tr16(const char* p) {
+  const s16x4 v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p));
+  return __builtin_bit_cast(u32x2, v);
+}
+
+// scheduling-group masks of __builtin_amdgcn_sched_group_barrier
+constexpr int kSgMfma = 0x008, kSgVmemRd = 0x020, kSgDsRd = 0x100, kSgDsWr = 0x200;
+
+template <int MASK, int N>
+__device__ __forceinline__ void sched_group() {
+  if constexpr (N > 0) __builtin_amdgcn_sched_group_barrier(MASK, N, 0);
+}
+// NMMA groups of {1 MFMA, a share of NA instructions of kind MASKA}
+template <int I, int NMMA, int NA, int MASKA>
+struct Interleave {
+  static __device__ __forceinline__ void run() {
+    if constexpr (I < NMMA) {
+      sched_group<kSgMfma, 1>();
+      sched_group<MASKA, (NA * (I + 1)) / NMMA - (NA * I) / NMMA>();
+      Interleave<I + 1, NMMA, NA, MASKA>::run();
+    }
+  }
+};
+
 
 constexpr int kMaxStages3 = 6;   // LDS stages a kernel may use (Tile3's NST: 4 for the MFMA-bound kernels, 6 for streaming)
 

@@ -10,7 +10,7 @@
 //   bf16: eight waves own contiguous K ranges and never synchronise inside the K loop: each stages
 //         its own 16 x E slice of W_r as stored and reads it back with the transposing LDS load; with
 //         16 slices in flight per wave a decode-sized call needs one memory round trip (route_bf16_kernel).
-#include "gemm_bf16.h"
+#include "gemm_dma.h"
 
 namespace dsmoe {
 
@@ -64,9 +64,7 @@ __device__ __forceinline__ unsigned long long select_wave(float p, int lane, int
     return m;
   }
   int rank = 0;   // experts that precede this lane's: larger probability, or equal and lower index
-#pragma unroll
-  for (int j = 0; j < kMaxExperts; ++j) {
-    if (j >= E) break;
+  for (int j = 0; j < E; ++j) {
     const float pj = lane_value(p, j);
     rank += (pj > p || (pj == p && j < lane)) ? 1 : 0;
   }
