@@ -6,7 +6,7 @@ else; the product never routes through it and it shares no code with the HIP pat
 
 The method is exact (not an approximation), so every function below is the defining formula written
 out with numpy fp64 array operations; `@` (a library matrix product) is the only library primitive
-used for the contractions.  There is no blocking, fusion or reordering beyond what the formulas state.
+used for the contractions (and scipy's erf for the GeLU expert).  There is no blocking, fusion or reordering beyond what the formulas state.
 
 Notation follows the paper (Sec. 3.1): a token X in R^{d_h}, N experts e_1..e_N, router scores
 S = softmax(h(X)), selected index set A.  Array shapes: X[T,d], W_r[d,E], b_r[E], W_gate/W_up[E,d,f],
@@ -15,7 +15,8 @@ W_down[E,f,d]; T tokens, E = N experts.
 Readings taken where the paper is silent (listed with reasons in the design notes):
   * the router h is one linear map X W_r (+ b_r);
   * an expert is a SwiGLU MLP, e(x) = (silu(x W_gate) * (x W_up)) W_down, without biases (the paper
-    says only "MLP module" and uses GeLU; the workload definition fixes SwiGLU);
+    says only "MLP module" and uses GeLU; the workload definition fixes SwiGLU); passing W_up = None
+    selects the paper's own two-matrix expert, e(x) = gelu(x W_1) W_2 with the exact (erf) GeLU;
   * the kept scores are used as they are (Eq. 1 has no renormalisation over the kept set);
   * the threshold is applied to the raw probability, strictly (S > eps); the paper's normalised
     threshold (Sec. 4.2 footnote: probability times N) is eps_raw = eps_paper / N;
@@ -31,6 +32,7 @@ from dataclasses import dataclass
 from typing import Optional, Sequence
 
 import numpy as np
+from scipy.special import erf as _erf   # library primitive for the GeLU expert only
 
 F64 = np.float64
 
@@ -177,10 +179,27 @@ def silu_prime(g):
     return s * (1.0 + g * (1.0 - s))
 
 
+def gelu(g):
+    """GeLU, the activation the paper's experts use (Sec. 4.1): g * Phi(g), Phi the standard normal CDF."""
+    return 0.5 * g * (1.0 + _erf(g / np.sqrt(2.0)))
+
+
+def gelu_prime(g):
+    """d gelu / d g = Phi(g) + g * phi(g), phi the standard normal density."""
+    return 0.5 * (1.0 + _erf(g / np.sqrt(2.0))) + g * np.exp(-0.5 * g * g) / np.sqrt(2.0 * np.pi)
+
+
+def _of(W, e):
+    return None if W is None else W[e]
+
+
 def expert_ffn(x, w_gate_e, w_up_e, w_down_e) -> np.ndarray:
-    """e_j(x) = (silu(x W_gate) * (x W_up)) W_down for rows x[n,d]."""
+    """e_j(x) for rows x[n,d].  SwiGLU expert: (silu(x W_gate) * (x W_up)) W_down.  With w_up_e = None the
+    two-matrix GeLU expert of the paper (Sec. 4.1): gelu(x W_1) W_2 with W_1 = w_gate_e, W_2 = w_down_e."""
     x = _f64(x)
     g = x @ _f64(w_gate_e)
+    if w_up_e is None:
+        return gelu(g) @ _f64(w_down_e)
     u = x @ _f64(w_up_e)
     return (silu(g) * u) @ _f64(w_down_e)
 
@@ -193,7 +212,7 @@ def expert_outputs_permuted(X, r: Routing, W_gate, W_up, W_down) -> np.ndarray:
     for e in range(E):
         lo, hi = r.expert_off[e], r.expert_off[e + 1]
         if hi > lo:
-            Y[lo:hi] = expert_ffn(X[r.row_token[lo:hi]], W_gate[e], W_up[e], W_down[e])
+            Y[lo:hi] = expert_ffn(X[r.row_token[lo:hi]], W_gate[e], _of(W_up, e), W_down[e])
     return Y
 
 
@@ -227,7 +246,7 @@ def sparse_forward(X, W_r, b_r, W_gate, W_up, W_down, mode: str, k: int = 0, eps
         sel = np.nonzero(M[tok, e])[0]
         if sel.size:
             t = tok[sel]
-            O[sel] += S[t, e][:, None] * expert_ffn(X[t], W_gate[e], W_up[e], W_down[e])
+            O[sel] += S[t, e][:, None] * expert_ffn(X[t], W_gate[e], _of(W_up, e), W_down[e])
     return O, S, M
 
 
@@ -243,7 +262,7 @@ def dense_forward(X, W_r, b_r, W_gate, W_up, W_down, tokens: Optional[Sequence[i
     tok = np.arange(T) if tokens is None else np.asarray(tokens, dtype=np.int64)
     Y = np.empty((tok.size, E, W_down.shape[2]), dtype=F64)
     for j in range(E):
-        Y[:, j, :] = expert_ffn(X[tok], W_gate[j], W_up[j], W_down[j])
+        Y[:, j, :] = expert_ffn(X[tok], W_gate[j], _of(W_up, j), W_down[j])
     O = np.zeros((tok.size, W_down.shape[2]), dtype=F64)
     for j in range(E):
         O += S[tok, j][:, None] * Y[:, j, :]
@@ -269,6 +288,10 @@ def expert_backward(X, S_j, w_gate_j, w_up_j, w_down_j, dO):
     X, dO = _f64(X), _f64(dO)
     wg, wu, wd = _f64(w_gate_j), _f64(w_up_j), _f64(w_down_j)
     G = X @ wg
+    if wu is None:   # two-matrix GeLU expert: H = gelu(G); no W_up gradient
+        dY = _f64(S_j)[:, None] * dO
+        dG = (dY @ wd.T) * gelu_prime(G)
+        return dG @ wg.T, X.T @ dG, None, gelu(G).T @ dY
     U = X @ wu
     H = silu(G) * U
     dY = _f64(S_j)[:, None] * dO
@@ -308,11 +331,12 @@ def dense_backward(X, W_r, b_r, W_gate, W_up, W_down, dO) -> DenseGrads:
     dS = grad_scores(Y, dO)
     dX = np.zeros_like(X)
     dW_gate = np.zeros(W_gate.shape, dtype=F64)
-    dW_up = np.zeros(W_up.shape, dtype=F64)
+    dW_up = None if W_up is None else np.zeros(W_up.shape, dtype=F64)
     dW_down = np.zeros(W_down.shape, dtype=F64)
     for j in range(E):
-        dx_j, dW_gate[j], dW_up[j], dW_down[j] = expert_backward(
-            X, S[:, j], W_gate[j], W_up[j], W_down[j], dO)
+        dx_j, dW_gate[j], dwu_j, dW_down[j] = expert_backward(X, S[:, j], W_gate[j], _of(W_up, j), W_down[j], dO)
+        if dW_up is not None:
+            dW_up[j] = dwu_j
         dX += dx_j
     dZ = softmax_backward(S, dS)
     dW_r = X.T @ dZ

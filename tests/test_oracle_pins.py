@@ -474,3 +474,79 @@ def test_threshold_topk_selection_is_topk_at_the_batch_mean_count():
     S2 = np.array([[0.60, 0.20, 0.15, 0.05], [0.45, 0.40, 0.10, 0.05]])
     assert orc.threshold_topk_k(S2, 0.25) == 2
     assert orc.select_threshold_topk(S2, 0.25).sum(axis=1).tolist() == [2, 2]
+
+
+# ------------------------------------------------------------------------------------------------
+# the paper's own expert: two matrices and GeLU (Sec. 4.1); selected by passing W_up = None
+# ------------------------------------------------------------------------------------------------
+def s_gelu(g):
+    return 0.5 * g * (1.0 + math.erf(g / math.sqrt(2.0)))
+
+
+def s_expert_gelu(x, w1, w2):
+    d, f = len(w1), len(w1[0])
+    h = [s_gelu(sum(x[i] * w1[i][c] for i in range(d))) for c in range(f)]
+    return [sum(h[c] * w2[c][k] for c in range(f)) for k in range(len(w2[0]))]
+
+
+def test_gelu_known_values_and_identities():
+    # Phi(1) and Phi(2) from any table of the standard normal CDF
+    assert abs(orc.gelu(np.array([1.0]))[0] - 0.8413447460685429) < 1e-15
+    assert abs(orc.gelu(np.array([2.0]))[0] - 2 * 0.9772498680518208) < 1e-15
+    g = np.linspace(-6, 6, 241)
+    # Phi(g) + Phi(-g) = 1  =>  gelu(g) - gelu(-g) = g
+    np.testing.assert_allclose(orc.gelu(g) - orc.gelu(-g), g, rtol=0, atol=1e-15)
+    assert orc.gelu(np.array([0.0]))[0] == 0.0
+    assert abs(orc.gelu(np.array([30.0]))[0] - 30.0) < 1e-12 and abs(orc.gelu(np.array([-30.0]))[0]) < 1e-12
+    # derivative by central differences
+    h = 1e-6
+    np.testing.assert_allclose(orc.gelu_prime(g), (orc.gelu(g + h) - orc.gelu(g - h)) / (2 * h), atol=1e-9)
+
+
+@pytest.mark.parametrize("mode,k,eps", [("topk", 2, 0), ("threshold", 0, 0.2)])
+def test_gelu_expert_sparse_forward_against_scalar_code(mode, k, eps):
+    X, w_r, b_r, w1, _, w2 = rand_layer(41, T=7, d=5, E=4, f=3, bias=True)
+    O, S, M = orc.sparse_forward(X, w_r, b_r, w1, None, w2, mode, k, eps)
+    for t in range(X.shape[0]):
+        s = s_scores(X[t].tolist(), w_r.tolist(), b_r.tolist())
+        A = s_select(s, mode, k, eps)
+        assert np.nonzero(M[t])[0].tolist() == A
+        o = np.zeros(X.shape[1])
+        for e in A:
+            o += s[e] * np.array(s_expert_gelu(X[t].tolist(), w1[e].tolist(), w2[e].tolist()))
+        np.testing.assert_allclose(O[t], o, rtol=1e-12, atol=1e-14)
+    # staged path (dispatch, per-expert rows, combine) equals the fused definition
+    r = orc.dispatch(M, S)
+    Y = orc.expert_outputs_permuted(X, r, w1, None, w2)
+    np.testing.assert_allclose(orc.combine(Y, r, X.shape[0]), O, rtol=1e-12, atol=1e-14)
+
+
+def test_gelu_expert_dense_backward_against_torch_autograd_and_finite_differences():
+    torch = pytest.importorskip("torch")
+    X, w_r, b_r, w1, _, w2 = rand_layer(42, T=10, d=6, E=4, f=5, bias=True)
+    dO = np.random.default_rng(12).standard_normal(X.shape)
+    tt = {k: torch.tensor(v, dtype=torch.float64, requires_grad=True)
+          for k, v in dict(X=X, w_r=w_r, b_r=b_r, w1=w1, w2=w2).items()}
+    S = torch.softmax(tt["X"] @ tt["w_r"] + tt["b_r"], dim=1)
+    G = torch.einsum("td,edf->tef", tt["X"], tt["w1"])
+    Y = torch.einsum("tef,efd->ted", torch.nn.functional.gelu(G), tt["w2"])     # exact (erf) GeLU
+    O = (S[:, :, None] * Y).sum(dim=1)
+    O.backward(torch.tensor(dO))
+    gr = orc.dense_backward(X, w_r, b_r, w1, None, w2, dO)
+    O_or, _, _ = orc.dense_forward(X, w_r, b_r, w1, None, w2)
+    np.testing.assert_allclose(O_or, O.detach().numpy(), rtol=1e-12, atol=1e-14)
+    assert gr.dW_up is None
+    for got, name in ((gr.dX, "X"), (gr.dW_r, "w_r"), (gr.db_r, "b_r"), (gr.dW_gate, "w1"), (gr.dW_down, "w2")):
+        np.testing.assert_allclose(got, tt[name].grad.numpy(), rtol=1e-10, atol=1e-12, err_msg=name)
+    # one entry of each gradient by central differences of the scalar loss <O, dO>
+    loss = lambda: float((orc.dense_forward(X, w_r, b_r, w1, None, w2)[0] * dO).sum())
+    h = 1e-6
+    for p, g_an, idx in ((X, gr.dX, (3, 2)), (w1, gr.dW_gate, (1, 4, 2)), (w2, gr.dW_down, (2, 3, 1)),
+                         (w_r, gr.dW_r, (5, 0))):
+        old = p[idx]
+        p[idx] = old + h
+        lp = loss()
+        p[idx] = old - h
+        lm = loss()
+        p[idx] = old
+        assert abs((lp - lm) / (2 * h) - g_an[idx]) < 1e-6 * max(1.0, abs(g_an[idx]))
