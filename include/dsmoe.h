@@ -38,6 +38,7 @@ typedef struct dsmoe_ctx dsmoe_ctx;
 
 typedef enum { DSMOE_F32 = 0, DSMOE_BF16 = 1 } dsmoe_dtype;
 typedef enum { DSMOE_SEL_TOPK = 0, DSMOE_SEL_THRESHOLD = 1, DSMOE_SEL_THRESHOLD_TOPK = 2 } dsmoe_sel_mode;
+typedef enum { DSMOE_EXPERT_SWIGLU = 0, DSMOE_EXPERT_GELU = 1 } dsmoe_expert_kind;
 
 typedef enum {
   DSMOE_OK = 0,
@@ -64,6 +65,13 @@ typedef struct {
 int32_t dsmoe_create(const dsmoe_desc* desc, dsmoe_ctx** out);
 int32_t dsmoe_destroy(dsmoe_ctx* ctx);
 const char* dsmoe_last_error(const dsmoe_ctx* ctx);
+
+/* The expert e_i of Eq. 1.  DSMOE_EXPERT_SWIGLU (default): e(x) = (silu(x W_gate) * (x W_up)) W_down.
+ * DSMOE_EXPERT_GELU: the paper's own two-matrix MLP (Sec. 4.1), e(x) = gelu(x W_1) W_2 with the exact
+ * GeLU g * Phi(g); W_1 is passed as w_gate, W_2 as w_down, w_up is ignored (may be NULL).  Applies to
+ * dsmoe_expert_ffn and dsmoe_sparse_fwd (which then uses the grouped kernels at every batch size); the
+ * dense-training calls return DSMOE_ERR_NOT_IMPL for the GeLU expert. */
+int32_t dsmoe_set_expert_kind(dsmoe_ctx* ctx, int32_t kind);
 
 /* Scratch memory the library needs (intermediate H = silu(G)*U rows, block histograms, the routing
  * objects and permuted outputs of dsmoe_sparse_fwd).  The caller allocates `bytes` of device memory,

@@ -15,10 +15,12 @@ LIB_PATH = os.path.join(_PKG, "libdsmoe.so")
 
 F32, BF16 = 0, 1
 SEL_TOPK, SEL_THRESHOLD, SEL_THRESHOLD_TOPK = 0, 1, 2
+EXPERT_SWIGLU, EXPERT_GELU = 0, 1
 OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_CAPACITY, ERR_HIP, ERR_NOT_IMPL = 0, -1, -2, -3, -4, -5, -6
 
 EXPORTS = [
-    "dsmoe_create", "dsmoe_destroy", "dsmoe_last_error", "dsmoe_workspace_bytes", "dsmoe_set_workspace",
+    "dsmoe_create", "dsmoe_destroy", "dsmoe_last_error", "dsmoe_set_expert_kind", "dsmoe_workspace_bytes",
+    "dsmoe_set_workspace",
     "dsmoe_poll_error", "dsmoe_route", "dsmoe_select", "dsmoe_dispatch", "dsmoe_expert_ffn", "dsmoe_combine",
     "dsmoe_sparse_fwd", "dsmoe_sparse_fwd_routing", "dsmoe_dense_saved_bytes", "dsmoe_dense_fwd",
     "dsmoe_dense_bwd_scratch_bytes", "dsmoe_dense_bwd", "dsmoe_mi_loss", "dsmoe_dense_bwd_mi",
@@ -54,6 +56,7 @@ def load_library() -> ctypes.CDLL:
         "dsmoe_create": (c_int32, [POINTER(Desc), POINTER(c_void_p)]),
         "dsmoe_destroy": (c_int32, [P]),
         "dsmoe_last_error": (c_char_p, [P]),
+        "dsmoe_set_expert_kind": (c_int32, [P, c_int32]),
         "dsmoe_workspace_bytes": (c_int32, [P, POINTER(c_size_t)]),
         "dsmoe_set_workspace": (c_int32, [P, P, c_size_t]),
         "dsmoe_poll_error": (c_int32, [P, P]),
@@ -98,7 +101,7 @@ class Layer:
     """One `dsmoe_ctx` plus its workspace.  Method names and argument order mirror the C ABI."""
 
     def __init__(self, d_model: int, d_ff: int, n_experts: int, dtype: str, max_tokens: int,
-                 max_rows: int | None = None, device="cuda:0"):
+                 max_rows: int | None = None, device="cuda:0", expert: str = "swiglu"):
         import torch
         self.lib = load_library()
         self.torch = torch
@@ -113,6 +116,7 @@ class Layer:
         rc = self.lib.dsmoe_create(byref(desc), byref(self.ctx))
         if rc != OK:
             raise DsmoeError(rc, "dsmoe_create rejected the descriptor")
+        self._check(self.lib.dsmoe_set_expert_kind(self.ctx, {"swiglu": EXPERT_SWIGLU, "gelu": EXPERT_GELU}[expert]))
         nbytes = c_size_t()
         self._check(self.lib.dsmoe_workspace_bytes(self.ctx, byref(nbytes)))
         self.workspace_bytes = nbytes.value

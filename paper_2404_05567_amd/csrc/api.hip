@@ -94,6 +94,13 @@ int32_t check_select_args(dsmoe_ctx* c, int32_t mode, int32_t k, float eps) {
     if ((p) != nullptr && misaligned(p))                                                          \
       return fail((c), DSMOE_ERR_INVALID_ARG, "pointer not 16-byte aligned: %s", #p);              \
   } while (0)
+// the expert's weight matrices: the two-matrix GeLU expert has no w_up (the argument is ignored)
+#define REQUIRE_EXPERT_WEIGHTS(c, w_gate, w_up, w_down)                                            \
+  do {                                                                                            \
+    REQUIRE_PTR(c, w_gate);                                                                       \
+    if ((c)->expert_kind == DSMOE_EXPERT_SWIGLU) REQUIRE_PTR(c, w_up);                             \
+    REQUIRE_PTR(c, w_down);                                                                       \
+  } while (0)
 #define HIP_TRY(c, expr)                                    \
   do {                                                      \
     hipError_t e_ = (expr);                                 \
@@ -122,6 +129,7 @@ int32_t dsmoe_create(const dsmoe_desc* desc, dsmoe_ctx** out) {
   c->workspace = nullptr;
   c->workspace_bytes = 0;
   c->err[0] = 0;
+  c->expert_kind = DSMOE_EXPERT_SWIGLU;
   c->n_cu = 256;
   int dev = 0;
   hipDeviceProp_t prop;
@@ -184,6 +192,14 @@ int32_t dsmoe_destroy(dsmoe_ctx* ctx) {
 }
 
 const char* dsmoe_last_error(const dsmoe_ctx* ctx) { return ctx ? ctx->err : "null context"; }
+
+int32_t dsmoe_set_expert_kind(dsmoe_ctx* c, int32_t kind) {
+  if (!c) return DSMOE_ERR_INVALID_ARG;
+  if (kind != DSMOE_EXPERT_SWIGLU && kind != DSMOE_EXPERT_GELU)
+    return fail(c, DSMOE_ERR_INVALID_ARG, "unknown expert kind %d", kind);
+  c->expert_kind = kind;
+  return DSMOE_OK;
+}
 
 int32_t dsmoe_workspace_bytes(const dsmoe_ctx* ctx, size_t* bytes) {
   if (!ctx || !bytes) return DSMOE_ERR_INVALID_ARG;
@@ -274,7 +290,7 @@ int32_t dsmoe_expert_ffn(dsmoe_ctx* c, const void* x, const void* x_perm, const 
   if (c->desc.max_rows == 0) return DSMOE_OK;
   if (!x_perm) { REQUIRE_PTR(c, x); REQUIRE_PTR(c, row_token); }
   OPTIONAL_PTR(c, x_perm);
-  REQUIRE_PTR(c, expert_off); REQUIRE_PTR(c, w_gate); REQUIRE_PTR(c, w_up); REQUIRE_PTR(c, w_down);
+  REQUIRE_PTR(c, expert_off); REQUIRE_EXPERT_WEIGHTS(c, w_gate, w_up, w_down);
   REQUIRE_PTR(c, y_perm);
   HIP_TRY(c, launch_expert_ffn(c, x, x_perm, row_token, expert_off, w_gate, w_up, w_down, y_perm,
                                static_cast<hipStream_t>(stream)));
@@ -304,8 +320,8 @@ int32_t dsmoe_sparse_fwd(dsmoe_ctx* c, const void* x, const void* w_r, const voi
                                reinterpret_cast<int32_t*>(w + c->ws.nnz), nullptr, s));
     return DSMOE_OK;
   }
-  REQUIRE_PTR(c, x); REQUIRE_PTR(c, w_r); OPTIONAL_PTR(c, b_r); REQUIRE_PTR(c, w_gate); REQUIRE_PTR(c, w_up);
-  REQUIRE_PTR(c, w_down); REQUIRE_PTR(c, out);
+  REQUIRE_PTR(c, x); REQUIRE_PTR(c, w_r); OPTIONAL_PTR(c, b_r); REQUIRE_EXPERT_WEIGHTS(c, w_gate, w_up, w_down);
+  REQUIRE_PTR(c, out);
   float* probs = reinterpret_cast<float*>(w + c->ws.probs);
   uint64_t* mask = reinterpret_cast<uint64_t*>(w + c->ws.mask);
   int32_t* cnt_tok = reinterpret_cast<int32_t*>(w + c->ws.cnt_tok);
@@ -324,7 +340,7 @@ int32_t dsmoe_sparse_fwd(dsmoe_ctx* c, const void* x, const void* w_r, const voi
   } else {
     HIP_TRY(c, launch_route(c, x, w_r, b_r, T, probs, mode, k, eps, mask, cnt_tok, s));
   }
-  if (c->desc.dtype == DSMOE_BF16 && T <= kDecodeMaxTokens) {
+  if (c->desc.dtype == DSMOE_BF16 && T <= kDecodeMaxTokens && c->expert_kind == DSMOE_EXPERT_SWIGLU) {
     // decode-sized batch: weight-streaming kernels that derive the dispatch from the masks themselves
     HIP_TRY(c, launch_decode_fwd(c, x, w_gate, w_up, w_down, T, out, s));
     return DSMOE_OK;
@@ -367,6 +383,8 @@ int32_t dsmoe_dense_fwd(dsmoe_ctx* c, const void* x, const void* w_r, const void
                         const void* w_up, const void* w_down, int32_t T, void* out, float* probs, void* saved,
                         void* stream) {
   if (int32_t rc = check_call(c, T, true)) return rc;
+  if (c->expert_kind != DSMOE_EXPERT_SWIGLU)
+    return fail(c, DSMOE_ERR_NOT_IMPL, "dense training is implemented for the SwiGLU expert only");
   if (T == 0) return DSMOE_OK;
   REQUIRE_PTR(c, x); REQUIRE_PTR(c, w_r); OPTIONAL_PTR(c, b_r); REQUIRE_PTR(c, w_gate); REQUIRE_PTR(c, w_up);
   REQUIRE_PTR(c, w_down); REQUIRE_PTR(c, out); OPTIONAL_PTR(c, probs); OPTIONAL_PTR(c, saved);
@@ -385,6 +403,8 @@ int32_t dsmoe_dense_bwd_mi(dsmoe_ctx* c, const void* x, const void* w_r, const v
                            void* dx, float* dw_r, float* db_r, float* dw_gate, float* dw_up, float* dw_down,
                            float mi_alpha, void* stream) {
   if (int32_t rc = check_call(c, T, false)) return rc;
+  if (c->expert_kind != DSMOE_EXPERT_SWIGLU)
+    return fail(c, DSMOE_ERR_NOT_IMPL, "dense training is implemented for the SwiGLU expert only");
   if (!std::isfinite(mi_alpha)) return fail(c, DSMOE_ERR_INVALID_ARG, "mi_alpha must be finite");
   REQUIRE_PTR(c, dw_r); OPTIONAL_PTR(c, db_r); REQUIRE_PTR(c, dw_gate); REQUIRE_PTR(c, dw_up); REQUIRE_PTR(c, dw_down);
   if (T == 0) {   // no tokens: every weight gradient is zero

@@ -62,6 +62,7 @@ struct dsmoe_ctx {
   char* workspace;
   size_t workspace_bytes;
   int n_cu;
+  int expert_kind;   // DSMOE_EXPERT_SWIGLU or DSMOE_EXPERT_GELU
   char err[256];
 };
 

@@ -4,6 +4,9 @@
 //   kernel 1 (gate/up):  H[r,:] = silu(x_r W_gate[e]) * (x_r W_up[e])   rows r of expert e
 //   kernel 2 (down):     Y[r,:] = H[r,:] W_down[e]
 //
+// With the paper's own two-matrix GeLU expert (Sec. 4.1) kernel 1 is the same grouped product as kernel 2 with
+// gathered rows and the activation in its epilogue:  H[r,:] = gelu(x_r W_1[e]),  Y[r,:] = H[r,:] W_2[e].
+//
 // Both are persistent grids walking a tile list derived on the device from expert_off, so no host
 // synchronisation is needed to learn the data-dependent row counts.  Token rows are gathered
 // through row_token while staging the L operand (no permuted copy of X is required).
@@ -76,10 +79,16 @@ gateup_kernel(const T* __restrict__ x, const T* __restrict__ x_perm, const int32
   }
 }
 
-template <typename T, int BM, int BN>
+// exact GeLU: g * Phi(g)
+__device__ __forceinline__ float gelu_f(float g) { return 0.5f * g * (1.f + erff(g * 0.70710678118654752f)); }
+
+// Grouped product out[r, 0..d) = act(in[row(r), 0..f) W[e]) over the rows r of each expert e: the down projection
+// (GELU = false, rows read in place) and the first product of the GeLU expert (GELU = true, rows gathered
+// through row_token when GATHER).  d: output width, f: contraction length.
+template <typename T, int BM, int BN, bool GELU = false, bool GATHER = false>
 __global__ void __launch_bounds__(kThreads, 2)
-down_kernel(const T* __restrict__ h, const int32_t* __restrict__ expert_off, const T* __restrict__ w_down,
-            T* __restrict__ y, int d, int f, int E, int uniform_rows) {
+down_kernel(const T* __restrict__ h, const int32_t* __restrict__ row_token, const int32_t* __restrict__ expert_off,
+            const T* __restrict__ w_down, T* __restrict__ y, int d, int f, int E, int uniform_rows) {
   typedef Tile<T, BM, BN, 1> TL;
   extern __shared__ __align__(16) char smem[];
   __shared__ GroupTiles gt;
@@ -101,7 +110,8 @@ down_kernel(const T* __restrict__ h, const int32_t* __restrict__ expert_off, con
 #pragma unroll
     for (int i = 0; i < SrcRows<T, BM>::NV; ++i) {
       const int r = min((int)(threadIdx.x >> 3) + 32 * i, valid - 1);
-      L.p[i] = reinterpret_cast<const char*>(h + (size_t)(row0 + r) * f) + (threadIdx.x & 7) * 16;
+      const size_t src_row = GATHER ? (size_t)row_token[row0 + r] : (size_t)(row0 + r);
+      L.p[i] = reinterpret_cast<const char*>(h + src_row * f) + (threadIdx.x & 7) * 16;
     }
     SrcCols<T, BN> R[1];
     R[0].base = reinterpret_cast<const char*>(w_down + (size_t)e * f * d + n0);
@@ -125,7 +135,8 @@ down_kernel(const T* __restrict__ h, const int32_t* __restrict__ expert_off, con
           const int n = TL::acc_n(nt, g);
           if (n0 + n >= d) continue;
           const f32x16& A = acc[0][nt][mt];
-          store4(yrow + n, A[4 * g], A[4 * g + 1], A[4 * g + 2], A[4 * g + 3]);
+          if (GELU) store4(yrow + n, gelu_f(A[4 * g]), gelu_f(A[4 * g + 1]), gelu_f(A[4 * g + 2]), gelu_f(A[4 * g + 3]));
+          else store4(yrow + n, A[4 * g], A[4 * g + 1], A[4 * g + 2], A[4 * g + 3]);
         }
     }
   }
@@ -198,10 +209,11 @@ gateup_bf16_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ x_pe
   }
 }
 
-template <int BM>
+template <int BM, bool GELU = false, bool GATHER = false>
 __global__ void __launch_bounds__(kThreads2)
-down_bf16_kernel(const bf16_t* __restrict__ h, const int32_t* __restrict__ expert_off,
-                 const bf16_t* __restrict__ w_down, bf16_t* __restrict__ y, int d, int f, int E, int uniform_rows) {
+down_bf16_kernel(const bf16_t* __restrict__ h, const int32_t* __restrict__ row_token,
+                 const int32_t* __restrict__ expert_off, const bf16_t* __restrict__ w_down, bf16_t* __restrict__ y,
+                 int d, int f, int E, int uniform_rows) {
   constexpr int BN = 256;
   typedef Tile3<BM, BN> TL;
   DSMOE_TILE3_STAGES(TL, st);
@@ -217,7 +229,9 @@ down_bf16_kernel(const bf16_t* __restrict__ h, const int32_t* __restrict__ exper
     t.valid = min(BM, gt.row_off[t.e + 1] - t.row0);
     t.n0 = nt_blk * BN;
     const int row0 = t.row0;
-    L.init(t.valid, 0, [&](int r) { return h + (size_t)(row0 + r) * f; });
+    L.init(t.valid, 0, [&](int r) {
+      return h + (GATHER ? (size_t)row_token[row0 + r] : (size_t)(row0 + r)) * f;
+    });
     const bf16_t* const base[1] = {w_down + (size_t)t.e * f * d + t.n0};
     R.init(base, d, min(BN, d - t.n0), f);
   };
@@ -246,7 +260,7 @@ down_bf16_kernel(const bf16_t* __restrict__ h, const int32_t* __restrict__ exper
         acc, st,
         [&](int, int, const float (&v)[1][4], float (&o)[1][4]) {
 #pragma unroll
-          for (int i = 0; i < 4; ++i) o[0][i] = v[0][i];
+          for (int i = 0; i < 4; ++i) o[0][i] = GELU ? gelu_f(v[0][i]) : v[0][i];
         },
         [&](int m, int n, const u32x4 (&p)[1]) {
           if (m >= cur.valid || cur.n0 + n >= d) return;
@@ -268,13 +282,24 @@ static hipError_t launch_ffn_bf16(const dsmoe_ctx* c, const void* x, const void*
   const int g1 = (int)((std::min<long>(t1, c->n_cu) + 7) / 8 * 8), g2 = (int)((std::min<long>(t2, c->n_cu) + 7) / 8 * 8);
   hipEvent_t* ev = (c->prof.ev && c->prof.n < c->prof.max_calls) ? c->prof.ev + 3 * c->prof.n++ : nullptr;
   if (ev) (void)hipEventRecord(ev[0], s);
-  gateup_bf16_kernel<BM><<<dim3(g1), dim3(kThreads2), 0, s>>>(
-      (const bf16_t*)x, (const bf16_t*)x_perm, row_token, expert_off, (const bf16_t*)w_gate, (const bf16_t*)w_up, h,
-      d, f, E);
+  if (c->expert_kind == DSMOE_EXPERT_GELU) {
+    // H = gelu(rows W_1): output width f, contraction over d, 256-column tiles
+    const int g1g = (int)((std::min<long>(max_mt * ((f + 255) / 256), c->n_cu) + 7) / 8 * 8);
+    if (x_perm)
+      down_bf16_kernel<BM, true, false><<<dim3(g1g), dim3(kThreads2), 0, s>>>(
+          (const bf16_t*)x_perm, nullptr, expert_off, (const bf16_t*)w_gate, h, f, d, E, 0);
+    else
+      down_bf16_kernel<BM, true, true><<<dim3(g1g), dim3(kThreads2), 0, s>>>(
+          (const bf16_t*)x, row_token, expert_off, (const bf16_t*)w_gate, h, f, d, E, 0);
+  } else {
+    gateup_bf16_kernel<BM><<<dim3(g1), dim3(kThreads2), 0, s>>>(
+        (const bf16_t*)x, (const bf16_t*)x_perm, row_token, expert_off, (const bf16_t*)w_gate, (const bf16_t*)w_up, h,
+        d, f, E);
+  }
   hipError_t err = hipGetLastError();
   if (err != hipSuccess) return err;
   if (ev) (void)hipEventRecord(ev[1], s);
-  down_bf16_kernel<BM><<<dim3(g2), dim3(kThreads2), 0, s>>>(h, expert_off, (const bf16_t*)w_down,
+  down_bf16_kernel<BM><<<dim3(g2), dim3(kThreads2), 0, s>>>(h, nullptr, expert_off, (const bf16_t*)w_down,
                                                                         (bf16_t*)y_perm, d, f, E, 0);
   err = hipGetLastError();
   if (ev) (void)hipEventRecord(ev[2], s);
@@ -296,12 +321,22 @@ static hipError_t launch_ffn_t(const dsmoe_ctx* c, const void* x, const void* x_
   constexpr int lds1 = Tile<T, BM, BN1, 2>::LDS_BYTES, lds2 = Tile<T, BM, BN2, 1>::LDS_BYTES;
   hipEvent_t* ev = (c->prof.ev && c->prof.n < c->prof.max_calls) ? c->prof.ev + 3 * c->prof.n++ : nullptr;
   if (ev) (void)hipEventRecord(ev[0], s);
-  gateup_kernel<T, BM, BN1><<<dim3(g1), dim3(kThreads), lds1, s>>>(
-      (const T*)x, (const T*)x_perm, row_token, expert_off, (const T*)w_gate, (const T*)w_up, h, d, f, E);
+  if (c->expert_kind == DSMOE_EXPERT_GELU) {
+    const int g1g = (int)((std::min<long>(max_mt * ((f + BN2 - 1) / BN2), full) + 7) / 8 * 8);
+    if (x_perm)
+      down_kernel<T, BM, BN2, true, false><<<dim3(g1g), dim3(kThreads), lds2, s>>>(
+          (const T*)x_perm, nullptr, expert_off, (const T*)w_gate, h, f, d, E, 0);
+    else
+      down_kernel<T, BM, BN2, true, true><<<dim3(g1g), dim3(kThreads), lds2, s>>>(
+          (const T*)x, row_token, expert_off, (const T*)w_gate, h, f, d, E, 0);
+  } else {
+    gateup_kernel<T, BM, BN1><<<dim3(g1), dim3(kThreads), lds1, s>>>(
+        (const T*)x, (const T*)x_perm, row_token, expert_off, (const T*)w_gate, (const T*)w_up, h, d, f, E);
+  }
   hipError_t err = hipGetLastError();
   if (err != hipSuccess) return err;
   if (ev) (void)hipEventRecord(ev[1], s);
-  down_kernel<T, BM, BN2><<<dim3(g2), dim3(kThreads), lds2, s>>>((const T*)h, expert_off, (const T*)w_down,
+  down_kernel<T, BM, BN2><<<dim3(g2), dim3(kThreads), lds2, s>>>((const T*)h, nullptr, expert_off, (const T*)w_down,
                                                                  (T*)y_perm, d, f, E, 0);
   err = hipGetLastError();
   if (ev) (void)hipEventRecord(ev[2], s);
@@ -316,14 +351,14 @@ hipError_t launch_down_dense(const dsmoe_ctx* c, const void* h, int T, int k_tot
   if (c->desc.dtype == DSMOE_BF16) {
     const long tiles = (long)((T + 255) / 256) * ((d + 255) / 256);
     const int g = (int)((std::min<long>(tiles, c->n_cu) + 7) / 8 * 8);
-    down_bf16_kernel<256><<<dim3(g), dim3(kThreads2), 0, s>>>((const bf16_t*)h, nullptr, (const bf16_t*)w,
+    down_bf16_kernel<256><<<dim3(g), dim3(kThreads2), 0, s>>>((const bf16_t*)h, nullptr, nullptr, (const bf16_t*)w,
                                                                           (bf16_t*)out, d, k_total, 1, T);
   } else {
     constexpr int BM = 128, BN = 256;
     const long tiles = (long)((T + BM - 1) / BM) * ((d + BN - 1) / BN);
     const int g = (int)((std::min<long>(tiles, c->n_cu * 2) + 7) / 8 * 8);
     down_kernel<float, BM, BN><<<dim3(g), dim3(kThreads), Tile<float, BM, BN, 1>::LDS_BYTES, s>>>(
-        (const float*)h, nullptr, (const float*)w, (float*)out, d, k_total, 1, T);
+        (const float*)h, nullptr, nullptr, (const float*)w, (float*)out, d, k_total, 1, T);
   }
   return hipGetLastError();
 }

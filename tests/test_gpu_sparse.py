@@ -64,7 +64,8 @@ def run_staged_and_check(torch, dsmoe, inp, mode, k, eps, max_rows=None, materia
     say(f"[case] {cfg.name} T={T} d={cfg.d} E={E} f={cfg.f} {cfg.dtype} mode={mode} k={k} eps={eps} "
         f"materialize={materialize}")
     w = weights_to_dev(torch, inp)
-    layer = dsmoe.Layer(cfg.d, cfg.f, E, cfg.dtype, max_tokens=max(T, 1), max_rows=max_rows)
+    layer = dsmoe.Layer(cfg.d, cfg.f, E, cfg.dtype, max_tokens=max(T, 1), max_rows=max_rows,
+                        expert="gelu" if inp.w_up is None else "swiglu")
 
     S_ref = orc.route(inp.x, inp.w_r, inp.b_r)
     M_ref = orc.select(S_ref, mode, k, eps)
@@ -130,7 +131,7 @@ def run_staged_and_check(torch, dsmoe, inp, mode, k, eps, max_rows=None, materia
     np.testing.assert_array_equal(mask_to_bool(m2, E), M_ref)
     np.testing.assert_array_equal(eo2.cpu().numpy(), r_ref.expert_off)
     np.testing.assert_array_equal(rt2.cpu().numpy()[:nnz], r_ref.row_token)
-    if cfg.dtype == "bf16" and 0 < T <= 128:
+    if cfg.dtype == "bf16" and 0 < T <= 128 and inp.w_up is not None:
         # decode-sized batches take the weight-streaming kernels (fp32 partial sums, one final rounding)
         err2 = helpers.rel_err(out2.float().cpu().numpy(), O_ref)
         say(f"  weight-streaming path rel err {err2:.3e}")
@@ -189,6 +190,31 @@ def test_threshold_topk_selection(torch, dsmoe, name, T, dtype, eps):
     say(f"  Threshold-TopK: K = {K}")
     assert 1 <= K < cfg.E
     run_staged_and_check(torch, dsmoe, inp, "threshold_topk", 0, eps)
+
+
+@pytest.mark.parametrize("name,T,dtype,mode,k,eps,materialize", [
+    ("c1", 128, "f32", "topk", 2, 0.0, False), ("c1", 128, "f32", "threshold", 0, 0.13, True),
+    ("rag", 777, "bf16", "threshold", 0, 0.05, False), ("rag", 777, "f32", "topk", 3, 0.0, False),
+    ("rag", 40, "bf16", "topk", 3, 0.0, True)])
+def test_gelu_two_matrix_expert(torch, dsmoe, name, T, dtype, mode, k, eps, materialize):
+    """The paper's own expert (Sec. 4.1): e(x) = gelu(x W_1) W_2, through every staged call and the fused one."""
+    if name == "c1":
+        cfg = gen.CONFIGS["c1"].with_(name="c1_gelu", mode=mode, k=k, eps=eps)
+    else:
+        cfg = gen.LayerConfig("ragged_gelu", 13, T=T, d=320, E=16, f=192, dtype=dtype, mode=mode, k=k, eps=eps,
+                              router_std=0.08)
+    inp = conditioned(cfg, mode, k, eps)
+    inp.w_up = None
+    run_staged_and_check(torch, dsmoe, inp, mode, k, eps, materialize=materialize)
+
+
+def test_gelu_expert_has_no_dense_training_yet(torch, dsmoe):
+    layer = dsmoe.Layer(64, 64, 8, "f32", max_tokens=4, expert="gelu")
+    x = torch.zeros((4, 64), device="cuda:0")
+    w = torch.zeros((8, 64, 64), device="cuda:0")
+    with pytest.raises(dsmoe.DsmoeError) as ei:
+        layer.dense_fwd(x, torch.zeros((64, 8), device="cuda:0"), None, w, w, w)
+    assert ei.value.code == dsmoe.ERR_NOT_IMPL
 
 
 def test_skewed_router_bias_empty_and_hot_experts(torch, dsmoe):
