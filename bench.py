@@ -88,15 +88,22 @@ class Bench:
         return (time.perf_counter() - t0) / steps * 1e3
 
     # ---- sparse prefill (c2, c5) ---------------------------------------------------------------------
-    def sparse_prefill(self, name, steps, warmup, keep_inputs=False):
+    def sparse_prefill(self, name, steps, warmup, keep_inputs=False, expert="swiglu", threshold_topk=False):
+        """expert="gelu": the paper's two-matrix expert on the same shapes (W_up unused, 4 nnz d f flop);
+        threshold_topk: Threshold-TopK selection with the config's threshold."""
         torch, gen, dsmoe = self.torch, self.gen, self.dsmoe
         cfg = gen.CONFIGS[name]
         inp = gen.make_layer(cfg, 0)
         x, w_r, b_r = (self.to_dev(a, cfg.dtype) for a in (inp.x, inp.w_r, inp.b_r))
         w_gate, w_up, w_down = (self.to_dev(a, cfg.dtype) for a in (inp.w_gate, inp.w_up, inp.w_down))
+        gelu = expert == "gelu"
+        if gelu:
+            w_up = None
         max_rows = cfg.T * (16 if name == "c2" else 24)
-        layer = dsmoe.Layer(cfg.d, cfg.f, cfg.E, cfg.dtype, max_tokens=cfg.T, max_rows=max_rows)
+        layer = dsmoe.Layer(cfg.d, cfg.f, cfg.E, cfg.dtype, max_tokens=cfg.T, max_rows=max_rows, expert=expert)
         mode = dsmoe.SEL_TOPK if cfg.mode == "topk" else dsmoe.SEL_THRESHOLD
+        if threshold_topk:
+            mode = dsmoe.SEL_THRESHOLD_TOPK
         out = torch.empty((cfg.T, cfg.d), dtype=x.dtype, device=self.dev)
 
         def step():
@@ -115,12 +122,14 @@ class Bench:
         layer.profile_enable(0)
         assert n_calls == steps
         assert torch.isfinite(out.float()).all()
-        gateup_tf = 4.0 * nnz * cfg.d * cfg.f / (gateup_ms / n_calls * 1e-3) / 1e12
+        first_flops = (2.0 if gelu else 4.0) * nnz * cfg.d * cfg.f      # one or two products into the hidden width
+        gateup_tf = first_flops / (gateup_ms / n_calls * 1e-3) / 1e12
         down_tf = 2.0 * nnz * cfg.d * cfg.f / (down_ms / n_calls * 1e-3) / 1e12
-        layer_flops = 6.0 * nnz * cfg.d * cfg.f + 2.0 * cfg.T * cfg.d * cfg.E
+        layer_flops = first_flops + 2.0 * nnz * cfg.d * cfg.f + 2.0 * cfg.T * cfg.d * cfg.E
         res = {
             "workload": f"{name}: sparse prefill T={cfg.T} d_model={cfg.d} E={cfg.E} d_ff={cfg.f} "
-                        f"{cfg.mode} eps={cfg.eps} k={cfg.k}",
+                        f"{'threshold_topk' if threshold_topk else cfg.mode} eps={cfg.eps} k={cfg.k}"
+                        + (" expert=gelu(x W_1) W_2" if gelu else ""),
             "tokens_per_s": cfg.T / (ms * 1e-3), "ms_per_step": ms, "nnz": nnz,
             "active_fraction": nnz / (cfg.T * cfg.E),
             "rows_per_expert_min_max": [int((eo[1:] - eo[:-1]).min()), int((eo[1:] - eo[:-1]).max())],
@@ -242,8 +251,9 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workloads", default="c2,c3,c4,c5",
-                    help="comma-separated subset of c2,c3,c4,c5 (c2 is the headline and always runs)")
+    ap.add_argument("--workloads", default="c2,c3,c4,c5,c2x",
+                    help="comma-separated subset of c2,c3,c4,c5,c2x (c2 is the headline and always runs; c2x = "
+                         "c2's shapes with the GeLU two-matrix expert and with Threshold-TopK selection)")
     ap.add_argument("--cpu-passes", type=int, default=20, help="0 skips the CPU baseline")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MiB",
                     help="also run three plain device copies of this many MiB (a kernel of known HBM traffic, "
@@ -278,6 +288,9 @@ def main():
         others["c4"] = b.dense_training(side_steps, 3)
     if "c5" in wl:
         others["c5"] = b.sparse_prefill("c5", side_steps, 3)
+    if "c2x" in wl:   # the rows beyond the base scope, on the headline shapes
+        others["c2_gelu_expert"] = b.sparse_prefill("c2", side_steps, 3, expert="gelu")
+        others["c2_threshold_topk"] = b.sparse_prefill("c2", side_steps, 3, threshold_topk=True)
 
     result = {
         "metric": METRIC,
