@@ -98,8 +98,15 @@ dense_gateup_kernel(const T* __restrict__ x, const T* __restrict__ w_gate, const
     GM::mainloop(acc, L, R, d / GM::BK, 1 << 30, st);
     if constexpr (std::is_same<T, bf16_t>::value) {
       // bf16: the three outputs are formed in the accumulator layout and cross the LDS already rounded
-      auto pre = [&](int m, int, const float (&v)[2][4], auto& out) {
-        const float s = t0 + m < Tn ? S[(size_t)(t0 + m) * E + e] : 0.f;
+      // the scores of this lane's rows, read before the first store of the epilogue
+      float srow[GM::TL::MT];
+#pragma unroll
+      for (int i = 0; i < GM::TL::MT; ++i) {
+        const int t = t0 + GM::TL::acc_m(i);
+        srow[i] = t < Tn ? S[(size_t)t * E + e] : 0.f;
+      }
+      auto pre = [&](int mt_i, int, int, const float (&v)[2][4], auto& out) {
+        const float s = srow[mt_i];
         constexpr int NO = sizeof(out) / sizeof(out[0]);
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
@@ -174,26 +181,39 @@ dense_bwd_dh_kernel(const T* __restrict__ d_out, const T* __restrict__ w_down, c
       const float p = GM::row_sum(part);
       if (GM::row_leader()) red[GM::wave_n()][cur_m] = p;
     };
-    GM::for_each_chunk(acc, st, [&](int m, int n, const float (&v)[1][GM::CHUNK]) {
-      if (m != cur_m) { flush(); cur_m = m; part = 0.f; }
-      const int t = t0 + m, col = n0 + n;
-      if (t >= Tn || col >= f) return;
-      const float s = S[(size_t)t * E + e];
-      const size_t o = (size_t)t * EF + (size_t)e * f + col, od = (size_t)t * ldg + (size_t)e * f + col;
-      float g[GM::CHUNK], u[GM::CHUNK], du[GM::CHUNK], dg[GM::CHUNK];
-      load_chunk(G + o, g);
-      load_chunk(U + o, u);
+    // saved activations and the score of each chunk, requested a 32-row block ahead of their use
+    u32x4 gq[GM::NJ], uq[GM::NJ];
+    float sq[GM::NJ];
+    GM::for_each_chunk_loaded(
+        acc, st,
+        [&](int j, int m, int n) {
+          const int t = t0 + m, col = n0 + n;
+          if (t >= Tn || col >= f) return;
+          const size_t o = (size_t)t * EF + (size_t)e * f + col;
+          gq[j] = load_raw(G + o);
+          uq[j] = load_raw(U + o);
+          sq[j] = S[(size_t)t * E + e];
+        },
+        [&](int j, int m, int n, const float (&v)[1][GM::CHUNK]) {
+          if (m != cur_m) { flush(); cur_m = m; part = 0.f; }
+          const int t = t0 + m, col = n0 + n;
+          if (t >= Tn || col >= f) return;
+          const float s = sq[j];
+          const size_t od = (size_t)t * ldg + (size_t)e * f + col;
+          float g[GM::CHUNK], u[GM::CHUNK], du[GM::CHUNK], dg[GM::CHUNK];
+          unpack_chunk(gq[j], g, (const T*)nullptr);
+          unpack_chunk(uq[j], u, (const T*)nullptr);
 #pragma unroll
-      for (int i = 0; i < GM::CHUNK; ++i) {
-        const float sg = sigmoid_f(g[i]), sl = g[i] * sg;
-        part = fmaf(sl * u[i], v[0][i], part);
-        const float dh = s * v[0][i];
-        du[i] = dh * sl;
-        dg[i] = dh * u[i] * (sg * (1.f + g[i] * (1.f - sg)));
-      }
-      store_chunk(dU + od, du);
-      store_chunk(dG + od, dg);
-    });
+          for (int i = 0; i < GM::CHUNK; ++i) {
+            const float sg = sigmoid_f(g[i]), sl = g[i] * sg;
+            part = fmaf(sl * u[i], v[0][i], part);
+            const float dh = s * v[0][i];
+            du[i] = dh * sl;
+            dg[i] = dh * u[i] * (sg * (1.f + g[i] * (1.f - sg)));
+          }
+          store_chunk(dU + od, du);
+          store_chunk(dG + od, dg);
+        });
     flush();
     __syncthreads();
     for (int m = threadIdx.x; m < GM::BM; m += GM::THREADS) {

@@ -196,7 +196,7 @@ gateup_bf16_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ x_pe
     }
     TL::template for_each_chunk_bf16<1>(
         acc, st,
-        [&](int, int, const float (&v)[2][4], float (&o)[1][4]) {
+        [&](int, int, int, const float (&v)[2][4], float (&o)[1][4]) {
 #pragma unroll
           for (int i = 0; i < 4; ++i) o[0][i] = silu_f(v[0][i]) * v[1][i];
         },
@@ -258,7 +258,7 @@ down_bf16_kernel(const bf16_t* __restrict__ h, const int32_t* __restrict__ row_t
     }
     TL::template for_each_chunk_bf16<1>(
         acc, st,
-        [&](int, int, const float (&v)[1][4], float (&o)[1][4]) {
+        [&](int, int, int, const float (&v)[1][4], float (&o)[1][4]) {
 #pragma unroll
           for (int i = 0; i < 4; ++i) o[0][i] = GELU ? gelu_f(v[0][i]) : v[0][i];
         },

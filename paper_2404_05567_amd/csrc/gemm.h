@@ -68,6 +68,20 @@ __device__ __forceinline__ void store_chunk(bf16_t* p, const float (&v)[W]) {
     store4(p, v[0], v[1], v[2], v[3]);
   }
 }
+// Two-step form of load_chunk for epilogues that request their operands before they need them: load_raw issues
+// the 16-byte load of a chunk (4 floats or 8 bf16), unpack_chunk converts it.
+__device__ __forceinline__ u32x4 load_raw(const void* p) { return ldg16(p); }
+__device__ __forceinline__ void unpack_chunk(const u32x4& q, float (&v)[4], const float*) {
+  const f32x4 t = __builtin_bit_cast(f32x4, q);
+  v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w;
+}
+__device__ __forceinline__ void unpack_chunk(const u32x4& q, float (&v)[8], const bf16_t*) {
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    v[2 * i] = __uint_as_float(q[i] << 16);
+    v[2 * i + 1] = __uint_as_float(q[i] & 0xffff0000u);
+  }
+}
 template <int W>
 __device__ __forceinline__ void load_chunk(const float* p, float (&v)[W]) {
 #pragma unroll
@@ -159,6 +173,16 @@ struct Gemm<float, BM_, BN_, NSRC_, LK, RK, KTAIL> {
           f(TL::acc_m(mt), TL::acc_n(nt, g), v);
         }
   }
+  // Same walk with the operands of f requested first: load(j, m, n) is called for the chunks of a group, then
+  // f(j, m, n, v) for the same chunks; j < NJ numbers the chunks of a group (one chunk per group here).
+  static constexpr int NJ = 1;
+  template <class LD, class F>
+  static __device__ __forceinline__ void for_each_chunk_loaded(const Acc& acc, const Stages& st, LD load, F f) {
+    for_each_chunk(acc, st, [&](int m, int n, const float (&v)[NSRC][4]) {
+      load(0, m, n);
+      f(0, m, n, v);
+    });
+  }
   static __device__ __forceinline__ int wave_n() { return threadIdx.x >> 7; }
   // sum of p over the lanes that hold the same tile row in one for_each_chunk call; row_leader() is true on one of them
   static __device__ __forceinline__ float row_sum(float p) { return p + __shfl_xor(p, 32, 64); }
@@ -220,7 +244,12 @@ struct Gemm<bf16_t, BM_, BN_, NSRC_, LK, RK, KTAIL> {
   }
   template <class F>
   static __device__ __forceinline__ void for_each_chunk(const Acc& acc, const Stages& st, F f) {
-    TL::for_each_chunk(acc, st, f);
+    TL::for_each_chunk(acc, st, [](int, int, int) {}, [&](int, int m, int n, const float (&v)[NSRC][8]) { f(m, n, v); });
+  }
+  static constexpr int NJ = TL::NJ;
+  template <class LD, class F>
+  static __device__ __forceinline__ void for_each_chunk_loaded(const Acc& acc, const Stages& st, LD load, F f) {
+    TL::template for_each_chunk<true>(acc, st, load, f);
   }
   static __device__ __forceinline__ int wave_n() { return (threadIdx.x >> 6) % 4; }
   static __device__ __forceinline__ float row_sum(float p) {

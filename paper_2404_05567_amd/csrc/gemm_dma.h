@@ -76,6 +76,29 @@ __device__ __forceinline__ u32x2 lds_read_tr16(const lds_char* p) {
   const s16x4 v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p));
   return __builtin_bit_cast(u32x2, v);
 }
+// LDS accesses of the epilogues, written as assembly so that the compiler's wait-count insertion does not tie them
+// to the global -> LDS loads still in flight: it cannot tell which stage a read touches once the address is
+// selected at run time, and would put `s_waitcnt vmcnt(0)` before every read, which also waits for every
+// global store issued so far (one counter covers loads and stores), i.e. the epilogue would pay a full store
+// round trip per row block.  The caller guarantees that no load in flight targets the bytes read (the epilogues
+// use the wave's own slices of the last two stages, loads in flight go to the first ones).  LDS operations of a
+// wave execute in order, so the reads see the wave's earlier writes.
+__device__ __forceinline__ u32x4 lds_read16_free(const lds_char* p) {
+  u32x4 v;
+  asm volatile("ds_read_b128 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=v"(v) : "v"(p) : "memory");
+  return v;
+}
+__device__ __forceinline__ void lds_write8_free(lds_char* p, u32x2 v) {
+  asm volatile("ds_write_b64 %0, %1" : : "v"(p), "v"(v) : "memory");
+}
+__device__ __forceinline__ void lds_write16_free(lds_char* p, u32x4 v) {
+  asm volatile("ds_write_b128 %0, %1" : : "v"(p), "v"(v) : "memory");
+}
+__device__ __forceinline__ void lds_read16x2_free(const lds_char* p0, const lds_char* p1, u32x4& a, u32x4& b) {
+  asm volatile("ds_read_b128 %0, %2\n\tds_read_b128 %1, %3\n\ts_waitcnt lgkmcnt(0)"
+               : "=&v"(a), "=&v"(b) : "v"(p0), "v"(p1) : "memory");
+}
+
 // s_waitcnt on the vector-memory counter alone (N outstanding loads allowed), optionally also on all LDS reads
 template <int N, bool LGKM0>
 __device__ __forceinline__ void wait_vm() {
@@ -420,12 +443,30 @@ struct Tile3 {
   // (inside its source) and v[s][0..7]; 8 (NSRC = 1) or 4 (NSRC = 2) neighbouring lanes cover a row, so
   // global accesses made from f are whole 128-byte (bf16: 64..128-byte) row segments.
   static constexpr int CHUNK = 8;
-  template <class F>
-  static __device__ __forceinline__ void for_each_chunk(const Acc& acc, const Stages3& st, F f) {
+  // The thread index as a value the compiler cannot trace back to threadIdx: everything an epilogue derives from
+  // it (row and column of a lane, LDS offsets) is then computed inside the epilogue instead of being hoisted out
+  // of the tile loop and kept, spilled, across the main loop.  A spill reload is a vector-memory load, and the
+  // wait for it would also wait for every global store the epilogue has issued.
+  static __device__ __forceinline__ int epilogue_tid() {
+    int t = threadIdx.x;
+    asm volatile("" : "+v"(t));
+    return t;
+  }
+  // load(j, m, n) is called for the NJ chunks of a 32-row block before the block crosses the LDS, f(j, m, n, v)
+  // after: global loads an epilogue needs (saved activations ...) are then all in flight together and ahead of
+  // the block's stores, instead of each waiting behind the stores of the chunk before.
+  // LOADS: `load` really issues global loads.  They are then waited for once per block, before the block's first
+  // store: the compiler cannot count a load behind stores in flight (this ISA has one counter for both and lets
+  // them complete out of order), so a loaded value first used after a store costs a full drain of the stores.
+  static constexpr int NJ = NSRC == 1 ? 4 : 2;
+  template <bool LOADS = false, class LD, class F>
+  static __device__ __forceinline__ void for_each_chunk(const Acc& acc, const Stages3& st, LD load, F f) {
     static_assert(RSrc::LDS / 8 == 2048 && LSrc::LDS / 8 == 2048, "a wave's slice of a stage holds 8 rows of 64 floats");
     constexpr int OPR = NSRC == 1 ? 8 : 4;        // lanes (column octets) per row and source
     constexpr int RPI = 64 / OPR;                  // rows covered by one read instruction
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    static_assert(NJ == 32 / RPI, "chunks of a lane per 32-row block");
+    const int tid = epilogue_tid();
+    const int lane = tid & 63, wave = tid >> 6;
     const int wslice = wave * 2048;
     const int m = lane & 31, kg = lane >> 5;
     // the stage addresses are link-time constants: keep them as values (a table in memory would be indexed)
@@ -444,13 +485,17 @@ struct Tile3 {
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
 #pragma unroll
+      for (int j = 0; j < NJ; ++j)
+        load(j, (wave / WGN) * WM + mt * 32 + RPI * j + lane / OPR, (wave % WGN) * WCOL + 8 * q);
+#pragma unroll
       for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
           const int u = nt * 8 + g * 2 + kg;
           f32x4 v = {acc[nt][mt][4 * g], acc[nt][mt][4 * g + 1], acc[nt][mt][4 * g + 2], acc[nt][mt][4 * g + 3]};
-          *reinterpret_cast<lds_f32x4*>(wrow + ((u ^ (m & 15)) * 16)) = v;
+          lds_write16_free(wrow + ((u ^ (m & 15)) * 16), __builtin_bit_cast(u32x4, v));
         }
+      if constexpr (LOADS) wait_vm<0, false>();
 #pragma unroll
       for (int j = 0; j < 32 / RPI; ++j) {
         const int r = RPI * j + lane / OPR;
@@ -459,17 +504,18 @@ struct Tile3 {
 #pragma unroll
         for (int s = 0; s < NSRC; ++s) {
           const int ub = s * 8 + 2 * q;
-          const f32x4 a = *reinterpret_cast<const lds_f32x4*>(rrow + ((ub ^ (r & 15)) * 16));
-          const f32x4 b = *reinterpret_cast<const lds_f32x4*>(rrow + (((ub + 1) ^ (r & 15)) * 16));
+          u32x4 ua, ub4;
+          lds_read16x2_free(rrow + ((ub ^ (r & 15)) * 16), rrow + (((ub + 1) ^ (r & 15)) * 16), ua, ub4);
+          const f32x4 a = __builtin_bit_cast(f32x4, ua), b = __builtin_bit_cast(f32x4, ub4);
           v[s][0] = a.x; v[s][1] = a.y; v[s][2] = a.z; v[s][3] = a.w;
           v[s][4] = b.x; v[s][5] = b.y; v[s][6] = b.z; v[s][7] = b.w;
         }
-        f((wave / WGN) * WM + mt * 32 + r, (wave % WGN) * WCOL + 8 * q, v);
+        f(j, (wave / WGN) * WM + mt * 32 + r, (wave % WGN) * WCOL + 8 * q, v);
       }
     }
   }
 
-  // Packed variant for bf16 outputs: pre(m, n, v, out) runs in the accumulator layout (row m, 4 consecutive
+  // Packed variant for bf16 outputs: pre(mt, m, n, v, out) runs in the accumulator layout (row m, 4 consecutive
   // columns from n, v[s][0..3]) and produces NOUT values per element; they are rounded to bf16, staged (one
   // 2 KB piece of the wave's scratch slices per output and 32-column tile: 32 rows of 64 bytes, XOR-swizzled),
   // and handed to f(m, n, p) with p[o] = 8 consecutive bf16 of output o, 4 lanes covering a 64-byte row
@@ -479,7 +525,8 @@ struct Tile3 {
     static_assert(RSrc::LDS / 8 == 2048 && LSrc::LDS / 8 == 2048, "a wave's slice of a stage holds 32 rows of 64 bytes");
     constexpr int NTC = NSRC == 1 ? NT : 1;       // 32-column tiles of an output per wave
     static_assert(NOUT * NTC <= 4, "four scratch pieces per wave");
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int tid = epilogue_tid();
+    const int lane = tid & 63, wave = tid >> 6;
     const int m = lane & 31, kg = lane >> 5;
     lds_char* const piece[4] = {st.r[NST - 2] + wave * 2048, st.r[NST - 1] + wave * 2048,
                                 st.l[NST - 2] + wave * 2048, st.l[NST - 1] + wave * 2048};
@@ -497,11 +544,11 @@ struct Tile3 {
           for (int s = 0; s < NSRC; ++s)
 #pragma unroll
             for (int i = 0; i < 4; ++i) v[s][i] = acc[NSRC == 1 ? tc : s][mt][4 * g + i];
-          pre(acc_m(mt), acc_n(tc, g), v, out);
+          pre(mt, acc_m(mt), acc_n(tc, g), v, out);
 #pragma unroll
           for (int o = 0; o < NOUT; ++o) {
             const u32x2 pk = {pack_bf16x2(out[o][0], out[o][1]), pack_bf16x2(out[o][2], out[o][3])};
-            *reinterpret_cast<__attribute__((address_space(3))) u32x2*>(piece[o * NTC + tc] + woff + ((g ^ wsw) * 16)) = pk;
+            lds_write8_free(piece[o * NTC + tc] + woff + ((g ^ wsw) * 16), pk);
           }
         }
 #pragma unroll
@@ -512,7 +559,7 @@ struct Tile3 {
           u32x4 p[NOUT];
 #pragma unroll
           for (int o = 0; o < NOUT; ++o)
-            p[o] = *reinterpret_cast<const lds_u32x4*>(piece[o * NTC + tc] + r * 64 + ((rq ^ ((r >> 2) & 3)) * 16));
+            p[o] = lds_read16_free(piece[o * NTC + tc] + r * 64 + ((rq ^ ((r >> 2) & 3)) * 16));
           f((wave / WGN) * WM + mt * 32 + r, (wave % WGN) * WCOL + tc * 32 + 8 * rq, p);
         }
     }
