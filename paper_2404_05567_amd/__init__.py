@@ -116,6 +116,7 @@ class Layer:
         rc = self.lib.dsmoe_create(byref(desc), byref(self.ctx))
         if rc != OK:
             raise DsmoeError(rc, "dsmoe_create rejected the descriptor")
+        self.expert = expert
         self._check(self.lib.dsmoe_set_expert_kind(self.ctx, {"swiglu": EXPERT_SWIGLU, "gelu": EXPERT_GELU}[expert]))
         nbytes = c_size_t()
         self._check(self.lib.dsmoe_workspace_bytes(self.ctx, byref(nbytes)))
@@ -223,7 +224,7 @@ class Layer:
                     dx=self._empty((T, self.d), self.tdtype), dw_r=self._empty((self.d, self.E), t.float32),
                     db_r=self._empty((self.E,), t.float32) if with_bias_grad else None,
                     dw_gate=self._empty((self.E, self.d, self.f), t.float32),
-                    dw_up=self._empty((self.E, self.d, self.f), t.float32),
+                    dw_up=self._empty((self.E, self.d, self.f), t.float32) if self.expert == "swiglu" else None,
                     dw_down=self._empty((self.E, self.f, self.d), t.float32))
 
     def dense_fwd(self, x, w_r, b_r, w_gate, w_up, w_down, want_probs=False, save=False, buffers=None):
@@ -263,7 +264,7 @@ class Layer:
             g = dict(dx=self._empty((T, self.d), self.tdtype), dw_r=self._empty((self.d, self.E), t.float32),
                      db_r=self._empty((self.E,), t.float32) if with_bias_grad else None,
                      dw_gate=self._empty((self.E, self.d, self.f), t.float32),
-                     dw_up=self._empty((self.E, self.d, self.f), t.float32),
+                     dw_up=self._empty((self.E, self.d, self.f), t.float32) if self.expert == "swiglu" else None,
                      dw_down=self._empty((self.E, self.f, self.d), t.float32))
         args = (self.ctx, _ptr(x), _ptr(w_r), _ptr(w_gate), _ptr(w_up), _ptr(w_down), _ptr(saved), _ptr(d_out), T,
                 _ptr(scratch), _ptr(g["dx"]), _ptr(g["dw_r"]), _ptr(g["db_r"]), _ptr(g["dw_gate"]), _ptr(g["dw_up"]),

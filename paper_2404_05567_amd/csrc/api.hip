@@ -383,11 +383,9 @@ int32_t dsmoe_dense_fwd(dsmoe_ctx* c, const void* x, const void* w_r, const void
                         const void* w_up, const void* w_down, int32_t T, void* out, float* probs, void* saved,
                         void* stream) {
   if (int32_t rc = check_call(c, T, true)) return rc;
-  if (c->expert_kind != DSMOE_EXPERT_SWIGLU)
-    return fail(c, DSMOE_ERR_NOT_IMPL, "dense training is implemented for the SwiGLU expert only");
   if (T == 0) return DSMOE_OK;
-  REQUIRE_PTR(c, x); REQUIRE_PTR(c, w_r); OPTIONAL_PTR(c, b_r); REQUIRE_PTR(c, w_gate); REQUIRE_PTR(c, w_up);
-  REQUIRE_PTR(c, w_down); REQUIRE_PTR(c, out); OPTIONAL_PTR(c, probs); OPTIONAL_PTR(c, saved);
+  REQUIRE_PTR(c, x); REQUIRE_PTR(c, w_r); OPTIONAL_PTR(c, b_r); REQUIRE_EXPERT_WEIGHTS(c, w_gate, w_up, w_down);
+  REQUIRE_PTR(c, out); OPTIONAL_PTR(c, probs); OPTIONAL_PTR(c, saved);
   if (!saved && (int64_t)T * c->desc.n_experts > c->desc.max_rows)
     return fail(c, DSMOE_ERR_WORKSPACE, "dense forward without a `saved` buffer keeps T * E = %lld hidden rows in the "
                 "workspace, which holds max_rows = %lld", (long long)T * c->desc.n_experts, (long long)c->desc.max_rows);
@@ -403,21 +401,21 @@ int32_t dsmoe_dense_bwd_mi(dsmoe_ctx* c, const void* x, const void* w_r, const v
                            void* dx, float* dw_r, float* db_r, float* dw_gate, float* dw_up, float* dw_down,
                            float mi_alpha, void* stream) {
   if (int32_t rc = check_call(c, T, false)) return rc;
-  if (c->expert_kind != DSMOE_EXPERT_SWIGLU)
-    return fail(c, DSMOE_ERR_NOT_IMPL, "dense training is implemented for the SwiGLU expert only");
   if (!std::isfinite(mi_alpha)) return fail(c, DSMOE_ERR_INVALID_ARG, "mi_alpha must be finite");
-  REQUIRE_PTR(c, dw_r); OPTIONAL_PTR(c, db_r); REQUIRE_PTR(c, dw_gate); REQUIRE_PTR(c, dw_up); REQUIRE_PTR(c, dw_down);
+  const bool swiglu = c->expert_kind == DSMOE_EXPERT_SWIGLU;   // the two-matrix expert has no w_up and no dw_up
+  REQUIRE_PTR(c, dw_r); OPTIONAL_PTR(c, db_r); REQUIRE_PTR(c, dw_gate); REQUIRE_PTR(c, dw_down);
+  if (swiglu) REQUIRE_PTR(c, dw_up);
   if (T == 0) {   // no tokens: every weight gradient is zero
     hipStream_t s = static_cast<hipStream_t>(stream);
     const size_t d = c->desc.d_model, f = c->desc.d_ff, E = c->desc.n_experts;
     HIP_TRY(c, hipMemsetAsync(dw_r, 0, d * E * 4, s));
     if (db_r) HIP_TRY(c, hipMemsetAsync(db_r, 0, E * 4, s));
     HIP_TRY(c, hipMemsetAsync(dw_gate, 0, E * d * f * 4, s));
-    HIP_TRY(c, hipMemsetAsync(dw_up, 0, E * d * f * 4, s));
+    if (swiglu) HIP_TRY(c, hipMemsetAsync(dw_up, 0, E * d * f * 4, s));
     HIP_TRY(c, hipMemsetAsync(dw_down, 0, E * d * f * 4, s));
     return DSMOE_OK;
   }
-  REQUIRE_PTR(c, x); REQUIRE_PTR(c, w_r); REQUIRE_PTR(c, w_gate); REQUIRE_PTR(c, w_up); REQUIRE_PTR(c, w_down);
+  REQUIRE_PTR(c, x); REQUIRE_PTR(c, w_r); REQUIRE_EXPERT_WEIGHTS(c, w_gate, w_up, w_down);
   REQUIRE_PTR(c, saved); REQUIRE_PTR(c, d_out); REQUIRE_PTR(c, scratch); REQUIRE_PTR(c, dx);
   hipError_t e = launch_dense_bwd(c, x, w_r, w_gate, w_up, w_down, saved, d_out, T, scratch, dx, dw_r, db_r,
                                   dw_gate, dw_up, dw_down, mi_alpha, static_cast<hipStream_t>(stream));

@@ -71,6 +71,11 @@ ScratchLayout scratch_layout(const dsmoe_ctx* c, int T) {
 }
 
 __device__ __forceinline__ float sigmoid_f(float g) { return 1.f / (1.f + __expf(-g)); }
+// exact GeLU g * Phi(g) and its derivative Phi(g) + g * phi(g) (the two-matrix expert of Sec. 4.1)
+__device__ __forceinline__ float gelu_cdf_f(float g) { return 0.5f * (1.f + erff(g * 0.70710678118654752f)); }
+__device__ __forceinline__ float gelu_prime_f(float g) {
+  return gelu_cdf_f(g) + g * 0.3989422804014327f * __expf(-0.5f * g * g);
+}
 
 // ---- forward: gate / up products of every expert on every token --------------------------------------
 template <typename T>
@@ -148,8 +153,49 @@ dense_gateup_kernel(const T* __restrict__ x, const T* __restrict__ w_gate, const
   }
 }
 
-// ---- backward: D_j = dO W_down[j]^T, then the SwiGLU backward and the score-gradient partial sums -----
+// ---- forward, two-matrix GeLU expert: G = X W_1 of every expert on every token, Ht = S gelu(G) -----------
 template <typename T>
+__global__ void __launch_bounds__((Gemm<T, DenseTiles<T>::BM, DenseTiles<T>::BN1, 1, false, true>::THREADS))
+dense_gelu1_kernel(const T* __restrict__ x, const T* __restrict__ w_1, const float* __restrict__ S, T* __restrict__ G,
+                   T* __restrict__ Ht, int Tn, int d, int f, int E) {
+  typedef Gemm<T, DenseTiles<T>::BM, DenseTiles<T>::BN1, 1, false, true> GM;
+  DSMOE_GEMM_STAGES(GM, st);
+  const int n_mt = (Tn + GM::BM - 1) / GM::BM, n_nt = (f + GM::BN - 1) / GM::BN;
+  const size_t EF = (size_t)E * f;
+  TileWalker tw;
+  tw.init(E * n_mt * n_nt);
+  int idx;
+  while (tw.next(idx)) {
+    const int nt = idx % n_nt, mt = (idx / n_nt) % n_mt, e = idx / (n_nt * n_mt);
+    const int t0 = mt * GM::BM, n0 = nt * GM::BN;
+    typename GM::LSrc L;
+    GM::l_rows(L, min(GM::BM, Tn - t0), 0, [&](int r) { return x + (size_t)(t0 + r) * d; });
+    typename GM::RSrc R;
+    const T* const base[1] = {w_1 + (size_t)e * d * f + n0};
+    GM::r_cols(R, base, f, f - n0, d);
+    typename GM::Acc acc;
+    GM::zero(acc);
+    GM::mainloop(acc, L, R, d / GM::BK, 1 << 30, st);
+    float sq[GM::NJ];
+    GM::for_each_chunk_loaded(
+        acc, st,
+        [&](int j, int m, int) { sq[j] = t0 + m < Tn ? S[(size_t)(t0 + m) * E + e] : 0.f; },
+        [&](int j, int m, int n, const float (&v)[1][GM::CHUNK]) {
+          const int t = t0 + m, col = n0 + n;
+          if (t >= Tn || col >= f) return;
+          const size_t o = (size_t)t * EF + (size_t)e * f + col;
+          if (G != nullptr) store_chunk(G + o, v[0]);
+          float h[GM::CHUNK];
+#pragma unroll
+          for (int i = 0; i < GM::CHUNK; ++i) h[i] = sq[j] * v[0][i] * gelu_cdf_f(v[0][i]);
+          store_chunk(Ht + o, h);
+        });
+  }
+}
+
+// ---- backward: D_j = dO W_down[j]^T, then the SwiGLU backward and the score-gradient partial sums -----
+// GELU: the expert is gelu(x W_1) W_2: dG = S D gelu'(G), grad S partial = sum gelu(G) D; U and dU are not touched.
+template <typename T, bool GELU>
 __global__ void __launch_bounds__((Gemm<T, DenseTiles<T>::BM, DenseTiles<T>::BN1, 1, false, false>::THREADS))
 dense_bwd_dh_kernel(const T* __restrict__ d_out, const T* __restrict__ w_down, const float* __restrict__ S,
                     const T* __restrict__ G, const T* __restrict__ U, T* __restrict__ dU, T* __restrict__ dG,
@@ -191,7 +237,7 @@ dense_bwd_dh_kernel(const T* __restrict__ d_out, const T* __restrict__ w_down, c
           if (t >= Tn || col >= f) return;
           const size_t o = (size_t)t * EF + (size_t)e * f + col;
           gq[j] = load_raw(G + o);
-          uq[j] = load_raw(U + o);
+          if constexpr (!GELU) uq[j] = load_raw(U + o);
           sq[j] = S[(size_t)t * E + e];
         },
         [&](int j, int m, int n, const float (&v)[1][GM::CHUNK]) {
@@ -202,6 +248,15 @@ dense_bwd_dh_kernel(const T* __restrict__ d_out, const T* __restrict__ w_down, c
           const size_t od = (size_t)t * ldg + (size_t)e * f + col;
           float g[GM::CHUNK], u[GM::CHUNK], du[GM::CHUNK], dg[GM::CHUNK];
           unpack_chunk(gq[j], g, (const T*)nullptr);
+          if constexpr (GELU) {
+#pragma unroll
+            for (int i = 0; i < GM::CHUNK; ++i) {
+              part = fmaf(g[i] * gelu_cdf_f(g[i]), v[0][i], part);
+              dg[i] = s * v[0][i] * gelu_prime_f(g[i]);
+            }
+            store_chunk(dG + od, dg);
+            return;
+          }
           unpack_chunk(uq[j], u, (const T*)nullptr);
 #pragma unroll
           for (int i = 0; i < GM::CHUNK; ++i) {
@@ -228,15 +283,16 @@ dense_bwd_dh_kernel(const T* __restrict__ d_out, const T* __restrict__ w_down, c
   }
 }
 
-// ---- backward: dW_down[j] = Ht_j^T dO (contraction over tokens) ------------------------------------------
+// ---- backward: out[j] = A_j^T B_j, contraction over tokens ------------------------------------------------
+// A_j = A[:, j * a_es .. + M), B_j = B[:, j * b_es .. + N) (row pitches lda, ldb); out[j] is [M][N].
+// dW_down[j] = Ht_j^T dO (a_es = f, b_es = 0) and, for the two-matrix expert, dW_1[j] = X^T dG_j (a_es = 0, b_es = f).
 template <typename T>
 __global__ void __launch_bounds__((Gemm<T, DenseTiles<T>::BM, DenseTiles<T>::BN1, 1, true, true, true>::THREADS))
-dense_bwd_dwdown_kernel(const T* __restrict__ Ht, const T* __restrict__ d_out, float* __restrict__ dw_down, int Tn,
-                        int d, int f, int E, const void* __restrict__ zeros) {
+dense_bwd_dwdown_kernel(const T* __restrict__ A, size_t lda, int a_es, int M, const T* __restrict__ B, size_t ldb,
+                        int b_es, int N, float* __restrict__ out, int Tn, int E, const void* __restrict__ zeros) {
   typedef Gemm<T, DenseTiles<T>::BM, DenseTiles<T>::BN1, 1, true, true, true> GM;
   DSMOE_GEMM_STAGES(GM, st);
-  const int n_mt = (f + GM::BM - 1) / GM::BM, n_nt = (d + GM::BN - 1) / GM::BN;
-  const size_t EF = (size_t)E * f;
+  const int n_mt = (M + GM::BM - 1) / GM::BM, n_nt = (N + GM::BN - 1) / GM::BN;
   TileWalker tw;
   tw.init(E * n_mt * n_nt);
   int idx;
@@ -244,16 +300,16 @@ dense_bwd_dwdown_kernel(const T* __restrict__ Ht, const T* __restrict__ d_out, f
     const int nt = idx % n_nt, mt = (idx / n_nt) % n_mt, e = idx / (n_nt * n_mt);
     const int m0 = mt * GM::BM, n0 = nt * GM::BN;
     typename GM::LSrc L;
-    GM::l_cols(L, Ht + (size_t)e * f + m0, EF, f - m0, Tn, zeros);
+    GM::l_cols(L, A + (size_t)e * a_es + m0, lda, M - m0, Tn, zeros);
     typename GM::RSrc R;
-    const T* const base[1] = {d_out + n0};
-    GM::r_cols(R, base, d, d - n0, Tn, zeros);
+    const T* const base[1] = {B + (size_t)e * b_es + n0};
+    GM::r_cols(R, base, ldb, N - n0, Tn, zeros);
     typename GM::Acc acc;
     GM::zero(acc);
     GM::mainloop(acc, L, R, (Tn + GM::BK - 1) / GM::BK, 1 << 30, st);
     GM::for_each_chunk(acc, st, [&](int m, int n, const float (&v)[1][GM::CHUNK]) {
-      if (m0 + m >= f || n0 + n >= d) return;
-      store_chunk(dw_down + ((size_t)e * f + m0 + m) * d + n0 + n, v[0]);
+      if (m0 + m >= M || n0 + n >= N) return;
+      store_chunk(out + ((size_t)e * M + m0 + m) * N + n0 + n, v[0]);
     });
   }
 }
@@ -291,7 +347,8 @@ dense_bwd_dwgu_kernel(const T* __restrict__ x, const T* __restrict__ dG, const T
 }
 
 // ---- backward: dX = sum_j dU_j W_up[j]^T + dG_j W_gate[j]^T + dZ W_r^T -----------------------------------
-template <typename T>
+// GELU: dX = sum_j dG_j W_1[j]^T + dZ W_r^T (no up projection).
+template <typename T, bool GELU>
 __global__ void __launch_bounds__((Gemm<T, DenseTiles<T>::BM, DenseTiles<T>::BN1, 1, false, false>::THREADS))
 dense_bwd_dx_kernel(const T* __restrict__ dU, const T* __restrict__ dG, const T* __restrict__ w_up,
                     const T* __restrict__ w_gate, const T* __restrict__ w_rp, T* __restrict__ dx, int Tn, int d, int f,
@@ -317,17 +374,25 @@ dense_bwd_dx_kernel(const T* __restrict__ dU, const T* __restrict__ dG, const T*
       typename GM::LSrc L;
       typename GM::RSrc R;
       const long long segL = (long long)f * sizeof(T), segR = (long long)d * f * sizeof(T);
-      GM::l_rows(L, min(GM::BM, Tn - t0), (size_t)segL, [&](int r) { return dU + (size_t)(t0 + r) * ldg; });
-      GM::r_rows(R, min(GM::BN, d - n0), (size_t)segR, [&](int r) { return w_up + (size_t)(n0 + r) * f; });
-      const long long dL = (const char*)dG - (const char*)dU, dR1 = (const char*)w_gate - (const char*)w_up,
-                      dR2 = (const char*)w_rp - (const char*)w_up;
-      L.set_jump(0, E, dL - E * segL);
-      R.set_jump(0, E, dR1 - E * segR);
-      R.set_jump(1, 2 * E, dR2 - dR1 - E * segR);
-      GM::mainloop(acc, L, R, 2 * (int)(EF / GM::BK) + EP / GM::BK, f / GM::BK, st);
+      if constexpr (GELU) {
+        // E segments dG_j W_1[j]^T, then dG's pad columns against the repacked W_r
+        GM::l_rows(L, min(GM::BM, Tn - t0), (size_t)segL, [&](int r) { return dG + (size_t)(t0 + r) * ldg; });
+        GM::r_rows(R, min(GM::BN, d - n0), (size_t)segR, [&](int r) { return w_gate + (size_t)(n0 + r) * f; });
+        R.set_jump(0, E, ((const char*)w_rp - (const char*)w_gate) - E * segR);
+        GM::mainloop(acc, L, R, (int)(EF / GM::BK) + EP / GM::BK, f / GM::BK, st);
+      } else {
+        GM::l_rows(L, min(GM::BM, Tn - t0), (size_t)segL, [&](int r) { return dU + (size_t)(t0 + r) * ldg; });
+        GM::r_rows(R, min(GM::BN, d - n0), (size_t)segR, [&](int r) { return w_up + (size_t)(n0 + r) * f; });
+        const long long dL = (const char*)dG - (const char*)dU, dR1 = (const char*)w_gate - (const char*)w_up,
+                        dR2 = (const char*)w_rp - (const char*)w_up;
+        L.set_jump(0, E, dL - E * segL);
+        R.set_jump(0, E, dR1 - E * segR);
+        R.set_jump(1, 2 * E, dR2 - dR1 - E * segR);
+        GM::mainloop(acc, L, R, 2 * (int)(EF / GM::BK) + EP / GM::BK, f / GM::BK, st);
+      }
     } else {
 #pragma unroll 1
-      for (int part = 0; part < 3; ++part) {
+      for (int part = GELU ? 1 : 0; part < 3; ++part) {
         typename GM::LSrc L;
         typename GM::RSrc R;
         if (part < 2) {
@@ -462,14 +527,22 @@ hipError_t dense_fwd_t(const dsmoe_ctx* c, const void* x, const void* w_gate, co
   typedef Gemm<T, DenseTiles<T>::BM, DenseTiles<T>::BN2, 2, false, true> GM;
   const int d = c->desc.d_model, f = c->desc.d_ff, E = c->desc.n_experts;
   constexpr int bpc = sizeof(T) == 4 ? 2 : 1;
+  typedef Gemm<T, DenseTiles<T>::BM, DenseTiles<T>::BN1, 1, false, true> GM1;
   static bool attrs = false;
   if (!attrs) {
     if (hipError_t e = set_lds(dense_gateup_kernel<T>, GM::LDS_BYTES)) return e;
+    if (hipError_t e = set_lds(dense_gelu1_kernel<T>, GM1::LDS_BYTES)) return e;
     attrs = true;
   }
-  const long tiles = (long)E * ((Tn + GM::BM - 1) / GM::BM) * ((f + GM::BN - 1) / GM::BN);
-  dense_gateup_kernel<T><<<dim3(grid_for(c, tiles, bpc)), dim3(GM::THREADS), GM::LDS_BYTES, s>>>(
-      (const T*)x, (const T*)w_gate, (const T*)w_up, S, G, U, Ht, Tn, d, f, E);
+  if (c->expert_kind == DSMOE_EXPERT_GELU) {
+    const long tiles = (long)E * ((Tn + GM1::BM - 1) / GM1::BM) * ((f + GM1::BN - 1) / GM1::BN);
+    dense_gelu1_kernel<T><<<dim3(grid_for(c, tiles, bpc)), dim3(GM1::THREADS), GM1::LDS_BYTES, s>>>(
+        (const T*)x, (const T*)w_gate, S, G, Ht, Tn, d, f, E);
+  } else {
+    const long tiles = (long)E * ((Tn + GM::BM - 1) / GM::BM) * ((f + GM::BN - 1) / GM::BN);
+    dense_gateup_kernel<T><<<dim3(grid_for(c, tiles, bpc)), dim3(GM::THREADS), GM::LDS_BYTES, s>>>(
+        (const T*)x, (const T*)w_gate, (const T*)w_up, S, G, U, Ht, Tn, d, f, E);
+  }
   if (hipError_t e = hipGetLastError()) return e;
   return launch_down_dense(c, Ht, Tn, E * f, w_down, out, s);
 }
@@ -502,17 +575,24 @@ hipError_t dense_bwd_t(const dsmoe_ctx* c, const void* x, const void* w_r, const
 
   static bool attrs = false;
   if (!attrs) {
-    if (hipError_t e = set_lds(dense_bwd_dh_kernel<T>, GRR::LDS_BYTES)) return e;
-    if (hipError_t e = set_lds(dense_bwd_dx_kernel<T>, GRR::LDS_BYTES)) return e;
+    if (hipError_t e = set_lds(dense_bwd_dh_kernel<T, false>, GRR::LDS_BYTES)) return e;
+    if (hipError_t e = set_lds(dense_bwd_dh_kernel<T, true>, GRR::LDS_BYTES)) return e;
+    if (hipError_t e = set_lds(dense_bwd_dx_kernel<T, false>, GRR::LDS_BYTES)) return e;
+    if (hipError_t e = set_lds(dense_bwd_dx_kernel<T, true>, GRR::LDS_BYTES)) return e;
     if (hipError_t e = set_lds(dense_bwd_dwdown_kernel<T>, GCC1::LDS_BYTES)) return e;
     if (hipError_t e = set_lds(dense_router_dw_kernel<T>, GCC1::LDS_BYTES)) return e;
     if (hipError_t e = set_lds(dense_bwd_dwgu_kernel<T>, GCC2::LDS_BYTES)) return e;
     attrs = true;
   }
 
+  const bool gelu = c->expert_kind == DSMOE_EXPERT_GELU;
   long tiles = E * cdiv(Tn, DT::BM) * cdiv(f, DT::BN1);
-  dense_bwd_dh_kernel<T><<<dim3(grid_for(c, tiles, bpc)), dim3(GRR::THREADS), GRR::LDS_BYTES, s>>>(
-      (const T*)d_out, (const T*)w_down, S, G, U, dU, dG, dS_part, Tn, d, f, E, sc.ldg);
+  if (gelu)
+    dense_bwd_dh_kernel<T, true><<<dim3(grid_for(c, tiles, bpc)), dim3(GRR::THREADS), GRR::LDS_BYTES, s>>>(
+        (const T*)d_out, (const T*)w_down, S, G, U, dU, dG, dS_part, Tn, d, f, E, sc.ldg);
+  else
+    dense_bwd_dh_kernel<T, false><<<dim3(grid_for(c, tiles, bpc)), dim3(GRR::THREADS), GRR::LDS_BYTES, s>>>(
+        (const T*)d_out, (const T*)w_down, S, G, U, dU, dG, dS_part, Tn, d, f, E, sc.ldg);
   if (hipError_t e = hipGetLastError()) return e;
 
   const float* p_mean = nullptr;
@@ -543,17 +623,27 @@ hipError_t dense_bwd_t(const dsmoe_ctx* c, const void* x, const void* w_r, const
 
   tiles = E * cdiv(f, DT::BM) * cdiv(d, DT::BN1);
   dense_bwd_dwdown_kernel<T><<<dim3(grid_for(c, tiles, bpc)), dim3(GCC1::THREADS), GCC1::LDS_BYTES, s>>>(
-      Ht, (const T*)d_out, dw_down, Tn, d, f, E, scratch + sc.zeros);
+      Ht, (size_t)E * f, f, f, (const T*)d_out, (size_t)d, 0, d, dw_down, Tn, E, scratch + sc.zeros);
   if (hipError_t e = hipGetLastError()) return e;
 
-  tiles = E * cdiv(d, DT::BM) * cdiv(f, DT::BN2);
-  dense_bwd_dwgu_kernel<T><<<dim3(grid_for(c, tiles, bpc)), dim3(GCC2::THREADS), GCC2::LDS_BYTES, s>>>(
-      (const T*)x, dG, dU, dw_gate, dw_up, Tn, d, f, E, sc.ldg, scratch + sc.zeros);
+  if (gelu) {   // dW_1[j] = X^T dG_j
+    tiles = E * cdiv(d, DT::BM) * cdiv(f, DT::BN1);
+    dense_bwd_dwdown_kernel<T><<<dim3(grid_for(c, tiles, bpc)), dim3(GCC1::THREADS), GCC1::LDS_BYTES, s>>>(
+        (const T*)x, (size_t)d, 0, d, dG, sc.ldg, f, f, dw_gate, Tn, E, scratch + sc.zeros);
+  } else {
+    tiles = E * cdiv(d, DT::BM) * cdiv(f, DT::BN2);
+    dense_bwd_dwgu_kernel<T><<<dim3(grid_for(c, tiles, bpc)), dim3(GCC2::THREADS), GCC2::LDS_BYTES, s>>>(
+        (const T*)x, dG, dU, dw_gate, dw_up, Tn, d, f, E, sc.ldg, scratch + sc.zeros);
+  }
   if (hipError_t e = hipGetLastError()) return e;
 
   tiles = cdiv(Tn, DT::BM) * cdiv(d, DT::BN1);
-  dense_bwd_dx_kernel<T><<<dim3(grid_for(c, tiles, bpc)), dim3(GRR::THREADS), GRR::LDS_BYTES, s>>>(
-      dU, dG, (const T*)w_up, (const T*)w_gate, w_rp, (T*)dx, Tn, d, f, E, sc.EP, sc.ldg);
+  if (gelu)
+    dense_bwd_dx_kernel<T, true><<<dim3(grid_for(c, tiles, bpc)), dim3(GRR::THREADS), GRR::LDS_BYTES, s>>>(
+        dU, dG, (const T*)w_up, (const T*)w_gate, w_rp, (T*)dx, Tn, d, f, E, sc.EP, sc.ldg);
+  else
+    dense_bwd_dx_kernel<T, false><<<dim3(grid_for(c, tiles, bpc)), dim3(GRR::THREADS), GRR::LDS_BYTES, s>>>(
+        dU, dG, (const T*)w_up, (const T*)w_gate, w_rp, (T*)dx, Tn, d, f, E, sc.EP, sc.ldg);
   return hipGetLastError();
 }
 

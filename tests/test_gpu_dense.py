@@ -273,3 +273,45 @@ def test_dense_backward_with_the_mi_loss_term(torch, dsmoe, name, T):
     g0 = layer.dense_bwd(w["x"], w["w_r"], w["w_gate"], w["w_up"], w["w_down"], saved, w["d_out"], with_bias_grad=True)
     torch.cuda.synchronize()
     assert helpers.rel_err(host(g0["dw_r"]), gr.dW_r) <= tol
+
+
+# --------------------------------------------------------------------------------------------------
+# the paper's two-matrix GeLU expert (Sec. 4.1) in dense training
+# --------------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("name,T,bias", [("c1", 128, False), ("c1", 100, True), ("c4", 300, False), ("c4", 777, True)])
+def test_dense_training_with_the_gelu_expert(torch, dsmoe, name, T, bias):
+    base = gen.CONFIGS[name]
+    cfg = base.with_(name=f"{name}_gelu", T=T) if name == "c1" else \
+        base.with_(name="c4_small_gelu", T=T, d=512, f=128 if T == 300 else 192, router_std=1.5 / np.sqrt(512))
+    tol = TOL[cfg.dtype]
+    say(f"[case] dense GeLU expert {cfg.name} T={cfg.T} d={cfg.d} E={cfg.E} f={cfg.f} {cfg.dtype} bias={bias}")
+    inp = gen.make_layer(cfg, 5, with_grad=True)
+    inp.w_up = None
+    if bias:
+        g = np.random.default_rng(cfg.index + 50)
+        b = (g.standard_normal(cfg.E) * 0.5).astype(np.float32)
+        inp.b_r = gen.round_to_bf16(b) if cfg.dtype == "bf16" else b
+    w = to_dev(torch, inp)
+    layer = dsmoe.Layer(cfg.d, cfg.f, cfg.E, cfg.dtype, max_tokens=cfg.T, expert="gelu")
+    O_ref, S_ref, _ = orc.dense_forward(inp.x, inp.w_r, inp.b_r, inp.w_gate, None, inp.w_down)
+    gr = orc.dense_backward(inp.x, inp.w_r, inp.b_r, inp.w_gate, None, inp.w_down, inp.d_out)
+
+    out, probs, saved = layer.dense_fwd(w["x"], w["w_r"], w["b_r"], w["w_gate"], None, w["w_down"],
+                                        want_probs=True, save=True)
+    torch.cuda.synchronize()
+    assert helpers.rel_err(host(probs), S_ref) <= 1e-5
+    err = helpers.rel_err(host(out), O_ref)
+    say(f"  forward rel err {err:.3e}")
+    assert err <= tol
+    out2, _, _ = layer.dense_fwd(w["x"], w["w_r"], w["b_r"], w["w_gate"], None, w["w_down"])   # nothing saved
+    torch.cuda.synchronize()
+    assert torch.equal(out2, out)
+
+    g = layer.dense_bwd(w["x"], w["w_r"], w["w_gate"], None, w["w_down"], saved, w["d_out"], with_bias_grad=True)
+    torch.cuda.synchronize()
+    assert g["dw_up"] is None
+    for key, ref in (("dx", gr.dX), ("dw_r", gr.dW_r), ("db_r", gr.db_r), ("dw_gate", gr.dW_gate),
+                     ("dw_down", gr.dW_down)):
+        err = helpers.rel_err(host(g[key]), ref)
+        say(f"  {key} rel err {err:.3e}")
+        assert err <= tol, key

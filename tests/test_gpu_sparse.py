@@ -208,15 +208,6 @@ def test_gelu_two_matrix_expert(torch, dsmoe, name, T, dtype, mode, k, eps, mate
     run_staged_and_check(torch, dsmoe, inp, mode, k, eps, materialize=materialize)
 
 
-def test_gelu_expert_has_no_dense_training_yet(torch, dsmoe):
-    layer = dsmoe.Layer(64, 64, 8, "f32", max_tokens=4, expert="gelu")
-    x = torch.zeros((4, 64), device="cuda:0")
-    w = torch.zeros((8, 64, 64), device="cuda:0")
-    with pytest.raises(dsmoe.DsmoeError) as ei:
-        layer.dense_fwd(x, torch.zeros((64, 8), device="cuda:0"), None, w, w, w)
-    assert ei.value.code == dsmoe.ERR_NOT_IMPL
-
-
 def test_skewed_router_bias_empty_and_hot_experts(torch, dsmoe):
     cfg = gen.LayerConfig("skew", 12, T=500, d=256, E=24, f=128, dtype="bf16", mode="threshold", eps=0.04,
                           router_std=0.05, zipf_s=2.0)
