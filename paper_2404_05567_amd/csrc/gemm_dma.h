@@ -138,12 +138,15 @@ struct DRows {
     brk[i] = at;
     jump[i] = bytes;
   }
-  __device__ __forceinline__ void issue(lds_char* stage, int seg, int kin) const {
+  // load instruction i (of NI) of a K step
+  __device__ __forceinline__ void issue_one(lds_char* stage, int seg, int kin, int i) const {
     const long long off = (long long)seg * (long long)seg_stride + (long long)kin * 64 +
                           (seg >= brk[0] ? jump[0] : 0ll) + (seg >= brk[1] ? jump[1] : 0ll);
-    lds_char* dst = stage + (threadIdx.x >> 6) * (CPW * 1024);
+    dma16(p[i] + off, stage + (threadIdx.x >> 6) * (CPW * 1024) + i * 1024);
+  }
+  __device__ __forceinline__ void issue(lds_char* stage, int seg, int kin) const {
 #pragma unroll
-    for (int i = 0; i < CPW; ++i) dma16(p[i] + off, dst + i * 1024);
+    for (int i = 0; i < CPW; ++i) issue_one(stage, seg, kin, i);
   }
   // lane offset of the fragment of 32 rows starting at `first` (a multiple of 32), K slice ks
   static __device__ __forceinline__ int frag_off(int first, int ks) {
@@ -191,18 +194,18 @@ struct DCols {
       p[i] = reinterpret_cast<const char*>(base[src] + (size_t)k * ld_elems + (cs < cols_valid ? cs : 0));
     }
   }
-  __device__ __forceinline__ void issue(lds_char* stage, int seg, int kin) const {
+  __device__ __forceinline__ void issue_one(lds_char* stage, int seg, int kin, int i) const {
     const size_t off = (size_t)seg * seg_stride + (size_t)kin * step_bytes;
-    lds_char* dst = stage + (threadIdx.x >> 6) * (CPW * 1024);
-#pragma unroll
-    for (int i = 0; i < CPW; ++i) {
-      const char* g = p[i] + off;
-      if (KTAIL) {
-        const int k = kin * kBK2 + ((threadIdx.x >> 6) * CPW + i) * KPC + (threadIdx.x & 63) / PPR;
-        g = k < k_valid ? g : zeros;
-      }
-      dma16(g, dst + i * 1024);
+    const char* g = p[i] + off;
+    if (KTAIL) {
+      const int k = kin * kBK2 + ((threadIdx.x >> 6) * CPW + i) * KPC + (threadIdx.x & 63) / PPR;
+      g = k < k_valid ? g : zeros;
     }
+    dma16(g, stage + (threadIdx.x >> 6) * (CPW * 1024) + i * 1024);
+  }
+  __device__ __forceinline__ void issue(lds_char* stage, int seg, int kin) const {
+#pragma unroll
+    for (int i = 0; i < CPW; ++i) issue_one(stage, seg, kin, i);
   }
   // lane offset (without the column-unit term) of a fragment, K slice ks; unit_off(first) adds the columns
   static __device__ __forceinline__ int frag_off(int first, int ks) {
@@ -302,6 +305,12 @@ struct Tile3 {
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt) Mma<bf16_t>::run(acc[nt][mt], f.w[nt], f.x[mt]);
   }
+  // the MFMAs I0 <= nt * MT + mt < I1 of mma()
+  template <int I0, int I1>
+  static __device__ __forceinline__ void mma_range(Acc& acc, const Frag& f) {
+#pragma unroll
+    for (int i = I0; i < I1; ++i) Mma<bf16_t>::run(acc[i / MT][i % MT], f.w[i / MT], f.x[i % MT]);
+  }
   // issue order for the scheduler: the LDS reads of the next slice go out two per MFMA, so that the last of
   // them has the remaining MFMAs to arrive
   static __device__ __forceinline__ void interleave() {
@@ -319,6 +328,33 @@ struct Tile3 {
     // steps past the end re-read the last one (only the variant for ragged step counts asks for them)
     if (++it.next < nkt && ++it.kin == seg_tiles) { it.kin = 0; ++it.seg; }
   }
+  struct Loop {   // what a K step needs besides the stage number
+    Acc& acc; Frag& fa; Frag& fb; const LSrc& L; const RSrc& R; Iter& it; int nkt, seg_tiles; const Stages3& st;
+    const Offs& o;
+  };
+  // the same, one load instruction at a time: P = 0 .. NI-1, the position advances after the last one
+  template <int P>
+  static __device__ __forceinline__ void issue_part(const LSrc& L, const RSrc& R, Iter& it, int nkt, int seg_tiles,
+                                                    lds_char* sl, lds_char* sr) {
+    if constexpr (P < LSrc::NI) L.issue_one(sl, it.seg, it.kin, P);
+    else R.issue_one(sr, it.seg, it.kin, P - LSrc::NI);
+    if constexpr (P == NI - 1)
+      if (++it.next < nkt && ++it.kin == seg_tiles) { it.kin = 0; ++it.seg; }
+  }
+  // second half of a K step when it refills a stage: the next slice's fragment reads ride on the first NG MFMAs,
+  // then every load instruction of the refill is followed by one MFMA, so that the matrix pipe works through the
+  // address arithmetic and the load issue instead of idling behind the barrier
+  template <int P, int M0>
+  static __device__ __forceinline__ void refill_and_mma(const Loop& q, lds_char* sl, lds_char* sr) {
+    if constexpr (P < NI) {
+      issue_part<P>(q.L, q.R, q.it, q.nkt, q.seg_tiles, sl, sr);
+      if constexpr (M0 < NMMA) mma_range<M0, M0 + 1>(q.acc, q.fb);
+      __builtin_amdgcn_sched_barrier(0);
+      refill_and_mma<P + 1, (M0 < NMMA ? M0 + 1 : M0)>(q, sl, sr);
+    } else {
+      mma_range<M0, NMMA>(q.acc, q.fb);
+    }
+  }
 
   // First part of the prologue: K steps 0 .. NST-3 into the stages of the same number.  May be called as soon
   // as every wave has left the previous run() (nobody reads the stages any more), e.g. before the previous
@@ -333,10 +369,6 @@ struct Tile3 {
     }
   }
 
-  struct Loop {   // what a K step needs besides the stage number
-    Acc& acc; Frag& fa; Frag& fb; const LSrc& L; const RSrc& R; Iter& it; int nkt, seg_tiles; const Stages3& st;
-    const Offs& o;
-  };
   // One K step on stage ST: slice 0 multiplies while slice 1 is read; then, once step + 1 has landed for
   // every wave (and every wave has read this stage to the end), the stage is refilled with step + NST and
   // slice 0 of the next stage is read while slice 1 multiplies.  WAITN: loads that may stay in flight.
@@ -350,11 +382,18 @@ struct Tile3 {
     wait_vm<WAITN, true>();
     __builtin_amdgcn_s_barrier();
     __builtin_amdgcn_sched_barrier(0);
-    if constexpr (ISSUE) issue_step(q.L, q.R, q.it, q.nkt, q.seg_tiles, q.st.l[ST], q.st.r[ST]);
-    __builtin_amdgcn_sched_barrier(0);
-    read_frags(q.fa, q.st.l[NX], q.st.r[NX], q.o, 0);
-    mma(q.acc, q.fb);
-    interleave();
+    if constexpr (ISSUE) {
+      constexpr int NG = (NFR + 1) / 2 < NMMA ? (NFR + 1) / 2 : NMMA;
+      read_frags(q.fa, q.st.l[NX], q.st.r[NX], q.o, 0);
+      mma_range<0, NG>(q.acc, q.fb);
+      Interleave<0, NG, NFR, kSgDsRd>::run();
+      __builtin_amdgcn_sched_barrier(0);
+      refill_and_mma<0, NG>(q, q.st.l[ST], q.st.r[ST]);
+    } else {
+      read_frags(q.fa, q.st.l[NX], q.st.r[NX], q.o, 0);
+      mma(q.acc, q.fb);
+      interleave();
+    }
   }
   // N consecutive refilling steps from stage ST
   template <int ST, int N>
