@@ -69,8 +69,7 @@ const char* dsmoe_last_error(const dsmoe_ctx* ctx);
 /* The expert e_i of Eq. 1.  DSMOE_EXPERT_SWIGLU (default): e(x) = (silu(x W_gate) * (x W_up)) W_down.
  * DSMOE_EXPERT_GELU: the paper's own two-matrix MLP (Sec. 4.1), e(x) = gelu(x W_1) W_2 with the exact
  * GeLU g * Phi(g); W_1 is passed as w_gate, W_2 as w_down; w_up and, in the backward pass, dw_up are
- * ignored (may be NULL).  Applies to every call that evaluates experts; dsmoe_sparse_fwd then uses the
- * grouped kernels at every batch size. */
+ * ignored (may be NULL).  Applies to every call that evaluates experts. */
 int32_t dsmoe_set_expert_kind(dsmoe_ctx* ctx, int32_t kind);
 
 /* Scratch memory the library needs (intermediate H = silu(G)*U rows, block histograms, the routing

@@ -340,7 +340,7 @@ int32_t dsmoe_sparse_fwd(dsmoe_ctx* c, const void* x, const void* w_r, const voi
   } else {
     HIP_TRY(c, launch_route(c, x, w_r, b_r, T, probs, mode, k, eps, mask, cnt_tok, s));
   }
-  if (c->desc.dtype == DSMOE_BF16 && T <= kDecodeMaxTokens && c->expert_kind == DSMOE_EXPERT_SWIGLU) {
+  if (c->desc.dtype == DSMOE_BF16 && T <= kDecodeMaxTokens) {
     // decode-sized batch: weight-streaming kernels that derive the dispatch from the masks themselves
     HIP_TRY(c, launch_decode_fwd(c, x, w_gate, w_up, w_down, T, out, s));
     return DSMOE_OK;

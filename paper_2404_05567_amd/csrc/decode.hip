@@ -112,6 +112,8 @@ __device__ __forceinline__ bool arrive_last(int32_t* counter, int expected) {
 }
 
 // ---- gate / up: partial G, U over one K chunk ----------------------------------------------------------
+// GELU: the two-matrix expert, H = gelu(x W_1) with W_1 passed as w_gate; items are 128-column slices of one product.
+template <bool GELU>
 __global__ void __launch_bounds__(kThreads2)
 decode_gateup_kernel(const bf16_t* __restrict__ x, const unsigned long long* __restrict__ mask,
                      const float* __restrict__ probs, const bf16_t* __restrict__ w_gate,
@@ -120,8 +122,10 @@ decode_gateup_kernel(const bf16_t* __restrict__ x, const unsigned long long* __r
                      long long max_rows, int row_cap, int32_t* __restrict__ info, int32_t* __restrict__ expert_off,
                      int32_t* __restrict__ row_token, float* __restrict__ row_weight, int32_t* __restrict__ tok_off,
                      int32_t* __restrict__ tok_rows, int32_t* __restrict__ nnz_out, int32_t* __restrict__ err_flag) {
-  constexpr int BNS = kDecSlice;                 // columns of gate and of up per item
-  typedef Tile3<kDecT, 2 * BNS, 2, false, true, false, 6, 2> TL;   // six stages: more weight bytes in flight
+  constexpr int BNS = GELU ? 2 * kDecSlice : kDecSlice;   // hidden-width columns per item
+  // six stages: more weight bytes in flight; 128 token rows x 128 weight columns (64 gate + 64 up, or 128 of W_1)
+  typedef std::conditional_t<GELU, Tile3<kDecT, 2 * kDecSlice, 1, false, true, false, 6, 2>,
+                             Tile3<kDecT, 2 * kDecSlice, 2, false, true, false, 6, 2>> TL;
   DSMOE_TILE3_STAGES(TL, st);
   __shared__ DecodePlan plan;
   __shared__ int toks[kDecT];
@@ -142,8 +146,13 @@ decode_gateup_kernel(const bf16_t* __restrict__ x, const unsigned long long* __r
     L.init(Me, 0, [&](int r) { return x + (size_t)toks[r] * d + (size_t)c * kc; });
     typename TL::RSrc R;
     const size_t wo = (size_t)e * d * f + (size_t)c * kc * f + n0;
-    const bf16_t* const base[2] = {w_gate + wo, w_up + wo};
-    R.init(base, f, min(BNS, f - n0), kc);
+    if constexpr (GELU) {
+      const bf16_t* const base[1] = {w_gate + wo};
+      R.init(base, f, min(BNS, f - n0), kc);
+    } else {
+      const bf16_t* const base[2] = {w_gate + wo, w_up + wo};
+      R.init(base, f, min(BNS, f - n0), kc);
+    }
     typename TL::Acc acc;
     TL::zero(acc);
     TL::mainloop(acc, L, R, kc / kBK2, 1 << 30, st);
@@ -154,6 +163,18 @@ decode_gateup_kernel(const bf16_t* __restrict__ x, const unsigned long long* __r
         const int mrow = TL::acc_m(mt);
         if (mrow >= Me) continue;
         bf16_t* hrow = H + (size_t)(hrow0 + mrow) * f;
+        if constexpr (GELU) {
+#pragma unroll
+          for (int nt = 0; nt < TL::NT; ++nt)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+              const int n = n0 + TL::acc_n(nt, g);
+              if (n >= f) continue;
+              const f32x16& G = acc[nt][mt];
+              store4(hrow + n, gelu_f(G[4 * g]), gelu_f(G[4 * g + 1]), gelu_f(G[4 * g + 2]), gelu_f(G[4 * g + 3]));
+            }
+          continue;
+        }
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
           const int n = n0 + TL::acc_n(0, g);
@@ -172,6 +193,18 @@ decode_gateup_kernel(const bf16_t* __restrict__ x, const unsigned long long* __r
       const int mrow = TL::acc_m(mt);
       if (mrow >= Me) continue;
       float* prow = P1 + ((size_t)c * plan.nnz + hrow0 + mrow) * (2 * (size_t)f);
+      if constexpr (GELU) {
+#pragma unroll
+        for (int nt = 0; nt < TL::NT; ++nt)
+#pragma unroll
+          for (int g = 0; g < 4; ++g) {
+            const int n = n0 + TL::acc_n(nt, g);
+            if (n >= f) continue;
+            const f32x16& G = acc[nt][mt];
+            store4(prow + n, G[4 * g], G[4 * g + 1], G[4 * g + 2], G[4 * g + 3]);
+          }
+        continue;
+      }
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
         const int n = n0 + TL::acc_n(0, g);
@@ -197,17 +230,20 @@ decode_gateup_kernel(const bf16_t* __restrict__ x, const unsigned long long* __r
         for (int q = 0; q < 4; ++q)
           if (c0 + q < plan.ks1) {
             gv[q] = __builtin_bit_cast(f32x4, ldg16(p + (size_t)(c0 + q) * cstride));
-            uv[q] = __builtin_bit_cast(f32x4, ldg16(p + (size_t)(c0 + q) * cstride + f));
+            if constexpr (!GELU) uv[q] = __builtin_bit_cast(f32x4, ldg16(p + (size_t)(c0 + q) * cstride + f));
           }
 #pragma unroll
         for (int q = 0; q < 4; ++q)
           if (c0 + q < plan.ks1) {
             g += gv[q];
-            u += uv[q];
+            if constexpr (!GELU) u += uv[q];
           }
       }
-      store4(H + (size_t)(hrow0 + r) * f + n, silu_f(g.x) * u.x, silu_f(g.y) * u.y, silu_f(g.z) * u.z,
-             silu_f(g.w) * u.w);
+      if constexpr (GELU)
+        store4(H + (size_t)(hrow0 + r) * f + n, gelu_f(g.x), gelu_f(g.y), gelu_f(g.z), gelu_f(g.w));
+      else
+        store4(H + (size_t)(hrow0 + r) * f + n, silu_f(g.x) * u.x, silu_f(g.y) * u.y, silu_f(g.z) * u.z,
+               silu_f(g.w) * u.w);
     }
   }
   if (blockIdx.x == gridDim.x - 1) {   // publish the routing objects of this call: later kernels read them,
@@ -389,9 +425,14 @@ hipError_t launch_decode_fwd(const dsmoe_ctx* c, const void* x, const void* w_ga
   const int grid = (c->n_cu + 7) / 8 * 8;
   const int row_cap = decode_row_cap(c);
 
-  decode_gateup_kernel<<<dim3(grid), dim3(kThreads2), 0, s>>>(
-      (const bf16_t*)x, mask, probs, (const bf16_t*)w_gate, (const bf16_t*)w_up, P1, H, arrivals, T, d, f, E,
-      (long long)c->desc.max_rows, row_cap, info, expert_off, row_token, row_weight, tok_off, tok_rows, nnz, err_flag);
+  if (c->expert_kind == DSMOE_EXPERT_GELU)
+    decode_gateup_kernel<true><<<dim3(grid), dim3(kThreads2), 0, s>>>(
+        (const bf16_t*)x, mask, probs, (const bf16_t*)w_gate, nullptr, P1, H, arrivals, T, d, f, E,
+        (long long)c->desc.max_rows, row_cap, info, expert_off, row_token, row_weight, tok_off, tok_rows, nnz, err_flag);
+  else
+    decode_gateup_kernel<false><<<dim3(grid), dim3(kThreads2), 0, s>>>(
+        (const bf16_t*)x, mask, probs, (const bf16_t*)w_gate, (const bf16_t*)w_up, P1, H, arrivals, T, d, f, E,
+        (long long)c->desc.max_rows, row_cap, info, expert_off, row_token, row_weight, tok_off, tok_rows, nnz, err_flag);
   if (hipError_t e = hipGetLastError()) return e;
   decode_down_kernel<<<dim3(grid), dim3(kThreads2), 0, s>>>(H, info, expert_off, (const bf16_t*)w_down,
                                                                          P2, d, f, E);

@@ -79,9 +79,6 @@ gateup_kernel(const T* __restrict__ x, const T* __restrict__ x_perm, const int32
   }
 }
 
-// exact GeLU: g * Phi(g)
-__device__ __forceinline__ float gelu_f(float g) { return 0.5f * g * (1.f + erff(g * 0.70710678118654752f)); }
-
 // Grouped product out[r, 0..d) = act(in[row(r), 0..f) W[e]) over the rows r of each expert e: the down projection
 // (GELU = false, rows read in place) and the first product of the GeLU expert (GELU = true, rows gathered
 // through row_token when GATHER).  d: output width, f: contraction length.

@@ -305,5 +305,7 @@ struct TileWalker {
 };
 
 __device__ __forceinline__ float silu_f(float g) { return g / (1.f + __expf(-g)); }
+// exact GeLU: g * Phi(g)
+__device__ __forceinline__ float gelu_f(float g) { return 0.5f * g * (1.f + erff(g * 0.70710678118654752f)); }
 
 }  // namespace dsmoe
