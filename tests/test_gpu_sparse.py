@@ -321,8 +321,8 @@ def test_repeated_calls_are_bitwise_identical(torch, dsmoe):
 # --------------------------------------------------------------------------------------------------
 # full benchmark sizes, in the launch configuration bench.py times (dsmoe_sparse_fwd)
 # --------------------------------------------------------------------------------------------------
-def full_size_check(torch, dsmoe, name, n_sample, max_rows):
-    cfg = gen.CONFIGS[name]
+def full_size_check(torch, dsmoe, name, n_sample, max_rows, cfg=None):
+    cfg = gen.CONFIGS[name] if cfg is None else cfg
     say(f"[case] full-size {name}: generating inputs")
     inp = conditioned(cfg, cfg.mode, cfg.k, cfg.eps)
     T, E = cfg.T, cfg.E
@@ -365,3 +365,13 @@ def test_c2_full_size_sparse_prefill(torch, dsmoe):
 def test_c5_full_size_skewed_prefill(torch, dsmoe):
     r = full_size_check(torch, dsmoe, "c5", n_sample=48, max_rows=16384 * 24)
     assert r.cnt_exp.max() > 10 * r.cnt_exp.min()
+
+
+@pytest.mark.parametrize("T", [512, 96])
+def test_largest_layer_of_the_paper(torch, dsmoe, T):
+    """The expert layer of the largest model in the paper's speed test (Table 6: embedding 7168, 32 experts of
+    hidden width 896, top-4), as a prefill-sized call (grouped kernels) and a decode-sized one (weight-streaming
+    kernels); sampled output rows against the checker."""
+    cfg = gen.LayerConfig(f"ds_moe_19b_T{T}", 15, T=T, d=7168, E=32, f=896, dtype="bf16", mode="topk", k=4,
+                          router_std=1.5 / np.sqrt(7168))
+    full_size_check(torch, dsmoe, cfg.name, n_sample=min(T, 16), max_rows=4 * T, cfg=cfg)
