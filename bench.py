@@ -188,14 +188,16 @@ class Bench:
         }
 
     # ---- decode sizes (c3) --------------------------------------------------------------------------
-    def decode(self, steps, warmup, n_sets=16):
+    def decode(self, steps, warmup, n_sets=16, shape=None):
         """T in {1, 8, 32, 128} x {top-4, threshold 0.02} on the c2 layer shape.  The loop cycles through
         `n_sets` independent weight sets (3.2 GB in all), as a model's layers would, so no call finds its
         weights in the 256 MB last-level cache.  Timed both as plain launches and as a replayed HIP graph of
-        the n_sets calls (a serving loop would use the latter; it removes the host's launch cost)."""
+        the n_sets calls (a serving loop would use the latter; it removes the host's launch cost).
+        shape = (d_model, d_ff, E) runs another layer shape the same way."""
         torch, gen, dsmoe = self.torch, self.gen, self.dsmoe
         cfg = gen.CONFIGS["c3"]
-        d, f, E = cfg.d, cfg.f, cfg.E
+        d, f, E = (cfg.d, cfg.f, cfg.E) if shape is None else shape
+        router_std = cfg.router_std if shape is None else 1.5 / d ** 0.5
         g = torch.Generator(device=self.dev)
         g.manual_seed(gen.BASE_SEED + 3000)
         bf = torch.bfloat16
@@ -203,7 +205,7 @@ class Bench:
         def rnd(shape, std):
             return (torch.randn(shape, generator=g, device=self.dev, dtype=torch.float32) * std).to(bf)
 
-        sets = [dict(w_r=rnd((d, E), cfg.router_std), w_gate=rnd((E, d, f), 0.02), w_up=rnd((E, d, f), 0.02),
+        sets = [dict(w_r=rnd((d, E), router_std), w_gate=rnd((E, d, f), 0.02), w_up=rnd((E, d, f), 0.02),
                      w_down=rnd((E, f, d), 0.02)) for _ in range(n_sets)]
         layer = dsmoe.Layer(d, f, E, "bf16", max_tokens=128)
         results = []
@@ -243,7 +245,9 @@ class Bench:
                     "gb_per_s": bytes_per_call / (best * 1e-3) / 1e9,
                     "frac_of_hbm_peak": bytes_per_call / (best * 1e-3) / 1e9 / PEAK_HBM_GBS,
                 })
-        return {"workload": f"c3: sparse decode on the c2 layer, {n_sets} weight sets cycled", "cases": results}
+        name = "c3: sparse decode on the c2 layer" if shape is None else \
+            f"sparse decode, layer d_model={d} E={E} d_ff={f}"
+        return {"workload": f"{name}, {n_sets} weight sets cycled", "cases": results}
 
 
 def main():
@@ -284,6 +288,9 @@ def main():
     others = {}
     if "c3" in wl:
         others["c3"] = b.decode(side_steps, 3)
+        # context: the same path on the expert layer of the largest model in the paper's speed test (Table 6:
+        # embedding 7168, 32 experts of width 896), where a layer's weights are 1.2 GB and launch costs matter less
+        others["c3_largest_paper_layer"] = b.decode(max(5, side_steps // 2), 2, n_sets=3, shape=(7168, 896, 32))
     if "c4" in wl:
         others["c4"] = b.dense_training(side_steps, 3)
     if "c5" in wl:
