@@ -16,8 +16,12 @@
  *   - Layouts are row-major: X[T,d], W_r[d,E], b_r[E], W_gate[E,d,f], W_up[E,d,f], W_down[E,f,d],
  *     with d = d_model, E = n_experts, f = d_ff.  "dtype" tensors hold fp32 or bf16 values as chosen
  *     in the descriptor; router probabilities, row weights and all accumulators are fp32.
- *   - The expert is a SwiGLU MLP without biases: e(x) = (silu(x W_gate) * (x W_up)) W_down.
+ *   - The expert is a SwiGLU MLP without biases: e(x) = (silu(x W_gate) * (x W_up)) W_down (default), or the
+ *     paper's two-matrix GeLU MLP (dsmoe_set_expert_kind).
  *   - T = 0 is a valid no-op.
+ *   - A context and its workspace serve one call at a time: calls that use the workspace (or the same
+ *     `saved` / `scratch` buffers) must be ordered on one stream or by events; a context is not
+ *     thread-safe.  Work of one call is ordered after the previous call's on the same stream.
  *   - Return value: DSMOE_OK or a negative dsmoe_status; dsmoe_last_error() gives a message for the
  *     last failing call on that context.  Errors found on the host (bad arguments) enqueue nothing.
  *     A capacity overflow (more dispatched rows than max_rows) is found on the device: the dispatch
