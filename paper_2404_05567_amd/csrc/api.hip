@@ -249,8 +249,10 @@ int32_t dsmoe_route(dsmoe_ctx* c, const void* x, const void* w_r, const void* b_
 
 int32_t dsmoe_select(dsmoe_ctx* c, const float* probs, int32_t T, int32_t mode, int32_t k, float eps,
                      uint64_t* mask, int32_t* cnt_tok, void* stream) {
-  if (int32_t rc = check_call(c, T, mode == DSMOE_SEL_THRESHOLD_TOPK)) return rc;
+  if (int32_t rc = check_call(c, T, false)) return rc;
   if (int32_t rc = check_select_args(c, mode, k, eps)) return rc;
+  if (mode == DSMOE_SEL_THRESHOLD_TOPK)
+    if (int32_t rc = check_call(c, T, true)) return rc;   // the counts and K of the first pass live in the workspace
   if (T == 0) return DSMOE_OK;
   REQUIRE_PTR(c, probs); REQUIRE_PTR(c, mask);
   if (cnt_tok && (reinterpret_cast<uintptr_t>(cnt_tok) & 3u)) return fail(c, DSMOE_ERR_INVALID_ARG, "cnt_tok misaligned");

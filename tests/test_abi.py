@@ -79,6 +79,17 @@ def test_calls_reject_bad_arguments_before_any_device_work(lib):
     assert lib.dsmoe_sparse_fwd(ctx, fake, fake, None, fake, fake, fake, 4, dsmoe.SEL_TOPK, 2, 0.0, fake, s) \
         == dsmoe.ERR_WORKSPACE
     assert lib.dsmoe_expert_ffn(ctx, fake, None, fake, fake, fake, fake, fake, fake, s) == dsmoe.ERR_WORKSPACE
+    # the later entry points: Threshold-TopK needs the workspace, the loss needs tokens, the expert kind is checked
+    assert lib.dsmoe_select(ctx, fake, 4, dsmoe.SEL_THRESHOLD_TOPK, 0, 0.1, fake, None, s) == dsmoe.ERR_WORKSPACE
+    assert lib.dsmoe_select(ctx, fake, 4, dsmoe.SEL_THRESHOLD_TOPK, 0, -1.0, fake, None, s) == dsmoe.ERR_INVALID_ARG
+    assert lib.dsmoe_mi_loss(ctx, fake, 4, fake, fake, s) == dsmoe.ERR_WORKSPACE
+    assert lib.dsmoe_set_expert_kind(ctx, 7) == dsmoe.ERR_INVALID_ARG
+    assert lib.dsmoe_set_expert_kind(ctx, dsmoe.EXPERT_GELU) == dsmoe.OK
+    assert lib.dsmoe_set_expert_kind(ctx, dsmoe.EXPERT_SWIGLU) == dsmoe.OK
+    import ctypes as ct
+    bad_alpha = ct.c_float(float("inf"))
+    assert lib.dsmoe_dense_bwd_mi(ctx, fake, fake, fake, fake, fake, fake, fake, 4, fake, fake, fake, None, fake, fake,
+                                  fake, bad_alpha, s) == dsmoe.ERR_INVALID_ARG
     assert lib.dsmoe_set_workspace(ctx, None, 1 << 20) == dsmoe.ERR_INVALID_ARG
     assert lib.dsmoe_set_workspace(ctx, c_void_p(0x1010), 1 << 30) == dsmoe.ERR_INVALID_ARG
     assert lib.dsmoe_set_workspace(ctx, fake, 16) == dsmoe.ERR_WORKSPACE
