@@ -140,9 +140,36 @@ down_kernel(const T* __restrict__ h, const int32_t* __restrict__ row_token, cons
 }
 
 // ---- bf16: 256-row tiles, 8 waves, direct global -> LDS loads -------------------------------------------
-// Both kernels are software-pipelined over tiles: the first K steps of the next tile are requested before
-// the epilogue of the current one.
-struct FfnTile { int e, row0, valid, n0; };
+// Both kernels walk their tiles in two passes (SplitWalker): 256-row tiles, then 128-row tiles for the short
+// ends of experts and for an uneven last turn of the grid.  Each pass is software-pipelined over its tiles:
+// the first K steps of the next tile are requested before the epilogue of the current one.
+template <class TL, class Next, class Setup, class Epi>
+__device__ __forceinline__ void tile_pipeline(const Stages3& st, int nkt, Next next, Setup setup, Epi epi) {
+  RowTile cur;
+  if (!next(cur)) return;
+  typename TL::LSrc L;
+  typename TL::RSrc R;
+  typename TL::Iter it;
+  setup(cur, L, R);
+  TL::prefetch(L, R, it, nkt, 1 << 30, st);
+  while (true) {
+    typename TL::Acc acc;
+    TL::zero(acc);
+    TL::run(acc, L, R, it, nkt, 1 << 30, st);
+    RowTile nxt;
+    typename TL::LSrc Ln;
+    typename TL::RSrc Rn;
+    typename TL::Iter itn;
+    const bool more = next(nxt);
+    if (more) {
+      setup(nxt, Ln, Rn);
+      TL::prefetch(Ln, Rn, itn, nkt, 1 << 30, st);
+    }
+    epi(cur, acc);
+    if (!more) break;
+    cur = nxt; L = Ln; R = Rn; it = itn;
+  }
+}
 
 template <int BM>
 __global__ void __launch_bounds__(kThreads2)
@@ -151,59 +178,42 @@ gateup_bf16_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ x_pe
                    const bf16_t* __restrict__ w_up, bf16_t* __restrict__ h, int d, int f, int E) {
   constexpr int BNS = 128;                         // columns per source (gate, up) and block
   typedef Tile3<BM, 2 * BNS, 2> TL;
+  typedef Tile3<BM / 2, 2 * BNS, 2> TH;            // the half tile runs in the same stages
+  static_assert(TH::NST == TL::NST && TH::LDS_R == TL::LDS_R && TH::LDS_L <= TL::LDS_L, "stages serve both");
   DSMOE_TILE3_STAGES(TL, st);
-  __shared__ GroupTiles gt;
-  build_group_tiles(gt, expert_off, E, BM);
-  const int n_tiles = (f + BNS - 1) / BNS, nkt = d / TL::BK;
-  TileWalker tw;
-  tw.init(gt.tile_off[E] * n_tiles);
-  auto setup = [&](int idx, FfnTile& t, typename TL::LSrc& L, typename TL::RSrc& R) {
-    const int nt_blk = idx % n_tiles, mg = idx / n_tiles;
-    t.e = find_group(gt, E, mg);
-    t.row0 = gt.row_off[t.e] + (mg - gt.tile_off[t.e]) * BM;
-    t.valid = min(BM, gt.row_off[t.e + 1] - t.row0);
-    t.n0 = nt_blk * BNS;
-    const int row0 = t.row0;
+  __shared__ SplitTiles gt;
+  build_split_tiles(gt, expert_off, E, BM / 2);
+  const int nkt = d / TL::BK;
+  SplitWalker tw;
+  tw.init(gt, E, (f + BNS - 1) / BNS, BM / 2);
+  auto setup = [&](const RowTile& t, auto& L, auto& R) {
+    const int row0 = t.row0, n0 = t.nt * BNS;
     L.init(t.valid, 0, [&](int r) {
       return x_perm ? x_perm + (size_t)(row0 + r) * d : x + (size_t)row_token[row0 + r] * d;
     });
-    const bf16_t* const base[2] = {w_gate + (size_t)t.e * d * f + t.n0, w_up + (size_t)t.e * d * f + t.n0};
-    R.init(base, f, min(BNS, f - t.n0), d);
+    const bf16_t* const base[2] = {w_gate + (size_t)t.e * d * f + n0, w_up + (size_t)t.e * d * f + n0};
+    R.init(base, f, min(BNS, f - n0), d);
   };
-  int idx;
-  if (!tw.next(idx)) return;
-  FfnTile cur;
-  typename TL::LSrc L;
-  typename TL::RSrc R;
-  typename TL::Iter it;
-  setup(idx, cur, L, R);
-  TL::prefetch(L, R, it, nkt, 1 << 30, st);
-  while (true) {
-    typename TL::Acc acc;
-    TL::zero(acc);
-    TL::run(acc, L, R, it, nkt, 1 << 30, st);
-    FfnTile nxt;
-    typename TL::LSrc Ln;
-    typename TL::RSrc Rn;
-    typename TL::Iter itn;
-    const bool more = tw.next(idx);
-    if (more) {
-      setup(idx, nxt, Ln, Rn);
-      TL::prefetch(Ln, Rn, itn, nkt, 1 << 30, st);
-    }
-    TL::template for_each_chunk_bf16<1>(
+  auto epilogue = [&](auto tile, const RowTile& t, const auto& acc) {
+    typedef decltype(tile) TT;
+    const int n0 = t.nt * BNS;
+    TT::template for_each_chunk_bf16<1>(
         acc, st,
         [&](int, int, int, const float (&v)[2][4], float (&o)[1][4]) {
 #pragma unroll
           for (int i = 0; i < 4; ++i) o[0][i] = silu_f(v[0][i]) * v[1][i];
         },
         [&](int m, int n, const u32x4 (&p)[1]) {
-          if (m >= cur.valid || cur.n0 + n >= f) return;
-          stg16(h + (size_t)(cur.row0 + m) * f + cur.n0 + n, p[0]);
+          if (m >= t.valid || n0 + n >= f) return;
+          stg16(h + (size_t)(t.row0 + m) * f + n0 + n, p[0]);
         });
-    if (!more) break;
-    cur = nxt; L = Ln; R = Rn; it = itn;
-  }
+  };
+  tile_pipeline<TL>(
+      st, nkt, [&](RowTile& t) { return tw.next_full(gt, E, t); }, setup,
+      [&](const RowTile& t, const typename TL::Acc& acc) { epilogue(TL{}, t, acc); });
+  tile_pipeline<TH>(
+      st, nkt, [&](RowTile& t) { return tw.next_half(gt, E, t); }, setup,
+      [&](const RowTile& t, const typename TH::Acc& acc) { epilogue(TH{}, t, acc); });
 }
 
 template <int BM, bool GELU = false, bool GATHER = false>
@@ -213,59 +223,42 @@ down_bf16_kernel(const bf16_t* __restrict__ h, const int32_t* __restrict__ row_t
                  int d, int f, int E, int uniform_rows) {
   constexpr int BN = 256;
   typedef Tile3<BM, BN> TL;
+  typedef Tile3<BM / 2, BN> TH;
+  static_assert(TH::NST == TL::NST && TH::LDS_R == TL::LDS_R && TH::LDS_L <= TL::LDS_L, "stages serve both");
   DSMOE_TILE3_STAGES(TL, st);
-  __shared__ GroupTiles gt;
-  build_group_tiles(gt, expert_off, E, BM, uniform_rows);
-  const int n_tiles = (d + BN - 1) / BN, nkt = f / TL::BK;
-  TileWalker tw;
-  tw.init(gt.tile_off[E] * n_tiles);
-  auto setup = [&](int idx, FfnTile& t, typename TL::LSrc& L, typename TL::RSrc& R) {
-    const int nt_blk = idx % n_tiles, mg = idx / n_tiles;
-    t.e = find_group(gt, E, mg);
-    t.row0 = gt.row_off[t.e] + (mg - gt.tile_off[t.e]) * BM;
-    t.valid = min(BM, gt.row_off[t.e + 1] - t.row0);
-    t.n0 = nt_blk * BN;
-    const int row0 = t.row0;
+  __shared__ SplitTiles gt;
+  build_split_tiles(gt, expert_off, E, BM / 2, uniform_rows);
+  const int nkt = f / TL::BK;
+  SplitWalker tw;
+  tw.init(gt, E, (d + BN - 1) / BN, BM / 2);
+  auto setup = [&](const RowTile& t, auto& L, auto& R) {
+    const int row0 = t.row0, n0 = t.nt * BN;
     L.init(t.valid, 0, [&](int r) {
       return h + (GATHER ? (size_t)row_token[row0 + r] : (size_t)(row0 + r)) * f;
     });
-    const bf16_t* const base[1] = {w_down + (size_t)t.e * f * d + t.n0};
-    R.init(base, d, min(BN, d - t.n0), f);
+    const bf16_t* const base[1] = {w_down + (size_t)t.e * f * d + n0};
+    R.init(base, d, min(BN, d - n0), f);
   };
-  int idx;
-  if (!tw.next(idx)) return;
-  FfnTile cur;
-  typename TL::LSrc L;
-  typename TL::RSrc R;
-  typename TL::Iter it;
-  setup(idx, cur, L, R);
-  TL::prefetch(L, R, it, nkt, 1 << 30, st);
-  while (true) {
-    typename TL::Acc acc;
-    TL::zero(acc);
-    TL::run(acc, L, R, it, nkt, 1 << 30, st);
-    FfnTile nxt;
-    typename TL::LSrc Ln;
-    typename TL::RSrc Rn;
-    typename TL::Iter itn;
-    const bool more = tw.next(idx);
-    if (more) {
-      setup(idx, nxt, Ln, Rn);
-      TL::prefetch(Ln, Rn, itn, nkt, 1 << 30, st);
-    }
-    TL::template for_each_chunk_bf16<1>(
+  auto epilogue = [&](auto tile, const RowTile& t, const auto& acc) {
+    typedef decltype(tile) TT;
+    const int n0 = t.nt * BN;
+    TT::template for_each_chunk_bf16<1>(
         acc, st,
         [&](int, int, int, const float (&v)[1][4], float (&o)[1][4]) {
 #pragma unroll
           for (int i = 0; i < 4; ++i) o[0][i] = GELU ? gelu_f(v[0][i]) : v[0][i];
         },
         [&](int m, int n, const u32x4 (&p)[1]) {
-          if (m >= cur.valid || cur.n0 + n >= d) return;
-          stg16(y + (size_t)(cur.row0 + m) * d + cur.n0 + n, p[0]);
+          if (m >= t.valid || n0 + n >= d) return;
+          stg16(y + (size_t)(t.row0 + m) * d + n0 + n, p[0]);
         });
-    if (!more) break;
-    cur = nxt; L = Ln; R = Rn; it = itn;
-  }
+  };
+  tile_pipeline<TL>(
+      st, nkt, [&](RowTile& t) { return tw.next_full(gt, E, t); }, setup,
+      [&](const RowTile& t, const typename TL::Acc& acc) { epilogue(TL{}, t, acc); });
+  tile_pipeline<TH>(
+      st, nkt, [&](RowTile& t) { return tw.next_half(gt, E, t); }, setup,
+      [&](const RowTile& t, const typename TH::Acc& acc) { epilogue(TH{}, t, acc); });
 }
 
 static hipError_t launch_ffn_bf16(const dsmoe_ctx* c, const void* x, const void* x_perm, const int32_t* row_token,

@@ -304,6 +304,108 @@ struct TileWalker {
   }
 };
 
+// Row tiles of a grouped problem in two heights.  An expert's rows are cut into full tiles of 2 * HB rows; a
+// remainder of more than HB rows is one more (ragged) full tile, a remainder of 1 .. HB rows is a half tile.
+struct SplitTiles {
+  int full_off[kMaxExperts + 1];   // exclusive prefix sums of the experts' full tiles ...
+  int half_off[kMaxExperts + 1];   // ... and of their half tiles (0 or 1 each)
+  int row_off[kMaxExperts + 1];
+};
+__device__ __forceinline__ void build_split_tiles(SplitTiles& g, const int32_t* __restrict__ expert_off, int E, int HB,
+                                                  int uniform_rows = 0) {
+  if (threadIdx.x < 64) {
+    const int e = threadIdx.x;
+    int lo = 0, hi = 0;
+    if (e < E) {
+      lo = expert_off ? expert_off[e] : e * uniform_rows;
+      hi = expert_off ? expert_off[e + 1] : (e + 1) * uniform_rows;
+    }
+    const int units = (hi - lo + HB - 1) / HB;
+    int nf = units >> 1, nh = units & 1;
+#pragma unroll
+    for (int s = 1; s < 64; s <<= 1) {
+      const int of = __shfl_up(nf, s, 64), oh = __shfl_up(nh, s, 64);
+      if (e >= s) { nf += of; nh += oh; }
+    }
+    g.full_off[e + 1] = nf;
+    g.half_off[e + 1] = nh;
+    if (e == 0) { g.full_off[0] = 0; g.half_off[0] = 0; }
+    if (e < E) g.row_off[e] = lo;
+    if (e == E - 1) g.row_off[E] = hi;
+  }
+  __syncthreads();
+}
+__device__ __forceinline__ int find_in_prefix(const int* off, int E, int i) {
+  int lo = 0, hi = E - 1;   // largest e with off[e] <= i
+  while (lo < hi) {
+    const int mid = (lo + hi + 1) >> 1;
+    if (off[mid] <= i) lo = mid; else hi = mid - 1;
+  }
+  return lo;
+}
+
+struct RowTile { int e, row0, valid, nt; };   // expert, first row, rows, column tile
+
+// Deals the tiles of a SplitTiles table (times n_tiles column tiles, column tile fastest) to a persistent
+// grid.  Full and half tiles are each cut in 8 contiguous chunks, one per XCD, and a chunk's tiles go round
+// robin over the XCD's blocks: first the full tiles (next_full), then the half tiles (next_half).  When the
+// full tiles do not fill the blocks' last turn evenly and there is room, the ones left over are cut in two
+// halves and dealt with the half tiles, so that the last turn costs every block half a tile instead of
+// costing few blocks a whole one.
+struct SplitWalker {
+  int n_tiles, slots, HB;
+  int fi, f_end;                    // next full tile of this block, end of the ones dealt as full tiles
+  int n_split, h_begin, n_p2, j;    // full tiles dealt as two halves (from f_end on), first half tile, items, next
+  __device__ __forceinline__ void init(const SplitTiles& g, int E, int n_tiles_, int HB_) {
+    n_tiles = n_tiles_;
+    HB = HB_;
+    slots = gridDim.x >> 3;
+    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+    const int F = g.full_off[E] * n_tiles, H = g.half_off[E] * n_tiles;
+    const int per = (F + 7) >> 3, perh = (H + 7) >> 3;
+    const int f_begin = min(F, xcd * per), f_stop = min(F, f_begin + per);
+    h_begin = min(H, xcd * perh);
+    const int h_cnt = min(H, h_begin + perh) - h_begin;
+    const int left = (f_stop - f_begin) % slots;
+    const bool split = left > 0 && 2 * left + h_cnt <= slots;
+    n_split = split ? left : 0;
+    f_end = f_stop - n_split;
+    n_p2 = 2 * n_split + h_cnt;
+    fi = f_begin + slot;
+    // the half tiles start at the first block that has no full tile in the last turn
+    j = (slot - (split ? 0 : left) + slots) % slots;
+  }
+  __device__ __forceinline__ void full_tile(const SplitTiles& g, int E, int idx, RowTile& t) const {
+    const int mg = idx / n_tiles;
+    t.nt = idx - mg * n_tiles;
+    t.e = find_in_prefix(g.full_off, E, mg);
+    t.row0 = g.row_off[t.e] + (mg - g.full_off[t.e]) * 2 * HB;
+    t.valid = min(2 * HB, g.row_off[t.e + 1] - t.row0);
+  }
+  __device__ __forceinline__ bool next_full(const SplitTiles& g, int E, RowTile& t) {
+    if (fi >= f_end) return false;
+    full_tile(g, E, fi, t);
+    fi += slots;
+    return true;
+  }
+  __device__ __forceinline__ bool next_half(const SplitTiles& g, int E, RowTile& t) {
+    if (j >= n_p2) return false;
+    if (j < 2 * n_split) {           // a full tile has more than HB rows: both halves hold rows
+      full_tile(g, E, f_end + (j >> 1), t);
+      t.row0 += (j & 1) * HB;
+      t.valid = min(HB, t.valid - (j & 1) * HB);
+    } else {
+      const int idx = h_begin + j - 2 * n_split, hm = idx / n_tiles;
+      t.nt = idx - hm * n_tiles;
+      t.e = find_in_prefix(g.half_off, E, hm);
+      t.row0 = g.row_off[t.e] + (g.full_off[t.e + 1] - g.full_off[t.e]) * 2 * HB;
+      t.valid = g.row_off[t.e + 1] - t.row0;
+    }
+    j += slots;
+    return true;
+  }
+};
+
 __device__ __forceinline__ float silu_f(float g) { return g / (1.f + __expf(-g)); }
 // exact GeLU: g * Phi(g)
 __device__ __forceinline__ float gelu_f(float g) { return 0.5f * g * (1.f + erff(g * 0.70710678118654752f)); }

@@ -561,9 +561,11 @@ struct Tile3 {
   // segment.  A quarter of the LDS traffic of the fp32 walk when the epilogue has one output.
   template <int NOUT, class P, class F>
   static __device__ __forceinline__ void for_each_chunk_bf16(const Acc& acc, const Stages3& st, P pre, F f) {
-    static_assert(RSrc::LDS / 8 == 2048 && LSrc::LDS / 8 == 2048, "a wave's slice of a stage holds 32 rows of 64 bytes");
     constexpr int NTC = NSRC == 1 ? NT : 1;       // 32-column tiles of an output per wave
     static_assert(NOUT * NTC <= 4, "four scratch pieces per wave");
+    // the first two pieces lie in the right operand's stages, the other two in the left operand's
+    static_assert(RSrc::LDS / 8 == 2048 && (NOUT * NTC <= 2 || LSrc::LDS / 8 == 2048),
+                  "a wave's slice of a stage holds 32 rows of 64 bytes");
     const int tid = epilogue_tid();
     const int lane = tid & 63, wave = tid >> 6;
     const int m = lane & 31, kg = lane >> 5;
