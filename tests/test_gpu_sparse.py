@@ -209,6 +209,43 @@ def test_gelu_two_matrix_expert(torch, dsmoe, name, T, dtype, mode, k, eps, mate
     run_staged_and_check(torch, dsmoe, inp, mode, k, eps, materialize=materialize)
 
 
+@pytest.mark.parametrize("expert", ["swiglu", "gelu"])
+@pytest.mark.parametrize("counts", [
+    [0, 1, 127, 128, 129, 255, 256, 257, 0, 384, 385, 640, 2, 200, 513, 0],   # every remainder class of both heights
+    [300] * 40 + [5] * 3 + [0] * 5,                                   # full and half tiles on most experts
+    [130] * 8,                                                        # few full tiles: cut in halves
+])
+def test_expert_ffn_on_crafted_row_groups(torch, dsmoe, counts, expert):
+    """The grouped FFN alone on hand-made row groups (sizes around the kernels' 128- and 256-row tiles), each
+    expert's rows against the checker's plain FFN of that expert (Eq. 1, the e_i(X) factor)."""
+    E, d, f, T = len(counts), 256, 192, 700
+    cfg = gen.LayerConfig("groups", 31, T=T, d=d, E=E, f=f, dtype="bf16", mode="topk", k=1, router_std=0.05)
+    inp = gen.make_layer(cfg, 0)
+    if expert == "gelu":
+        inp.w_up = None
+    rng = np.random.default_rng(5)
+    off = np.concatenate([[0], np.cumsum(counts)]).astype(np.int32)
+    nnz = int(off[-1])
+    row_token = rng.integers(0, T, size=nnz).astype(np.int32)
+    say(f"[case] crafted groups E={E} nnz={nnz} expert={expert}")
+    w = weights_to_dev(torch, inp)
+    # a row capacity well above nnz gives a grid with idle blocks, which is when full tiles are cut in halves
+    layer = dsmoe.Layer(d, f, E, "bf16", max_tokens=4096, max_rows=max(nnz, 20000), expert=expert)
+    for materialize in (False, True):
+        r = dict(expert_off=torch.from_numpy(off).cuda(), row_token=torch.from_numpy(row_token).cuda())
+        if materialize:
+            r["x_perm"] = w["x"][torch.from_numpy(row_token.astype(np.int64)).cuda()].contiguous()
+        y = layer.expert_ffn(w["x"], r, w["w_gate"], w["w_up"], w["w_down"])
+        torch.cuda.synchronize()
+        y_gpu = y[:nnz].float().cpu().numpy()
+        for e in range(E):
+            if counts[e] == 0:
+                continue
+            rows = row_token[off[e]:off[e + 1]]
+            ref = orc.expert_ffn(inp.x[rows], inp.w_gate[e], None if inp.w_up is None else inp.w_up[e], inp.w_down[e])
+            assert helpers.rel_err(y_gpu[off[e]:off[e + 1]], ref) <= TOL["bf16"], (e, counts[e], materialize)
+
+
 def test_skewed_router_bias_empty_and_hot_experts(torch, dsmoe):
     cfg = gen.LayerConfig("skew", 12, T=500, d=256, E=24, f=128, dtype="bf16", mode="threshold", eps=0.04,
                           router_std=0.05, zipf_s=2.0)
