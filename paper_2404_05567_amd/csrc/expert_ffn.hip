@@ -171,6 +171,36 @@ __device__ __forceinline__ void tile_pipeline(const Stages3& st, int nkt, Next n
   }
 }
 
+// The same walk with the load pipeline running on from tile to tile (Tile3::run_chain): the next tile is set
+// up before the current one starts, and epi may use stage NST-1 only.
+template <class TL, class Next, class Setup, class Epi>
+__device__ __forceinline__ void tile_chain(const Stages3& st, int nkt, Next next, Setup setup, Epi epi) {
+  RowTile cur;
+  if (!next(cur)) return;
+  typename TL::LSrc L;
+  typename TL::RSrc R;
+  typename TL::Iter it;
+  setup(cur, L, R);
+  TL::chain_begin(L, R, it, nkt, st);
+  while (true) {
+    RowTile nxt;
+    typename TL::LSrc Ln = L;
+    typename TL::RSrc Rn = R;
+    typename TL::Iter itn = it;
+    const bool more = next(nxt);
+    if (more) {
+      setup(nxt, Ln, Rn);
+      itn.seg = 0; itn.kin = 0; itn.next = 0;
+    }
+    typename TL::Acc acc;
+    TL::zero(acc);
+    TL::run_chain(acc, L, R, it, Ln, Rn, itn, nkt, st);
+    epi(cur, acc);
+    if (!more) break;
+    cur = nxt; L = Ln; R = Rn; it = itn;
+  }
+}
+
 template <int BM>
 __global__ void __launch_bounds__(kThreads2)
 gateup_bf16_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ x_perm, const int32_t* __restrict__ row_token,
@@ -194,10 +224,10 @@ gateup_bf16_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ x_pe
     const bf16_t* const base[2] = {w_gate + (size_t)t.e * d * f + n0, w_up + (size_t)t.e * d * f + n0};
     R.init(base, f, min(BNS, f - n0), d);
   };
-  auto epilogue = [&](auto tile, const RowTile& t, const auto& acc) {
+  auto epilogue = [&](auto tile, auto last_stage, const RowTile& t, const auto& acc) {
     typedef decltype(tile) TT;
     const int n0 = t.nt * BNS;
-    TT::template for_each_chunk_bf16<1>(
+    TT::template for_each_chunk_bf16<1, decltype(last_stage)::value>(
         acc, st,
         [&](int, int, int, const float (&v)[2][4], float (&o)[1][4]) {
 #pragma unroll
@@ -208,12 +238,17 @@ gateup_bf16_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ x_pe
           stg16(h + (size_t)(t.row0 + m) * f + n0 + n, p[0]);
         });
   };
-  tile_pipeline<TL>(
-      st, nkt, [&](RowTile& t) { return tw.next_full(gt, E, t); }, setup,
-      [&](const RowTile& t, const typename TL::Acc& acc) { epilogue(TL{}, t, acc); });
+  if (TL::chainable(nkt))
+    tile_chain<TL>(
+        st, nkt, [&](RowTile& t) { return tw.next_full(gt, E, t); }, setup,
+        [&](const RowTile& t, const typename TL::Acc& acc) { epilogue(TL{}, std::true_type{}, t, acc); });
+  else
+    tile_pipeline<TL>(
+        st, nkt, [&](RowTile& t) { return tw.next_full(gt, E, t); }, setup,
+        [&](const RowTile& t, const typename TL::Acc& acc) { epilogue(TL{}, std::false_type{}, t, acc); });
   tile_pipeline<TH>(
       st, nkt, [&](RowTile& t) { return tw.next_half(gt, E, t); }, setup,
-      [&](const RowTile& t, const typename TH::Acc& acc) { epilogue(TH{}, t, acc); });
+      [&](const RowTile& t, const typename TH::Acc& acc) { epilogue(TH{}, std::false_type{}, t, acc); });
 }
 
 template <int BM, bool GELU = false, bool GATHER = false>
@@ -239,10 +274,10 @@ down_bf16_kernel(const bf16_t* __restrict__ h, const int32_t* __restrict__ row_t
     const bf16_t* const base[1] = {w_down + (size_t)t.e * f * d + n0};
     R.init(base, d, min(BN, d - n0), f);
   };
-  auto epilogue = [&](auto tile, const RowTile& t, const auto& acc) {
+  auto epilogue = [&](auto tile, auto last_stage, const RowTile& t, const auto& acc) {
     typedef decltype(tile) TT;
     const int n0 = t.nt * BN;
-    TT::template for_each_chunk_bf16<1>(
+    TT::template for_each_chunk_bf16<1, decltype(last_stage)::value>(
         acc, st,
         [&](int, int, int, const float (&v)[1][4], float (&o)[1][4]) {
 #pragma unroll
@@ -253,12 +288,17 @@ down_bf16_kernel(const bf16_t* __restrict__ h, const int32_t* __restrict__ row_t
           stg16(y + (size_t)(t.row0 + m) * d + n0 + n, p[0]);
         });
   };
-  tile_pipeline<TL>(
-      st, nkt, [&](RowTile& t) { return tw.next_full(gt, E, t); }, setup,
-      [&](const RowTile& t, const typename TL::Acc& acc) { epilogue(TL{}, t, acc); });
+  if (TL::chainable(nkt))
+    tile_chain<TL>(
+        st, nkt, [&](RowTile& t) { return tw.next_full(gt, E, t); }, setup,
+        [&](const RowTile& t, const typename TL::Acc& acc) { epilogue(TL{}, std::true_type{}, t, acc); });
+  else
+    tile_pipeline<TL>(
+        st, nkt, [&](RowTile& t) { return tw.next_full(gt, E, t); }, setup,
+        [&](const RowTile& t, const typename TL::Acc& acc) { epilogue(TL{}, std::false_type{}, t, acc); });
   tile_pipeline<TH>(
       st, nkt, [&](RowTile& t) { return tw.next_half(gt, E, t); }, setup,
-      [&](const RowTile& t, const typename TH::Acc& acc) { epilogue(TH{}, t, acc); });
+      [&](const RowTile& t, const typename TH::Acc& acc) { epilogue(TH{}, std::false_type{}, t, acc); });
 }
 
 static hipError_t launch_ffn_bf16(const dsmoe_ctx* c, const void* x, const void* x_perm, const int32_t* row_token,

@@ -105,6 +105,16 @@ __device__ __forceinline__ void wait_vm() {
   __builtin_amdgcn_s_waitcnt((N & 0xF) | ((N >> 4) << 14) | (7 << 4) | ((LGKM0 ? 0 : 15) << 8));
 }
 
+// The thread index as a value the compiler cannot trace back to threadIdx: what is derived from it is
+// computed where it is used instead of being hoisted out of a tile loop and kept (spilled) across the main
+// loop.  A spill reload is a vector-memory load, and the wait for it also waits for every global store in
+// flight.
+__device__ __forceinline__ int opaque_tid() {
+  int t = threadIdx.x;
+  asm volatile("" : "+v"(t));
+  return t;
+}
+
 // ---- "rows" operand -----------------------------------------------------------------------------------
 template <int ROWS>
 struct DRows {
@@ -125,7 +135,8 @@ struct DRows {
     seg_stride = seg_stride_bytes;
     brk[0] = brk[1] = 0x7fffffff;
     jump[0] = jump[1] = 0;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int tid = opaque_tid();
+    const int lane = tid & 63, wave = tid >> 6;
 #pragma unroll
     for (int i = 0; i < CPW; ++i) {
       const int r = 16 * (wave * CPW + i) + (lane >> 2);
@@ -180,7 +191,8 @@ struct DCols {
   // exist from there on (columns past the end are read from column 0 and never reach a stored output)
   __device__ __forceinline__ void init(const bf16_t* const (&base)[NSRC], size_t ld_elems, int cols_valid, int kv,
                                        const void* zero_page = nullptr) {
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int tid = opaque_tid();
+    const int lane = tid & 63, wave = tid >> 6;
     step_bytes = (size_t)kBK2 * ld_elems * 2;
     seg_stride = 0;
     k_valid = kv;
@@ -473,6 +485,68 @@ struct Tile3 {
     run(acc, L, R, it, nkt, seg_tiles, st);
   }
 
+  // ---- chained tiles: the load pipeline keeps running from one tile into the next --------------------------
+  // A wave cannot count its loads past stores it has in flight (one counter for both, and stores may
+  // complete ahead of older loads), so the first counted wait after an epilogue waits for the epilogue's
+  // stores.  In a chain that wait comes late: the last K steps of a tile already request steps 0 .. NST-2 of
+  // the next one, they have landed before the epilogue's first store, and the next tile's first NST-2 steps
+  // need no wait at all.  The stores then have those steps to complete behind the MFMAs.  The epilogue
+  // between two run_chain() calls may use the wave's own slices of stage NST-1 only.
+  // Needs nkt % NST == 0 and nkt >= 2 * NST.
+  static constexpr bool chainable(int nkt) { return nkt % NST == 0 && nkt >= 2 * NST; }
+  static __device__ __forceinline__ void chain_begin(const LSrc& L, const RSrc& R, Iter& it, int nkt, const Stages3& st) {
+    it.seg = 0; it.kin = 0; it.next = 0;
+    chain_issue<0>(L, R, it, nkt, st);
+    __builtin_amdgcn_sched_barrier(0);
+    wait_vm<0, true>();
+    __builtin_amdgcn_sched_barrier(0);
+  }
+  template <int ST>
+  static __device__ __forceinline__ void chain_issue(const LSrc& L, const RSrc& R, Iter& it, int nkt, const Stages3& st) {
+    if constexpr (ST < NST - 1) {
+      issue_step(L, R, it, nkt, 1 << 30, st.l[ST], st.r[ST]);
+      chain_issue<ST + 1>(L, R, it, nkt, st);
+    }
+  }
+  // N consecutive refilling steps from stage ST whose next step is known to have landed
+  template <int ST, int N>
+  static __device__ __forceinline__ void steps_landed(const Loop& q) {
+    if constexpr (N > 0) {
+      step<ST, 63, true>(q);
+      steps_landed<(ST + 1) % NST, N - 1>(q);
+    }
+  }
+  // acc += L * R for one tile of a chain.  On entry this tile's steps 0 .. NST-2 have been requested and every
+  // wave has seen its own land; (Ln, Rn, itn) is the next tile at step 0, or a copy of (L, R, it) when there is
+  // none (the last steps then re-read into stages nobody reads any more).  On return the next tile's steps
+  // 0 .. NST-2 have landed as far as this wave requested them, itn stands at step NST-1, and no wave reads
+  // stage NST-1 any more.
+  static __device__ __forceinline__ void run_chain(Acc& acc, const LSrc& L, const RSrc& R, Iter& it, const LSrc& Ln,
+                                                   const RSrc& Rn, Iter& itn, int nkt, const Stages3& st) {
+    Offs o;
+    offsets(o);
+    Frag fa, fb;
+    issue_step(L, R, it, nkt, 1 << 30, st.l[NST - 1], st.r[NST - 1]);
+    __builtin_amdgcn_sched_barrier(0);
+    __builtin_amdgcn_s_barrier();     // every wave's share of steps 0 .. NST-2 has landed
+    __builtin_amdgcn_sched_barrier(0);
+    read_frags(fa, st.l[0], st.r[0], o, 0);
+    const Loop q{acc, fa, fb, L, R, it, nkt, 1 << 30, st, o};
+    const Loop qn{acc, fa, fb, Ln, Rn, itn, nkt, 1 << 30, st, o};
+    steps_landed<0, NST - 2>(q);
+    steps<NST - 2, 2>(q);
+    for (int kt = NST; kt + 2 * NST <= nkt; kt += NST) steps<0, NST>(q);
+    steps<0, NST - 1>(qn);
+    read_frags(fb, st.l[NST - 1], st.r[NST - 1], o, 1);
+    mma(acc, fa);
+    interleave();
+    __builtin_amdgcn_sched_barrier(0);
+    wait_vm<0, true>();
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_sched_barrier(0);
+    mma(acc, fb);
+  }
+
   // Transposed walk over the accumulators.  The MFMA leaves a lane with one row and 4 consecutive columns
   // per register quad, which makes 8-byte accesses spread over 32 rows.  Here every 32-row block of the
   // wave goes through the wave's own slices of the last two stages (fp32, XOR-swizzled 16-byte units, no
@@ -486,11 +560,7 @@ struct Tile3 {
   // it (row and column of a lane, LDS offsets) is then computed inside the epilogue instead of being hoisted out
   // of the tile loop and kept, spilled, across the main loop.  A spill reload is a vector-memory load, and the
   // wait for it would also wait for every global store the epilogue has issued.
-  static __device__ __forceinline__ int epilogue_tid() {
-    int t = threadIdx.x;
-    asm volatile("" : "+v"(t));
-    return t;
-  }
+  static __device__ __forceinline__ int epilogue_tid() { return opaque_tid(); }
   // load(j, m, n) is called for the NJ chunks of a 32-row block before the block crosses the LDS, f(j, m, n, v)
   // after: global loads an epilogue needs (saved activations ...) are then all in flight together and ahead of
   // the block's stores, instead of each waiting behind the stores of the chunk before.
@@ -559,17 +629,19 @@ struct Tile3 {
   // 2 KB piece of the wave's scratch slices per output and 32-column tile: 32 rows of 64 bytes, XOR-swizzled),
   // and handed to f(m, n, p) with p[o] = 8 consecutive bf16 of output o, 4 lanes covering a 64-byte row
   // segment.  A quarter of the LDS traffic of the fp32 walk when the epilogue has one output.
-  template <int NOUT, class P, class F>
+  // LAST_STAGE: the scratch pieces lie in stage NST-1 alone (at most two; for the epilogues of a chain).
+  template <int NOUT, bool LAST_STAGE = false, class P, class F>
   static __device__ __forceinline__ void for_each_chunk_bf16(const Acc& acc, const Stages3& st, P pre, F f) {
     constexpr int NTC = NSRC == 1 ? NT : 1;       // 32-column tiles of an output per wave
-    static_assert(NOUT * NTC <= 4, "four scratch pieces per wave");
+    static_assert(NOUT * NTC <= (LAST_STAGE ? 2 : 4), "four scratch pieces per wave, two in one stage");
     // the first two pieces lie in the right operand's stages, the other two in the left operand's
-    static_assert(RSrc::LDS / 8 == 2048 && (NOUT * NTC <= 2 || LSrc::LDS / 8 == 2048),
+    static_assert(RSrc::LDS / 8 == 2048 && (NOUT * NTC <= (LAST_STAGE ? 1 : 2) || LSrc::LDS / 8 == 2048),
                   "a wave's slice of a stage holds 32 rows of 64 bytes");
     const int tid = epilogue_tid();
     const int lane = tid & 63, wave = tid >> 6;
     const int m = lane & 31, kg = lane >> 5;
-    lds_char* const piece[4] = {st.r[NST - 2] + wave * 2048, st.r[NST - 1] + wave * 2048,
+    lds_char* const piece[4] = {st.r[LAST_STAGE ? NST - 1 : NST - 2] + wave * 2048,
+                                (LAST_STAGE ? st.l[NST - 1] : st.r[NST - 1]) + wave * 2048,
                                 st.l[NST - 2] + wave * 2048, st.l[NST - 1] + wave * 2048};
     const int woff = m * 64 + kg * 8, wsw = (m >> 2) & 3;
     const int rrow = lane >> 2, rq = lane & 3;
