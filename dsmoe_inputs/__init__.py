@@ -169,3 +169,68 @@ def redraw_rows(inp: LayerInputs, rows: np.ndarray) -> None:
     seed = BASE_SEED + 1000 * cfg.index + inp.variant
     g = np.random.Generator(np.random.Philox(key=seed, counter=[0, 0, inp.redraws, _S_REDRAW]))
     inp.x[rows] = _store(g.standard_normal((rows.size, cfg.d), dtype=np.float32), cfg.dtype)
+
+
+# --------------------------------------------------------------------------------------------------
+# Mixture-of-Attention-heads layer (Sec. 3.2).  Shapes follow Table 1: DS-MoE-1B has 16 attention experts
+# of 2 heads of 64, DS-MoE-6B 8 experts of 4 heads of 128; the number of heads per expert is the number of
+# shared key/value heads.  Keys and values are drawn directly (the paper takes the cache as given).
+# --------------------------------------------------------------------------------------------------
+@dataclass(frozen=True)
+class MoaConfig:
+    name: str
+    index: int
+    T: int                # new tokens (the last T cache positions)
+    L: int                # cache length
+    d: int                # d_model
+    E: int                # attention experts
+    n_head: int           # heads per expert = shared key/value heads
+    d_head: int
+    dtype: str            # "f32" | "bf16"
+    mode: str             # "dense" | "topk" | "threshold"
+    k: int = 0
+    eps: float = 0.0
+    router_std: float = 0.02
+    weight_std: float = 0.02
+
+    def with_(self, **kw) -> "MoaConfig":
+        return replace(self, **kw)
+
+
+MOA_CONFIGS: Dict[str, MoaConfig] = {
+    # tiny correctness case
+    "m1": MoaConfig("m1", 11, T=48, L=80, d=128, E=8, n_head=2, d_head=64, dtype="bf16", mode="topk", k=2,
+                    router_std=0.1),
+    # prefill of the 6B shape (Table 1), every expert active: how the paper runs the attention layer at inference
+    "m2": MoaConfig("m2", 12, T=2048, L=2048, d=4096, E=8, n_head=4, d_head=128, dtype="bf16", mode="dense",
+                    router_std=1.0 / np.sqrt(4096)),
+}
+
+
+@dataclass
+class MoaInputs:
+    cfg: MoaConfig
+    variant: int
+    x: np.ndarray        # [T, d]
+    w_r: np.ndarray      # [d, E]
+    w_q: np.ndarray      # [E, d, n_head * d_head]
+    k: np.ndarray        # [n_head, L, d_head]
+    v: np.ndarray        # [n_head, L, d_head]
+    w_o: np.ndarray      # [E, n_head * d_head, d]
+    b_r: Optional[np.ndarray] = None
+    redraws: int = field(default=0)
+
+
+def make_moa(cfg: MoaConfig, variant: int = 0) -> MoaInputs:
+    hd = cfg.n_head * cfg.d_head
+    std = np.float32(cfg.weight_std)
+    n = lambda stream, shape: _rng(cfg, variant, stream).standard_normal(shape, dtype=np.float32)
+    return MoaInputs(
+        cfg, variant,
+        x=_store(n(_S_X, (cfg.T, cfg.d)), cfg.dtype),
+        w_r=_store(n(_S_WR, (cfg.d, cfg.E)) * np.float32(cfg.router_std), cfg.dtype),
+        w_q=_store(n(_S_WG, (cfg.E, cfg.d, hd)) * std, cfg.dtype),
+        k=_store(n(_S_WU, (cfg.n_head, cfg.L, cfg.d_head)), cfg.dtype),
+        v=_store(n(_S_DO, (cfg.n_head, cfg.L, cfg.d_head)), cfg.dtype),
+        w_o=_store(n(_S_WD, (cfg.E, hd, cfg.d)) * std, cfg.dtype),
+    )
