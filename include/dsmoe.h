@@ -189,6 +189,43 @@ int32_t dsmoe_profile_enable(dsmoe_ctx* ctx, int32_t max_calls);
 int32_t dsmoe_profile_read(dsmoe_ctx* ctx, int32_t* n_calls /* host */, float* gateup_ms /* host */,
                            float* down_ms /* host */);
 
+/* ---- Mixture-of-Attention-heads layer (Sec. 3.2, "Mixture of Attention Head", Eq. 7-8) -------------
+ * Forward only, bf16 only.  E experts; expert i has a query projection W_q[i] and an output projection
+ * W_o[i]; the n_head key/value heads of the cache are shared by all experts (grouped-query attention:
+ * head j of every expert attends to K[j], V[j]).  For a token x with router scores S (softmax of
+ * x W_r + b_r, as in the MLP layer) and selected set A:
+ *     Q_i = x W_q[i],   O_ij = softmax(scale * Q_ij K_j^T) V_j W_o[i][j]   (Eq. 7)
+ *     out = sum_{i in A} S_i sum_j O_ij                                    (Eq. 8)
+ * The T tokens of a call are the last T positions of the cache (position of token t = L - T + t) and a
+ * token attends to positions <= its own (causal); the caller has already written their keys and values
+ * into the cache.  `scale`: Eq. 7 prints no factor (scale = 1); 1/sqrt(d_head) is the usual one.
+ * Every expert is computed for every token (the paper runs this layer densely at inference, Sec. 4.4);
+ * the selection only zeroes the weights of the experts outside A.
+ *
+ * Layouts (device, row-major, 16-byte aligned): x [T,d]; w_r [d,E]; b_r [E] or NULL;
+ * w_q [E, d, n_head*d_head]; k_cache, v_cache [n_head, L, d_head]; w_o [E, n_head*d_head, d]; out [T,d].
+ * Limits: E a multiple of 8 and <= 64, d a multiple of 64, d_head 64 or 128, L >= T >= 0,
+ * T <= max_tokens.  The context owns no device memory; dsmoe_moa_set_workspace lends it
+ * dsmoe_moa_workspace_bytes bytes (router scores, masks, Q and the weighted attention outputs).
+ * mode: DSMOE_SEL_TOPK (k), DSMOE_SEL_THRESHOLD (eps) or DSMOE_SEL_ALL.  Errors as for the MLP layer
+ * (status code, message from dsmoe_moa_last_error); one call at a time per context. */
+#define DSMOE_SEL_ALL (-1)
+typedef struct dsmoe_moa_desc {
+  int32_t d_model, n_experts, n_head, d_head, dtype /* DSMOE_BF16 */, max_tokens;
+} dsmoe_moa_desc;
+typedef struct dsmoe_moa_ctx dsmoe_moa_ctx;
+int32_t dsmoe_moa_create(const dsmoe_moa_desc* desc /* host */, dsmoe_moa_ctx** out /* host */);
+int32_t dsmoe_moa_destroy(dsmoe_moa_ctx* ctx);
+const char* dsmoe_moa_last_error(const dsmoe_moa_ctx* ctx);
+int32_t dsmoe_moa_workspace_bytes(const dsmoe_moa_ctx* ctx, size_t* bytes /* host */);
+int32_t dsmoe_moa_set_workspace(dsmoe_moa_ctx* ctx, void* workspace /* device, 256-byte aligned */, size_t bytes);
+int32_t dsmoe_moa_fwd(dsmoe_moa_ctx* ctx, const void* x, const void* w_r, const void* b_r, const void* w_q,
+                      const void* k_cache, const void* v_cache, const void* w_o, int32_t T, int32_t L,
+                      int32_t mode, int32_t k, float eps, float scale, void* out, void* stream);
+/* Copies the router scores (fp32 [T,E]) and selection masks (bit e of mask[t]; all experts for
+ * DSMOE_SEL_ALL) of the last dsmoe_moa_fwd call out of the workspace; either pointer may be NULL. */
+int32_t dsmoe_moa_routing(dsmoe_moa_ctx* ctx, int32_t T, float* probs, uint64_t* mask, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

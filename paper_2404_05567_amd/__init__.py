@@ -15,6 +15,7 @@ LIB_PATH = os.path.join(_PKG, "libdsmoe.so")
 
 F32, BF16 = 0, 1
 SEL_TOPK, SEL_THRESHOLD, SEL_THRESHOLD_TOPK = 0, 1, 2
+SEL_ALL = -1          # attention layer only: every expert
 EXPERT_SWIGLU, EXPERT_GELU = 0, 1
 OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_CAPACITY, ERR_HIP, ERR_NOT_IMPL = 0, -1, -2, -3, -4, -5, -6
 
@@ -25,7 +26,14 @@ EXPORTS = [
     "dsmoe_sparse_fwd", "dsmoe_sparse_fwd_routing", "dsmoe_dense_saved_bytes", "dsmoe_dense_fwd",
     "dsmoe_dense_bwd_scratch_bytes", "dsmoe_dense_bwd", "dsmoe_mi_loss", "dsmoe_dense_bwd_mi",
     "dsmoe_profile_enable", "dsmoe_profile_read",
+    "dsmoe_moa_create", "dsmoe_moa_destroy", "dsmoe_moa_last_error", "dsmoe_moa_workspace_bytes",
+    "dsmoe_moa_set_workspace", "dsmoe_moa_fwd", "dsmoe_moa_routing",
 ]
+
+
+class MoaDesc(ctypes.Structure):
+    _fields_ = [("d_model", c_int32), ("n_experts", c_int32), ("n_head", c_int32), ("d_head", c_int32),
+                ("dtype", c_int32), ("max_tokens", c_int32)]
 
 
 class Desc(ctypes.Structure):
@@ -75,6 +83,13 @@ def load_library() -> ctypes.CDLL:
         "dsmoe_dense_bwd_mi": (c_int32, [P, P, P, P, P, P, P, P, c_int32, P, P, P, P, P, P, P, c_float, P]),
         "dsmoe_profile_enable": (c_int32, [P, c_int32]),
         "dsmoe_profile_read": (c_int32, [P, POINTER(c_int32), POINTER(c_float), POINTER(c_float)]),
+        "dsmoe_moa_create": (c_int32, [POINTER(MoaDesc), POINTER(c_void_p)]),
+        "dsmoe_moa_destroy": (c_int32, [P]),
+        "dsmoe_moa_last_error": (c_char_p, [P]),
+        "dsmoe_moa_workspace_bytes": (c_int32, [P, POINTER(c_size_t)]),
+        "dsmoe_moa_set_workspace": (c_int32, [P, P, c_size_t]),
+        "dsmoe_moa_fwd": (c_int32, [P, P, P, P, P, P, P, P, c_int32, c_int32, c_int32, c_int32, c_float, c_float, P, P]),
+        "dsmoe_moa_routing": (c_int32, [P, c_int32, P, P, P]),
     }
     for name, (res, args) in sig.items():
         fn = getattr(lib, name)
@@ -274,3 +289,55 @@ class Layer:
         else:
             self._check(self.lib.dsmoe_dense_bwd(*args, _stream()))
         return g
+
+
+class MoaLayer:
+    """One `dsmoe_moa_ctx` plus its workspace (Mixture-of-Attention-heads layer, forward, bf16)."""
+
+    def __init__(self, d_model: int, n_experts: int, n_head: int, d_head: int, max_tokens: int, device="cuda:0"):
+        import torch
+        self.lib = load_library()
+        self.torch = torch
+        self.device = torch.device(device)
+        self.d, self.E, self.n_head, self.d_head = d_model, n_experts, n_head, d_head
+        self.max_tokens = max_tokens
+        desc = MoaDesc(d_model, n_experts, n_head, d_head, BF16, max_tokens)
+        self.ctx = c_void_p()
+        rc = self.lib.dsmoe_moa_create(byref(desc), byref(self.ctx))
+        if rc != OK:
+            raise DsmoeError(rc, "dsmoe_moa_create rejected the descriptor")
+        nbytes = c_size_t()
+        self._check(self.lib.dsmoe_moa_workspace_bytes(self.ctx, byref(nbytes)))
+        self.workspace_bytes = nbytes.value
+        with torch.cuda.device(self.device):
+            self.workspace = torch.empty(nbytes.value + 256, dtype=torch.uint8, device=self.device)
+            base = (self.workspace.data_ptr() + 255) // 256 * 256
+            self._check(self.lib.dsmoe_moa_set_workspace(self.ctx, c_void_p(base), c_size_t(nbytes.value)))
+
+    def __del__(self):
+        try:
+            if getattr(self, "ctx", None):
+                self.lib.dsmoe_moa_destroy(self.ctx)
+                self.ctx = None
+        except Exception:
+            pass
+
+    def _check(self, rc: int):
+        if rc != OK:
+            raise DsmoeError(rc, self.lib.dsmoe_moa_last_error(self.ctx).decode())
+
+    def fwd(self, x, w_r, b_r, w_q, k_cache, v_cache, w_o, mode: int, k: int = 0, eps: float = 0.0,
+            scale: float = 1.0, out=None):
+        T, L = x.shape[0], k_cache.shape[1]
+        if out is None:
+            out = self.torch.empty((T, self.d), dtype=self.torch.bfloat16, device=self.device)
+        self._check(self.lib.dsmoe_moa_fwd(self.ctx, _ptr(x), _ptr(w_r), _ptr(b_r), _ptr(w_q), _ptr(k_cache),
+                                           _ptr(v_cache), _ptr(w_o), T, L, mode, k, eps, scale, _ptr(out), _stream()))
+        return out
+
+    def routing(self, T: int):
+        t = self.torch
+        probs = t.empty((T, self.E), dtype=t.float32, device=self.device)
+        mask = t.empty((T,), dtype=t.int64, device=self.device)
+        self._check(self.lib.dsmoe_moa_routing(self.ctx, T, _ptr(probs), _ptr(mask), _stream()))
+        return probs, mask

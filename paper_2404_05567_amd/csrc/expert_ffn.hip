@@ -393,6 +393,18 @@ hipError_t launch_down_dense(const dsmoe_ctx* c, const void* h, int T, int k_tot
   return hipGetLastError();
 }
 
+// out[g][r][:] = x[row_index[g * rows + r]][:] W[g] for `groups` matrices W[g] of [k][n]: every group reads its
+// rows of x through the index (bf16 only).  The query projections of the attention experts are this product
+// with the same token rows in every group.
+hipError_t launch_gathered_rows_gemm(const dsmoe_ctx* c, const void* x, const int32_t* row_index, int groups,
+                                     int rows, int k, int n, const void* w, void* out, hipStream_t s) {
+  const long tiles = (long)groups * ((rows + 255) / 256 + 1) * ((n + 255) / 256);
+  const int g = (int)((std::min<long>(tiles, c->n_cu) + 7) / 8 * 8);
+  down_bf16_kernel<256, false, true><<<dim3(g), dim3(kThreads2), 0, s>>>(
+      (const bf16_t*)x, row_index, nullptr, (const bf16_t*)w, (bf16_t*)out, n, k, groups, rows);
+  return hipGetLastError();
+}
+
 hipError_t launch_expert_ffn(const dsmoe_ctx* c, const void* x, const void* x_perm, const int32_t* row_token,
                              const int32_t* expert_off, const void* w_gate, const void* w_up,
                              const void* w_down, void* y_perm, hipStream_t s) {
