@@ -187,6 +187,39 @@ class Bench:
             "bwd_with_mi_loss_term_ms": ms_bmi, "mi_loss_ms": ms_mi,
         }
 
+    # ---- Mixture-of-Attention-heads forward (m2) ----------------------------------------------------
+    def moa_prefill(self, steps, warmup, name="m2"):
+        """The attention layer of the paper's 6B shape (Table 1) on a 2048-token prompt, every expert active
+        (how the paper runs this layer at inference)."""
+        torch, gen, dsmoe = self.torch, self.gen, self.dsmoe
+        cfg = gen.MOA_CONFIGS[name]
+        inp = gen.make_moa(cfg)
+        bf = torch.bfloat16
+        to = lambda a: torch.from_numpy(a).to(self.dev).to(bf)
+        x, w_r, w_q, k, v, w_o = (to(a) for a in (inp.x, inp.w_r, inp.w_q, inp.k, inp.v, inp.w_o))
+        layer = dsmoe.MoaLayer(cfg.d, cfg.E, cfg.n_head, cfg.d_head, max_tokens=cfg.T)
+        out = torch.empty((cfg.T, cfg.d), dtype=bf, device=self.dev)
+        scale = 1.0 / cfg.d_head ** 0.5
+        mode = {"dense": dsmoe.SEL_ALL, "topk": dsmoe.SEL_TOPK, "threshold": dsmoe.SEL_THRESHOLD}[cfg.mode]
+
+        def step():
+            layer.fwd(x, w_r, None, w_q, k, v, w_o, mode, cfg.k, cfg.eps, scale, out=out)
+
+        ms = self.timed(step, steps, warmup)
+        assert torch.isfinite(out.float()).all()
+        hd = cfg.n_head * cfg.d_head
+        pairs = sum(cfg.L - cfg.T + t + 1 for t in range(cfg.T))          # (query, visible key) pairs per head
+        flops_proj = 2 * 2 * cfg.T * cfg.d * cfg.E * hd + 2 * cfg.T * cfg.d * cfg.E
+        flops_att = 4 * cfg.E * cfg.n_head * cfg.d_head * pairs
+        return {
+            "workload": f"{name}: attention-expert layer forward, T={cfg.T} L={cfg.L} d_model={cfg.d} E={cfg.E} "
+                        f"heads={cfg.n_head}x{cfg.d_head}, {cfg.mode}",
+            "ms_per_step": ms, "tokens_per_s": cfg.T / (ms * 1e-3),
+            "tflop_projections": flops_proj / 1e12, "tflop_attention": flops_att / 1e12,
+            "tflops_per_s": (flops_proj + flops_att) / (ms * 1e-3) / 1e12,
+            "frac_of_bf16_peak": (flops_proj + flops_att) / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+        }
+
     # ---- decode sizes (c3) --------------------------------------------------------------------------
     def decode(self, steps, warmup, n_sets=16, shape=None):
         """T in {1, 8, 32, 128} x {top-4, threshold 0.02} on the c2 layer shape.  The loop cycles through
@@ -255,7 +288,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workloads", default="c2,c3,c4,c5,c2x",
+    ap.add_argument("--workloads", default="c2,c3,c4,c5,c2x,m2",
                     help="comma-separated subset of c2,c3,c4,c5,c2x (c2 is the headline and always runs; c2x = "
                          "c2's shapes with the GeLU two-matrix expert and with Threshold-TopK selection)")
     ap.add_argument("--cpu-passes", type=int, default=20, help="0 skips the CPU baseline")
@@ -298,6 +331,9 @@ def main():
     if "c2x" in wl:   # the rows beyond the base scope, on the headline shapes
         others["c2_gelu_expert"] = b.sparse_prefill("c2", side_steps, 3, expert="gelu")
         others["c2_threshold_topk"] = b.sparse_prefill("c2", side_steps, 3, threshold_topk=True)
+
+    if "m2" in wl:    # the attention-expert layer (Sec. 3.2), the paper's 6B shape
+        others["m2_attention_experts"] = b.moa_prefill(side_steps, 3)
 
     result = {
         "metric": METRIC,

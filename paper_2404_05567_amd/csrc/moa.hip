@@ -69,7 +69,7 @@ typedef __attribute__((address_space(3))) char lds_byte;
 // care about their order.  So P never leaves the registers.  Softmax is the running-maximum form; a query's
 // two lanes (h = 0, 1) share the maximum and keep separate partial sums until the end.
 template <int DH>
-__global__ void __launch_bounds__(256)
+__global__ void __launch_bounds__(256, 2)
 moa_attention_kernel(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
                      const float* __restrict__ probs, const unsigned long long* __restrict__ mask,
                      bf16_t* __restrict__ Cs, int T, int L, int E, int NH, float scale_log2e) {
@@ -82,8 +82,8 @@ moa_attention_kernel(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K,
   __shared__ __align__(16) char v_tile[DH * VP];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, q = lane & 31, h = lane >> 5;
   const int n_qt = (T + BQ - 1) / BQ;
-  const int qt = n_qt - 1 - (int)blockIdx.x;             // the tiles with the most keys start first
-  const int j = blockIdx.y, e = blockIdx.z;
+  const int qt = n_qt - 1 - (int)blockIdx.y;             // the tiles with the most keys start first, for every head
+  const int j = blockIdx.x % NH, e = blockIdx.x / NH;
   const int pos0 = L - T, hd = NH * DH;
   const int t = qt * BQ + wave * 32 + q, tq = min(t, T - 1);
 
@@ -143,6 +143,7 @@ moa_attention_kernel(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K,
   };
 
   const int limit = pos0 + t;                            // last cache position query t sees
+  const int wave_limit = pos0 + qt * BQ + wave * 32;     // ... and the wave's first query
   load_tile(0);
   for (int kt = 0; kt < n_kt; ++kt) {
     __syncthreads();                                     // the previous tile has been read by every wave
@@ -160,28 +161,38 @@ moa_attention_kernel(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K,
     }
     const int key0 = kt * BKEY + 4 * h;
     float mx = -INFINITY;
+    if (kt * BKEY + BKEY - 1 <= wave_limit) {            // the whole tile is visible to every query of the wave
 #pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      const int key = key0 + 8 * (r / 4) + r % 4;
-      sacc[r] = key <= limit ? sacc[r] * scale_log2e : -INFINITY;
-      mx = fmaxf(mx, sacc[r]);
+      for (int r = 0; r < 16; ++r) {
+        sacc[r] *= scale_log2e;
+        mx = fmaxf(mx, sacc[r]);
+      }
+    } else {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int key = key0 + 8 * (r / 4) + r % 4;
+        sacc[r] = key <= limit ? sacc[r] * scale_log2e : -INFINITY;
+        mx = fmaxf(mx, sacc[r]);
+      }
     }
     mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
     const float m_new = fmaxf(m_run, mx);
     const float m_safe = m_new == -INFINITY ? 0.f : m_new;
-    const float alpha = exp2f(m_run - m_safe);
+    const float alpha = __builtin_amdgcn_exp2f(m_run - m_safe);   // arguments <= 0: the bare instruction will do
     m_run = m_new;
     float psum = 0.f;
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
-      sacc[r] = exp2f(sacc[r] - m_safe);
+      sacc[r] = __builtin_amdgcn_exp2f(sacc[r] - m_safe);
       psum += sacc[r];
     }
     l_run = l_run * alpha + psum;
+    if (__any(alpha != 1.f)) {      // most tiles leave every running maximum of the wave as it is
 #pragma unroll
-    for (int dt = 0; dt < NDT; ++dt)
+      for (int dt = 0; dt < NDT; ++dt)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) o[dt][r] *= alpha;
+        for (int r = 0; r < 16; ++r) o[dt][r] *= alpha;
+    }
     u32x4 pf[2];
 #pragma unroll
     for (int s = 0; s < 2; ++s)
@@ -323,7 +334,7 @@ int32_t dsmoe_moa_fwd(dsmoe_moa_ctx* c, const void* x, const void* w_r, const vo
   moa_row_index_kernel<<<dim3((n_idx + 255) / 256), dim3(256), 0, s>>>(rowidx, T, n_idx);
   MOA_HIP(c, hipGetLastError());
   MOA_HIP(c, launch_gathered_rows_gemm(&c->inner, x, rowidx, E, T, d, hd, w_q, q, s));
-  const dim3 grid((T + 127) / 128, NH, E);
+  const dim3 grid(NH * E, (T + 127) / 128);
   const float sl2e = scale * 1.4426950408889634f;
   const unsigned long long* mk = reinterpret_cast<const unsigned long long*>(mask);
   if (DH == 64)

@@ -96,6 +96,49 @@ def test_calls_reject_bad_arguments_before_any_device_work(lib):
     assert lib.dsmoe_destroy(ctx) == dsmoe.OK
 
 
+def test_attention_layer_entry_points_validate_on_the_host(lib):
+    def make_moa(**kw):
+        d = dict(d_model=256, n_experts=8, n_head=2, d_head=64, dtype=dsmoe.BF16, max_tokens=64)
+        d.update(kw)
+        ctx = c_void_p()
+        return lib.dsmoe_moa_create(byref(dsmoe.MoaDesc(**d)), byref(ctx)), ctx
+
+    assert make_moa(dtype=dsmoe.F32)[0] == dsmoe.ERR_UNSUPPORTED
+    assert make_moa(d_head=96)[0] == dsmoe.ERR_UNSUPPORTED
+    assert make_moa(n_experts=12)[0] == dsmoe.ERR_UNSUPPORTED
+    assert make_moa(d_model=100)[0] == dsmoe.ERR_UNSUPPORTED
+    assert make_moa(n_head=0)[0] == dsmoe.ERR_INVALID_ARG
+    rc, ctx = make_moa()
+    assert rc == dsmoe.OK and ctx.value
+    n = c_size_t()
+    assert lib.dsmoe_moa_workspace_bytes(ctx, byref(n)) == dsmoe.OK
+    # scores, masks, counts, row index, Q and the weighted attention outputs
+    assert n.value >= 64 * 8 * 4 + 64 * 8 + 2 * (8 * 64 * 128 * 2)
+    fake, odd, s = c_void_p(0x1000), c_void_p(0x1004), None
+    import ctypes as ct
+    one = ct.c_float(1.0)
+    call = lambda **kw: lib.dsmoe_moa_fwd(
+        ctx, kw.get("x", fake), fake, None, fake, fake, fake, fake, kw.get("T", 4), kw.get("L", 8),
+        kw.get("mode", dsmoe.SEL_TOPK), kw.get("k", 2), ct.c_float(kw.get("eps", 0.0)), kw.get("scale", one), fake, s)
+    assert call() == dsmoe.ERR_WORKSPACE
+    assert b"workspace" in lib.dsmoe_moa_last_error(ctx)
+    assert call(T=65) == dsmoe.ERR_INVALID_ARG
+    assert call(T=4, L=3) == dsmoe.ERR_INVALID_ARG
+    assert call(k=0) == dsmoe.ERR_INVALID_ARG
+    assert call(mode=dsmoe.SEL_THRESHOLD, eps=-1.0) == dsmoe.ERR_INVALID_ARG
+    assert call(mode=dsmoe.SEL_THRESHOLD_TOPK) == dsmoe.ERR_INVALID_ARG
+    assert call(scale=ct.c_float(float("nan"))) == dsmoe.ERR_INVALID_ARG
+    assert lib.dsmoe_moa_routing(ctx, 4, fake, fake, s) == dsmoe.ERR_WORKSPACE
+    assert lib.dsmoe_moa_set_workspace(ctx, c_void_p(0x1010), 1 << 30) == dsmoe.ERR_INVALID_ARG
+    assert lib.dsmoe_moa_set_workspace(ctx, fake, 16) == dsmoe.ERR_WORKSPACE
+    assert lib.dsmoe_moa_set_workspace(ctx, fake, n.value) == dsmoe.OK      # only recorded, not touched
+    assert call(x=None) == dsmoe.ERR_INVALID_ARG
+    assert call(x=odd) == dsmoe.ERR_INVALID_ARG
+    assert call(T=0) == dsmoe.OK
+    assert lib.dsmoe_moa_destroy(ctx) == dsmoe.OK
+    assert lib.dsmoe_moa_destroy(None) == dsmoe.ERR_INVALID_ARG
+
+
 def test_binding_fails_loudly_without_the_library(monkeypatch, tmp_path):
     monkeypatch.setattr(dsmoe, "_lib", None)
     monkeypatch.setattr(dsmoe, "LIB_PATH", str(tmp_path / "libdsmoe.so"))
