@@ -102,8 +102,8 @@ hipError_t launch_expert_ffn(const dsmoe_ctx* c, const void* x, const void* x_pe
                              const void* w_down, void* y_perm, hipStream_t s);
 hipError_t launch_down_dense(const dsmoe_ctx* c, const void* h, int T, int k_total, const void* w, void* out,
                              hipStream_t s);
-hipError_t launch_gathered_rows_gemm(const dsmoe_ctx* c, const void* x, const int32_t* row_index, int groups,
-                                     int rows, int k, int n, const void* w, void* out, hipStream_t s);
+hipError_t launch_shared_rows_gemm(const dsmoe_ctx* c, const void* x, int groups, int rows, int k, int n,
+                                   const void* w, void* out, hipStream_t s);
 // dispatch.hip (combine)
 hipError_t launch_combine(const dsmoe_ctx* c, const void* y_perm, const float* row_weight,
                           const int32_t* tok_off, const int32_t* tok_rows, int T, void* out, hipStream_t s);

@@ -251,7 +251,9 @@ gateup_bf16_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ x_pe
       [&](const RowTile& t, const typename TH::Acc& acc) { epilogue(TH{}, std::false_type{}, t, acc); });
 }
 
-template <int BM, bool GELU = false, bool GATHER = false>
+// GATHER: 0 = row r of group e is row row_off[e] + r of h, 1 = row row_token[row_off[e] + r], 2 = row r (every
+// group reads the same rows)
+template <int BM, bool GELU = false, int GATHER = 0>
 __global__ void __launch_bounds__(kThreads2)
 down_bf16_kernel(const bf16_t* __restrict__ h, const int32_t* __restrict__ row_token,
                  const int32_t* __restrict__ expert_off, const bf16_t* __restrict__ w_down, bf16_t* __restrict__ y,
@@ -267,9 +269,10 @@ down_bf16_kernel(const bf16_t* __restrict__ h, const int32_t* __restrict__ row_t
   SplitWalker tw;
   tw.init(gt, E, (d + BN - 1) / BN, BM / 2);
   auto setup = [&](const RowTile& t, auto& L, auto& R) {
-    const int row0 = t.row0, n0 = t.nt * BN;
+    const int row0 = t.row0, n0 = t.nt * BN, group0 = gt.row_off[t.e];
     L.init(t.valid, 0, [&](int r) {
-      return h + (GATHER ? (size_t)row_token[row0 + r] : (size_t)(row0 + r)) * f;
+      if constexpr (GATHER == 2) return h + (size_t)(row0 - group0 + r) * f;
+      return h + (GATHER == 1 ? (size_t)row_token[row0 + r] : (size_t)(row0 + r)) * f;
     });
     const bf16_t* const base[1] = {w_down + (size_t)t.e * f * d + n0};
     R.init(base, d, min(BN, d - n0), f);
@@ -316,10 +319,10 @@ static hipError_t launch_ffn_bf16(const dsmoe_ctx* c, const void* x, const void*
     // H = gelu(rows W_1): output width f, contraction over d, 256-column tiles
     const int g1g = (int)((std::min<long>(max_mt * ((f + 255) / 256), c->n_cu) + 7) / 8 * 8);
     if (x_perm)
-      down_bf16_kernel<BM, true, false><<<dim3(g1g), dim3(kThreads2), 0, s>>>(
+      down_bf16_kernel<BM, true, 0><<<dim3(g1g), dim3(kThreads2), 0, s>>>(
           (const bf16_t*)x_perm, nullptr, expert_off, (const bf16_t*)w_gate, h, f, d, E, 0);
     else
-      down_bf16_kernel<BM, true, true><<<dim3(g1g), dim3(kThreads2), 0, s>>>(
+      down_bf16_kernel<BM, true, 1><<<dim3(g1g), dim3(kThreads2), 0, s>>>(
           (const bf16_t*)x, row_token, expert_off, (const bf16_t*)w_gate, h, f, d, E, 0);
   } else {
     gateup_bf16_kernel<BM><<<dim3(g1), dim3(kThreads2), 0, s>>>(
@@ -393,15 +396,14 @@ hipError_t launch_down_dense(const dsmoe_ctx* c, const void* h, int T, int k_tot
   return hipGetLastError();
 }
 
-// out[g][r][:] = x[row_index[g * rows + r]][:] W[g] for `groups` matrices W[g] of [k][n]: every group reads its
-// rows of x through the index (bf16 only).  The query projections of the attention experts are this product
-// with the same token rows in every group.
-hipError_t launch_gathered_rows_gemm(const dsmoe_ctx* c, const void* x, const int32_t* row_index, int groups,
-                                     int rows, int k, int n, const void* w, void* out, hipStream_t s) {
+// out[g][r][:] = x[r][:] W[g] for `groups` matrices W[g] of [k][n] and the same `rows` rows of x in every group
+// (bf16 only): the query projections of the attention experts.
+hipError_t launch_shared_rows_gemm(const dsmoe_ctx* c, const void* x, int groups, int rows, int k, int n,
+                                   const void* w, void* out, hipStream_t s) {
   const long tiles = (long)groups * ((rows + 255) / 256 + 1) * ((n + 255) / 256);
   const int g = (int)((std::min<long>(tiles, c->n_cu) + 7) / 8 * 8);
-  down_bf16_kernel<256, false, true><<<dim3(g), dim3(kThreads2), 0, s>>>(
-      (const bf16_t*)x, row_index, nullptr, (const bf16_t*)w, (bf16_t*)out, n, k, groups, rows);
+  down_bf16_kernel<256, false, 2><<<dim3(g), dim3(kThreads2), 0, s>>>(
+      (const bf16_t*)x, nullptr, nullptr, (const bf16_t*)w, (bf16_t*)out, n, k, groups, rows);
   return hipGetLastError();
 }
 

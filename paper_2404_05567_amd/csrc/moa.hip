@@ -22,7 +22,7 @@ struct dsmoe_moa_ctx {
   dsmoe_ctx inner;          // descriptor and CU count for the shared launchers; owns nothing
   char* workspace;
   size_t workspace_bytes;
-  size_t o_probs, o_mask, o_cnt, o_rowidx, o_q, o_cs, total;
+  size_t o_probs, o_mask, o_cnt, o_q, o_cs, total;
   char err[256];
 };
 
@@ -49,14 +49,6 @@ bool misaligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u)
     hipError_t e_ = (expr);                                                                             \
     if (e_ != hipSuccess) return moa_fail((c), DSMOE_ERR_HIP, "%s: %s", #expr, hipGetErrorString(e_));   \
   } while (0)
-
-// row_index[g * T + r] = r: every expert's query projection reads the same T token rows
-__global__ void moa_row_index_kernel(int32_t* __restrict__ idx, int T, int n) {
-  const int i = blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < n) idx[i] = i % T;
-}
-
-typedef __attribute__((address_space(3))) char lds_byte;
 
 // One block: 128 queries (4 waves of 32) of one expert e and head j against the keys they may see, 32 keys at
 // a time.  Both products run on the 32x32x16 bf16 MFMA with the queries on the lane axis:
@@ -248,7 +240,6 @@ int32_t dsmoe_moa_create(const dsmoe_moa_desc* desc, dsmoe_moa_ctx** out) {
   c->o_probs = take(T * E * 4);
   c->o_mask = take(T * 8);
   c->o_cnt = take(T * 4);
-  c->o_rowidx = take(E * T * 4);
   c->o_q = take(E * T * hd * 2);
   c->o_cs = take(T * E * hd * 2);
   c->total = o;
@@ -323,17 +314,13 @@ int32_t dsmoe_moa_fwd(dsmoe_moa_ctx* c, const void* x, const void* w_r, const vo
   float* probs = reinterpret_cast<float*>(c->workspace + c->o_probs);
   uint64_t* mask = reinterpret_cast<uint64_t*>(c->workspace + c->o_mask);
   int32_t* cnt = reinterpret_cast<int32_t*>(c->workspace + c->o_cnt);
-  int32_t* rowidx = reinterpret_cast<int32_t*>(c->workspace + c->o_rowidx);
   bf16_t* q = reinterpret_cast<bf16_t*>(c->workspace + c->o_q);
   bf16_t* cs = reinterpret_cast<bf16_t*>(c->workspace + c->o_cs);
   const bool all = mode == DSMOE_SEL_ALL;
 
   // every expert selected = the E highest scores: the masks are then all ones
   MOA_HIP(c, launch_route(&c->inner, x, w_r, b_r, T, probs, all ? DSMOE_SEL_TOPK : mode, all ? E : k, eps, mask, cnt, s));
-  const int n_idx = E * T;
-  moa_row_index_kernel<<<dim3((n_idx + 255) / 256), dim3(256), 0, s>>>(rowidx, T, n_idx);
-  MOA_HIP(c, hipGetLastError());
-  MOA_HIP(c, launch_gathered_rows_gemm(&c->inner, x, rowidx, E, T, d, hd, w_q, q, s));
+  MOA_HIP(c, launch_shared_rows_gemm(&c->inner, x, E, T, d, hd, w_q, q, s));
   const dim3 grid(NH * E, (T + 127) / 128);
   const float sl2e = scale * 1.4426950408889634f;
   const unsigned long long* mk = reinterpret_cast<const unsigned long long*>(mask);
