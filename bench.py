@@ -221,7 +221,7 @@ class Bench:
         }
 
     # ---- decode sizes (c3) --------------------------------------------------------------------------
-    def decode(self, steps, warmup, n_sets=16, shape=None):
+    def decode(self, steps, warmup, n_sets=16, shape=None, tokens=(1, 8, 32, 128)):
         """T in {1, 8, 32, 128} x {top-4, threshold 0.02} on the c2 layer shape.  The loop cycles through
         `n_sets` independent weight sets (3.2 GB in all), as a model's layers would, so no call finds its
         weights in the 256 MB last-level cache.  Timed both as plain launches and as a replayed HIP graph of
@@ -242,7 +242,7 @@ class Bench:
                      w_down=rnd((E, f, d), 0.02)) for _ in range(n_sets)]
         layer = dsmoe.Layer(d, f, E, "bf16", max_tokens=128)
         results = []
-        for T in (1, 8, 32, 128):
+        for T in tokens:
             x = rnd((T, d), 1.0)
             out = torch.empty((T, d), dtype=bf, device=self.dev)
             for mode_name, mode, k, eps in (("top4", dsmoe.SEL_TOPK, 4, 0.0), ("eps0.02", dsmoe.SEL_THRESHOLD, 0, 0.02)):
@@ -292,6 +292,8 @@ def main():
                     help="comma-separated subset of c2,c3,c4,c5,c2x (c2 is the headline and always runs; c2x = "
                          "c2's shapes with the GeLU two-matrix expert and with Threshold-TopK selection)")
     ap.add_argument("--cpu-passes", type=int, default=20, help="0 skips the CPU baseline")
+    ap.add_argument("--decode-tokens", default="1,8,32,128", help="batch sizes of the decode workload (profiling aid)")
+    ap.add_argument("--skip-large-decode", action="store_true", help="leave out the second decode layer shape")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MiB",
                     help="also run three plain device copies of this many MiB (a kernel of known HBM traffic, "
                          "used to scale rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
@@ -320,10 +322,13 @@ def main():
     side_steps = max(5, min(args.steps, 20))
     others = {}
     if "c3" in wl:
-        others["c3"] = b.decode(side_steps, 3)
+        tokens = tuple(int(v) for v in args.decode_tokens.split(","))
+        others["c3"] = b.decode(side_steps, 3, tokens=tokens)
         # context: the same path on the expert layer of the largest model in the paper's speed test (Table 6:
         # embedding 7168, 32 experts of width 896), where a layer's weights are 1.2 GB and launch costs matter less
-        others["c3_largest_paper_layer"] = b.decode(max(5, side_steps // 2), 2, n_sets=3, shape=(7168, 896, 32))
+        if not args.skip_large_decode:
+            others["c3_largest_paper_layer"] = b.decode(max(5, side_steps // 2), 2, n_sets=3, shape=(7168, 896, 32),
+                                                        tokens=tokens)
     if "c4" in wl:
         others["c4"] = b.dense_training(side_steps, 3)
     if "c5" in wl:
