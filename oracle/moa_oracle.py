@@ -82,3 +82,55 @@ def moa_forward(X, W_r, b_r, W_q, K, V, W_o, mode: str, k: int = 0, eps: float =
         Oi = expert_heads(X, W_q[i], K, V, W_o[i], pos0, scale)
         O += (S[:, i] * M[:, i])[:, None] * Oi
     return O, S, M
+
+
+# --------------------------------------------------------------------------------------------------
+# Dense training of the attention layer: every expert active, weighted by its score (Sec. 3.2, "Dense
+# Training"), and the gradients of that forward.  The score gradient follows Eq. 3 with the attention
+# experts in the place of the MLP experts; the rest is the chain rule through Eq. 7.
+# --------------------------------------------------------------------------------------------------
+def _attention_probs(Q, K_j, pos0: int, scale: float) -> np.ndarray:
+    T, L = Q.shape[0], K_j.shape[0]
+    A = scale * (Q @ K_j.T)
+    visible = np.arange(L)[None, :] <= (pos0 + np.arange(T))[:, None]
+    A = np.where(visible, A, -np.inf)
+    A = A - A.max(axis=1, keepdims=True)
+    P = np.exp(A)
+    return P / P.sum(axis=1, keepdims=True)
+
+
+def moa_dense_backward(X, W_r, b_r, W_q, K, V, W_o, dO, scale: float = 1.0):
+    """Gradients of O = sum_i S_i sum_j O_ij (all experts) with respect to X, W_r, b_r, W_q, W_o and the cache
+    K, V, for the upstream gradient dO[T,d].  Returns a dict of arrays shaped like their tensors."""
+    X, W_r, W_q, K, V, W_o, dO = (_f64(a) for a in (X, W_r, W_q, K, V, W_o, dO))
+    T, d = X.shape
+    E, n_head, L, d_head = W_q.shape[0], K.shape[0], K.shape[1], K.shape[2]
+    pos0 = L - T
+    S = moe.route(X, W_r, b_r)
+    dX = np.zeros_like(X)
+    dW_q, dW_o = np.zeros_like(W_q), np.zeros_like(W_o)
+    dK, dV = np.zeros_like(K), np.zeros_like(V)
+    dS = np.zeros_like(S)
+    for i in range(E):
+        Qi = X @ W_q[i]
+        dQi = np.zeros_like(Qi)
+        out_i = np.zeros((T, d), dtype=F64)                    # e_i(X) = sum_j O_ij
+        dE = S[:, i][:, None] * dO                             # gradient reaching the expert's output
+        for j in range(n_head):
+            cols = slice(j * d_head, (j + 1) * d_head)
+            P = _attention_probs(Qi[:, cols], K[j], pos0, scale)
+            C = P @ V[j]
+            out_i += C @ W_o[i][cols, :]
+            dW_o[i][cols, :] += C.T @ dE
+            dC = dE @ W_o[i][cols, :].T
+            dV[j] += P.T @ dC
+            dP = dC @ V[j].T
+            dA = P * (dP - (dP * P).sum(axis=1, keepdims=True))   # softmax backward, row by row
+            dQi[:, cols] = scale * (dA @ K[j])
+            dK[j] += scale * (dA.T @ Qi[:, cols])
+        dS[:, i] = (out_i * dO).sum(axis=1)                    # Eq. 3: grad S_i = <e_i(X), dO>
+        dW_q[i] = X.T @ dQi
+        dX += dQi @ W_q[i].T
+    dZ = S * (dS - (dS * S).sum(axis=1, keepdims=True))
+    dX += dZ @ W_r.T
+    return dict(dX=dX, dW_r=X.T @ dZ, db_r=dZ.sum(axis=0), dW_q=dW_q, dW_o=dW_o, dK=dK, dV=dV, dS=dS)

@@ -136,3 +136,64 @@ def test_generator_shapes_follow_table_1():
     assert inp.w_q.shape == (8, 128, 128) and inp.k.shape == (2, 80, 64) and inp.w_o.shape == (8, 128, 128)
     again = gen.make_moa(gen.MOA_CONFIGS["m1"])
     np.testing.assert_array_equal(inp.k, again.k)
+
+
+# ---- dense-training gradients of the attention layer ---------------------------------------------------
+def _loss(p, dO, scale):
+    O, _, _ = moa.moa_forward(p["X"], p["W_r"], p["b_r"], p["W_q"], p["K"], p["V"], p["W_o"], "dense", scale=scale)
+    return float((O * dO).sum())
+
+
+@pytest.mark.parametrize("scale", [1.0, 0.6])
+def test_dense_backward_against_central_differences(scale):
+    p = tiny(T=4, L=6, d=5, E=3, n_head=2, d_head=3, seed=21)
+    dO = np.random.default_rng(2).standard_normal(p["X"].shape)
+    g = moa.moa_dense_backward(p["X"], p["W_r"], p["b_r"], p["W_q"], p["K"], p["V"], p["W_o"], dO, scale)
+    h = 1e-6
+    for name, key in (("dX", "X"), ("dW_r", "W_r"), ("db_r", "b_r"), ("dW_q", "W_q"), ("dW_o", "W_o"), ("dK", "K"),
+                      ("dV", "V")):
+        num = np.zeros_like(p[key])
+        it = np.nditer(p[key], flags=["multi_index"])
+        for _ in it:
+            idx = it.multi_index
+            keep = p[key][idx]
+            p[key][idx] = keep + h
+            up = _loss(p, dO, scale)
+            p[key][idx] = keep - h
+            dn = _loss(p, dO, scale)
+            p[key][idx] = keep
+            num[idx] = (up - dn) / (2 * h)
+        np.testing.assert_allclose(g[name], num, rtol=2e-6, atol=2e-8, err_msg=name)
+
+
+def test_dense_backward_against_autograd_of_an_independent_layer():
+    torch = pytest.importorskip("torch")
+    p = tiny(T=5, L=8, d=6, E=4, n_head=2, d_head=4, seed=23)
+    dO = np.random.default_rng(4).standard_normal(p["X"].shape)
+    scale = 0.5
+    t = {k: torch.tensor(v, dtype=torch.float64, requires_grad=True) for k, v in p.items()}
+    T, L = 5, 8
+    S = torch.softmax(t["X"] @ t["W_r"] + t["b_r"], dim=1)
+    Q = torch.einsum("td,edh->eth", t["X"], t["W_q"]).reshape(4, T, 2, 4)              # [E, T, head, d_head]
+    att = scale * torch.einsum("etjc,jlc->ejtl", Q, t["K"])                             # [E, head, T, L]
+    visible = torch.arange(L)[None, :] <= (L - T + torch.arange(T))[:, None]
+    att = att.masked_fill(~visible, float("-inf"))
+    ctx = torch.einsum("ejtl,jlc->etjc", torch.softmax(att, dim=-1), t["V"]).reshape(4, T, 8)
+    O = torch.einsum("te,eth,ehd->td", S, ctx, t["W_o"])
+    (O * torch.tensor(dO)).sum().backward()
+    g = moa.moa_dense_backward(p["X"], p["W_r"], p["b_r"], p["W_q"], p["K"], p["V"], p["W_o"], dO, scale)
+    for name, key in (("dX", "X"), ("dW_r", "W_r"), ("db_r", "b_r"), ("dW_q", "W_q"), ("dW_o", "W_o"), ("dK", "K"),
+                      ("dV", "V")):
+        np.testing.assert_allclose(g[name], t[key].grad.numpy(), rtol=1e-10, atol=1e-12, err_msg=name)
+    # and the forward of that layer is the checker's forward
+    Oc, _, _ = moa.moa_forward(p["X"], p["W_r"], p["b_r"], p["W_q"], p["K"], p["V"], p["W_o"], "dense", scale=scale)
+    np.testing.assert_allclose(Oc, O.detach().numpy(), rtol=1e-11, atol=1e-13)
+
+
+def test_score_gradient_is_the_inner_product_of_eq_3():
+    p = tiny(seed=25)
+    dO = np.random.default_rng(6).standard_normal(p["X"].shape)
+    g = moa.moa_dense_backward(p["X"], p["W_r"], p["b_r"], p["W_q"], p["K"], p["V"], p["W_o"], dO, 1.0)
+    for i in range(4):
+        e_i = moa.expert_heads(p["X"], p["W_q"][i], p["K"], p["V"], p["W_o"][i], p["K"].shape[1] - p["X"].shape[0], 1.0)
+        np.testing.assert_allclose(g["dS"][:, i], (e_i * dO).sum(axis=1), rtol=1e-12, atol=1e-13)
