@@ -70,7 +70,7 @@ ScratchLayout scratch_layout(const dsmoe_ctx* c, int T) {
   return l;
 }
 
-__device__ __forceinline__ float sigmoid_f(float g) { return 1.f / (1.f + __expf(-g)); }
+__device__ __forceinline__ float sigmoid_f(float g) { return __builtin_amdgcn_rcpf(1.f + __expf(-g)); }
 // exact GeLU g * Phi(g) and its derivative Phi(g) + g * phi(g) (the two-matrix expert of Sec. 4.1)
 __device__ __forceinline__ float gelu_cdf_f(float g) { return 0.5f * (1.f + erff(g * 0.70710678118654752f)); }
 __device__ __forceinline__ float gelu_prime_f(float g) {

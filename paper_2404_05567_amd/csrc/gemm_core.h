@@ -406,7 +406,8 @@ struct SplitWalker {
   }
 };
 
-__device__ __forceinline__ float silu_f(float g) { return g / (1.f + __expf(-g)); }
+// the reciprocal instruction (1 ulp) instead of a full-precision division: ten instructions fewer per element
+__device__ __forceinline__ float silu_f(float g) { return g * __builtin_amdgcn_rcpf(1.f + __expf(-g)); }
 // exact GeLU: g * Phi(g)
 __device__ __forceinline__ float gelu_f(float g) { return 0.5f * g * (1.f + erff(g * 0.70710678118654752f)); }
 
