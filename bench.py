@@ -55,9 +55,23 @@ def cpu_baseline(inp, cfg, passes: int):
     for _ in range(passes):
         orc.sparse_forward(inp.x, inp.w_r, inp.b_r, inp.w_gate, inp.w_up, inp.w_down, cfg.mode, cfg.k, cfg.eps)
     dt = time.perf_counter() - t0
-    return {"value": passes * cfg.T / dt, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
-            "sample": f"{passes} full passes of workload {cfg.name} ({cfg.T} tokens each), numpy fp64, "
-                      f"{dt:.1f} s wall"}
+    out = {"value": passes * cfg.T / dt, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
+           "sample": f"{passes} full passes of workload {cfg.name} ({cfg.T} tokens each), numpy fp64, "
+                     f"{dt:.1f} s wall"}
+    # context: the tiny config on one thread
+    try:
+        import dsmoe_inputs as gen
+        from threadpoolctl import threadpool_limits
+        c1 = gen.CONFIGS["c1"]
+        tiny = gen.make_layer(c1, 0)
+        with threadpool_limits(limits=1):
+            t0 = time.perf_counter()
+            for _ in range(5):
+                orc.sparse_forward(tiny.x, tiny.w_r, tiny.b_r, tiny.w_gate, tiny.w_up, tiny.w_down, c1.mode, c1.k, c1.eps)
+            out["c1_single_thread_ms_per_pass"] = (time.perf_counter() - t0) / 5 * 1e3
+    except ImportError:
+        pass
+    return out
 
 
 class Bench:
