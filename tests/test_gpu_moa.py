@@ -96,6 +96,12 @@ def test_sixteen_experts_of_the_1b_shape(torch, dsmoe):
     run_and_check(torch, dsmoe, conditioned(cfg), "threshold", 0, 0.05)
 
 
+def test_sixty_four_experts_of_one_head(torch, dsmoe):
+    cfg = gen.MoaConfig("e64", 15, T=100, L=1100, d=256, E=64, n_head=1, d_head=64, dtype="bf16", mode="topk", k=5,
+                        router_std=0.1)
+    run_and_check(torch, dsmoe, conditioned(cfg), "topk", 5, 0.0)
+
+
 def test_repeated_calls_are_bitwise_identical_and_no_tokens(torch, dsmoe):
     cfg = gen.MOA_CONFIGS["m1"]
     inp = conditioned(cfg)
