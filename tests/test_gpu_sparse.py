@@ -246,6 +246,34 @@ def test_expert_ffn_on_crafted_row_groups(torch, dsmoe, counts, expert):
             assert helpers.rel_err(y_gpu[off[e]:off[e + 1]], ref) <= TOL["bf16"], (e, counts[e], materialize)
 
 
+@pytest.mark.parametrize("counts", [[130] * 8, [300, 20, 0, 257, 5, 128, 129, 1]])
+def test_expert_ffn_long_contraction_few_tiles(torch, dsmoe, counts):
+    """Few row tiles and a long contraction (d = 2048, 64 K steps: the chained pipeline and the half tiles of an
+    uneven last turn); twice, bitwise equal."""
+    E, d, f, T = len(counts), 2048, 192, 400
+    cfg = gen.LayerConfig("ksplit", 32, T=T, d=d, E=E, f=f, dtype="bf16", mode="topk", k=1, router_std=0.05)
+    inp = gen.make_layer(cfg, 0)
+    rng = np.random.default_rng(6)
+    off = np.concatenate([[0], np.cumsum(counts)]).astype(np.int32)
+    nnz = int(off[-1])
+    row_token = rng.integers(0, T, size=nnz).astype(np.int32)
+    say(f"[case] long contraction, few tiles: E={E} nnz={nnz}")
+    w = weights_to_dev(torch, inp)
+    layer = dsmoe.Layer(d, f, E, "bf16", max_tokens=4096, max_rows=20000)
+    r = dict(expert_off=torch.from_numpy(off).cuda(), row_token=torch.from_numpy(row_token).cuda())
+    y1 = layer.expert_ffn(w["x"], r, w["w_gate"], w["w_up"], w["w_down"]).clone()
+    y2 = layer.expert_ffn(w["x"], r, w["w_gate"], w["w_up"], w["w_down"])
+    torch.cuda.synchronize()
+    assert torch.equal(y1[:nnz], y2[:nnz])
+    y_gpu = y2[:nnz].float().cpu().numpy()
+    for e in range(E):
+        if counts[e] == 0:
+            continue
+        rows = row_token[off[e]:off[e + 1]]
+        ref = orc.expert_ffn(inp.x[rows], inp.w_gate[e], inp.w_up[e], inp.w_down[e])
+        assert helpers.rel_err(y_gpu[off[e]:off[e + 1]], ref) <= TOL["bf16"], (e, counts[e])
+
+
 def test_skewed_router_bias_empty_and_hot_experts(torch, dsmoe):
     cfg = gen.LayerConfig("skew", 12, T=500, d=256, E=24, f=128, dtype="bf16", mode="threshold", eps=0.04,
                           router_std=0.05, zipf_s=2.0)
