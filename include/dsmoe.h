@@ -14,7 +14,8 @@
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls enqueue work and
  *     return; they never synchronise the stream (dsmoe_poll_error excepted).
  *   - Layouts are row-major: X[T,d], W_r[d,E], b_r[E], W_gate[E,d,f], W_up[E,d,f], W_down[E,f,d],
- *     with d = d_model, E = n_experts, f = d_ff.  "dtype" tensors hold fp32 or bf16 values as chosen
+ *     with d = d_model, E = n_experts, f = d_ff.  Limits: E <= 64 and a multiple of 8 (selection sets are
+ *     64-bit masks; bits at or above E of a caller's mask are ignored), d and f multiples of 64.  "dtype" tensors hold fp32 or bf16 values as chosen
  *     in the descriptor; router probabilities, row weights and all accumulators are fp32.
  *   - The expert is a SwiGLU MLP without biases: e(x) = (silu(x W_gate) * (x W_up)) W_down (default), or the
  *     paper's two-matrix GeLU MLP (dsmoe_set_expert_kind).
@@ -42,12 +43,18 @@ typedef struct dsmoe_ctx dsmoe_ctx;
 
 typedef enum { DSMOE_F32 = 0, DSMOE_BF16 = 1 } dsmoe_dtype;
 typedef enum { DSMOE_SEL_TOPK = 0, DSMOE_SEL_THRESHOLD = 1, DSMOE_SEL_THRESHOLD_TOPK = 2 } dsmoe_sel_mode;
+/* OR into DSMOE_SEL_THRESHOLD or DSMOE_SEL_THRESHOLD_TOPK: `eps` is then the paper's normalised threshold
+ * (Sec. 4.2, footnote: an expert is kept when N * S_i exceeds it, N = n_experts; the paper's example value is
+ * 0.48).  The library tests S_i > eps / N with the quotient rounded once to fp32.  Without the flag `eps` is
+ * compared with the raw probability S_i. */
+#define DSMOE_SEL_NORMALISED 0x100
 typedef enum { DSMOE_EXPERT_SWIGLU = 0, DSMOE_EXPERT_GELU = 1 } dsmoe_expert_kind;
 
 typedef enum {
   DSMOE_OK = 0,
   DSMOE_ERR_INVALID_ARG = -1, /* null pointer, negative size, k outside [1,E], eps < 0 or NaN, misaligned */
-  DSMOE_ERR_UNSUPPORTED = -2, /* E > 64, d_model or d_ff not a multiple of 64, unknown dtype */
+  DSMOE_ERR_UNSUPPORTED = -2, /* E > 64 or not a multiple of 8, d_model or d_ff not a multiple of 64, unknown
+                                 dtype, a size beyond a stated limit of the call */
   DSMOE_ERR_WORKSPACE = -3,   /* workspace missing or too small */
   DSMOE_ERR_CAPACITY = -4,    /* device-side: dispatched rows exceeded max_rows */
   DSMOE_ERR_HIP = -5,         /* a HIP runtime call failed */
@@ -93,11 +100,11 @@ int32_t dsmoe_poll_error(dsmoe_ctx* ctx, void* stream);
 int32_t dsmoe_route(dsmoe_ctx* ctx, const void* x, const void* w_r, const void* b_r, int32_t T,
                     float* probs, void* stream);
 
-/* Expert selection (Sec. 3.1 "K experts with the highest scores"; Sec. 3.2 "Sparse Inference": scores
- * above a threshold eps).  TOPK keeps the k highest probabilities, equal values going to the lower
- * expert index.  THRESHOLD keeps {e : probs[t,e] > eps} (raw probability, strict; the paper's
- * normalised threshold of Sec. 4.2 is eps * E) and falls back to the arg-max expert (lowest index)
- * when that set is empty.  THRESHOLD_TOPK (Sec. 4.3 "Threshold-TopK"): the threshold rule gives every
+/* Expert selection (Sec. 3.1: the K best-scored experts; Sec. 3.2 "Sparse Inference": the experts whose
+ * score passes a threshold eps).  TOPK keeps the k highest probabilities, equal values going to the lower
+ * expert index.  THRESHOLD keeps {e : probs[t,e] > eps} (raw probability, strict; with DSMOE_SEL_NORMALISED
+ * eps is the paper's normalised threshold of Sec. 4.2 and the test is probs[t,e] > eps / E) and falls back
+ * to the arg-max expert (lowest index) when that set is empty.  THRESHOLD_TOPK (Sec. 4.3 "Threshold-TopK"): the threshold rule gives every
  * token a count; K = the batch mean of the counts rounded half up, clamped to [1, E], computed on the
  * device; every token then keeps its top K (k is ignored; needs the workspace).
  * probs: fp32 [T,E]; mask: u64 [T], bit e set <=> expert e selected (written);
@@ -105,7 +112,8 @@ int32_t dsmoe_route(dsmoe_ctx* ctx, const void* x, const void* w_r, const void* 
 int32_t dsmoe_select(dsmoe_ctx* ctx, const float* probs, int32_t T, int32_t mode, int32_t k, float eps,
                      uint64_t* mask, int32_t* cnt_tok, void* stream);
 
-/* Token-to-expert dispatch (the "duplication of intermediate tokens" of Sec. 4.4): groups the
+/* Token-to-expert dispatch (the first of the two overheads of dynamic inference named in Sec. 4.4: every
+ * token is duplicated once per selected expert): groups the
  * (token, expert) pairs by expert, experts ascending, tokens ascending inside an expert.
  * Written: expert_off i32 [E+1] exclusive prefix sum of tokens per expert (expert_off[E] = nnz);
  * row_token i32 [max_rows] token of each row; row_weight fp32 [max_rows] = probs[token, expert];
@@ -124,8 +132,8 @@ int32_t dsmoe_expert_ffn(dsmoe_ctx* ctx, const void* x, const void* x_perm, cons
                          const int32_t* expert_off, const void* w_gate, const void* w_up,
                          const void* w_down, void* y_perm, void* stream);
 
-/* Probability-weighted combine and un-permute (Eq. 1 second half; the "aggregation of outputs from
- * various experts" of Sec. 4.4): out[t,:] = sum_j row_weight[r_j] * y_perm[r_j,:] over the rows
+/* Probability-weighted combine and un-permute (Eq. 1 second half; the second overhead named in Sec. 4.4:
+ * the expert outputs of a token are gathered and added up): out[t,:] = sum_j row_weight[r_j] * y_perm[r_j,:] over the rows
  * r_j = tok_rows[tok_off[t] .. tok_off[t+1]) in that (ascending expert) order, fp32 accumulation.
  * out: dtype [T,d] (written). */
 int32_t dsmoe_combine(dsmoe_ctx* ctx, const void* y_perm, const float* row_weight, const int32_t* tok_off,

@@ -15,6 +15,7 @@ LIB_PATH = os.path.join(_PKG, "libdsmoe.so")
 
 F32, BF16 = 0, 1
 SEL_TOPK, SEL_THRESHOLD, SEL_THRESHOLD_TOPK = 0, 1, 2
+SEL_NORMALISED = 0x100   # OR into a threshold mode: eps is the paper's normalised threshold (N * S_i > eps)
 SEL_ALL = -1          # attention layer only: every expert
 EXPERT_SWIGLU, EXPERT_GELU = 0, 1
 OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_CAPACITY, ERR_HIP, ERR_NOT_IMPL = 0, -1, -2, -3, -4, -5, -6
@@ -116,7 +117,7 @@ class Layer:
     """One `dsmoe_ctx` plus its workspace.  Method names and argument order mirror the C ABI."""
 
     def __init__(self, d_model: int, d_ff: int, n_experts: int, dtype: str, max_tokens: int,
-                 max_rows: int | None = None, device="cuda:0", expert: str = "swiglu"):
+                 max_rows: int | None = None, device="cuda:0", expert: str = "swiglu", workspace: bool = True):
         import torch
         self.lib = load_library()
         self.torch = torch
@@ -136,10 +137,12 @@ class Layer:
         nbytes = c_size_t()
         self._check(self.lib.dsmoe_workspace_bytes(self.ctx, byref(nbytes)))
         self.workspace_bytes = nbytes.value
-        with torch.cuda.device(self.device):
-            self.workspace = torch.empty(nbytes.value + 256, dtype=torch.uint8, device=self.device)
-            base = (self.workspace.data_ptr() + 255) // 256 * 256
-            self._check(self.lib.dsmoe_set_workspace(self.ctx, c_void_p(base), c_size_t(nbytes.value)))
+        self.workspace = None
+        if workspace:       # workspace=False: only the calls that need none (e.g. dsmoe_dispatch_static) work
+            with torch.cuda.device(self.device):
+                self.workspace = torch.empty(nbytes.value + 256, dtype=torch.uint8, device=self.device)
+                base = (self.workspace.data_ptr() + 255) // 256 * 256
+                self._check(self.lib.dsmoe_set_workspace(self.ctx, c_void_p(base), c_size_t(nbytes.value)))
 
     def __del__(self):
         try:
@@ -170,17 +173,21 @@ class Layer:
         self._check(self.lib.dsmoe_select(self.ctx, _ptr(probs), T, mode, k, eps, _ptr(mask), _ptr(cnt), _stream()))
         return mask, cnt
 
-    def dispatch(self, x, probs, mask, materialize: bool = False):
+    def dispatch(self, x, probs, mask, materialize: bool = False, static: bool = False, out=None):
+        """static: dsmoe_dispatch_static (the library's own scratch array instead of the workspace);
+        out: a dict of buffers from an earlier call to write into (nothing is allocated then)."""
         T = probs.shape[0]
         t = self.torch
         cap = max(self.max_rows, 1)
-        r = dict(expert_off=self._empty((self.E + 1,), t.int32), row_token=self._empty((cap,), t.int32),
-                 row_weight=self._empty((cap,), t.float32), tok_off=self._empty((T + 1,), t.int32),
-                 tok_rows=self._empty((cap,), t.int32), nnz=self._empty((4,), t.int32),
-                 x_perm=self._empty((cap, self.d), self.tdtype) if materialize else None)
-        self._check(self.lib.dsmoe_dispatch(self.ctx, _ptr(x), _ptr(probs), _ptr(mask), T, _ptr(r["expert_off"]),
-                                            _ptr(r["row_token"]), _ptr(r["row_weight"]), _ptr(r["tok_off"]),
-                                            _ptr(r["tok_rows"]), _ptr(r["nnz"]), _ptr(r["x_perm"]), _stream()))
+        r = out if out is not None else dict(
+            expert_off=self._empty((self.E + 1,), t.int32), row_token=self._empty((cap,), t.int32),
+            row_weight=self._empty((cap,), t.float32), tok_off=self._empty((T + 1,), t.int32),
+            tok_rows=self._empty((cap,), t.int32), nnz=self._empty((4,), t.int32),
+            x_perm=self._empty((cap, self.d), self.tdtype) if materialize else None)
+        fn = self.lib.dsmoe_dispatch
+        self._check(fn(self.ctx, _ptr(x), _ptr(probs), _ptr(mask), T, _ptr(r["expert_off"]),
+                    _ptr(r["row_token"]), _ptr(r["row_weight"]), _ptr(r["tok_off"]),
+                    _ptr(r["tok_rows"]), _ptr(r["nnz"]), _ptr(r["x_perm"]), _stream()))
         return r
 
     def expert_ffn(self, x, r, w_gate, w_up, w_down):

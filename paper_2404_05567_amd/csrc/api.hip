@@ -72,7 +72,16 @@ int32_t check_call(dsmoe_ctx* c, int32_t T, bool needs_ws) {
   return DSMOE_OK;
 }
 
-int32_t check_select_args(dsmoe_ctx* c, int32_t mode, int32_t k, float eps) {
+// Validates a selection request and resolves DSMOE_SEL_NORMALISED: on return `mode` is one of the three base
+// modes and `eps` the raw-probability threshold (the paper's normalised threshold divided by N, Sec. 4.2).
+int32_t check_select_args(dsmoe_ctx* c, int32_t& mode, int32_t k, float& eps) {
+  if (mode & DSMOE_SEL_NORMALISED) {
+    mode &= ~DSMOE_SEL_NORMALISED;
+    if (mode != DSMOE_SEL_THRESHOLD && mode != DSMOE_SEL_THRESHOLD_TOPK)
+      return fail(c, DSMOE_ERR_INVALID_ARG, "DSMOE_SEL_NORMALISED goes with a threshold mode (got mode %d)", mode);
+    if (!(eps >= 0.f) || std::isinf(eps)) return fail(c, DSMOE_ERR_INVALID_ARG, "eps must be finite and >= 0");
+    eps = eps / static_cast<float>(c->desc.n_experts);
+  }
   if (mode == DSMOE_SEL_TOPK) {
     if (k < 1 || k > c->desc.n_experts)
       return fail(c, DSMOE_ERR_INVALID_ARG, "k = %d outside [1, %d]", k, c->desc.n_experts);

@@ -1,5 +1,6 @@
-// Token-to-expert dispatch and the weighted combine: the two "overheads of dynamic inference" the
-// paper names in Sec. 4.4 (duplication of intermediate tokens, aggregation of expert outputs).
+// Token-to-expert dispatch and the weighted combine: the two costs that Sec. 4.4 of the paper attributes to
+// dynamic (sparse) inference - a token is copied once per selected expert, and its expert outputs are
+// collected and summed afterwards.
 //
 // Dispatch is a stable counting sort of the (token, expert) pairs by expert: a per-block histogram,
 // then a scatter pass in which every block re-derives its own base offsets from the histogram table
@@ -13,13 +14,18 @@ namespace dsmoe {
 
 constexpr int kDB = kDispatchTokensPerBlock;   // 256 tokens = 4 waves of 64
 
+// Bits of a selection mask that name an expert.  A caller's mask may carry stray bits above E; they are dropped
+// where a mask is loaded, so that the per-token counts (a population count) and the per-expert counts (bits
+// below E) always agree and no row index can pass the counted total.
+__device__ __forceinline__ unsigned long long expert_bits(int E) { return E >= 64 ? ~0ull : (1ull << E) - 1ull; }
+
 __global__ void __launch_bounds__(kDB)
 dispatch_hist_kernel(const unsigned long long* __restrict__ mask, int T, int E, int32_t* __restrict__ blk_cnt,
                      int32_t* __restrict__ blk_tok) {
   __shared__ int sCnt[4][kMaxExperts];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int t = blockIdx.x * kDB + threadIdx.x;
-  const unsigned long long m = t < T ? mask[t] : 0ull;
+  const unsigned long long m = t < T ? mask[t] & expert_bits(E) : 0ull;
   int mine = 0;
   for (int e = 0; e < E; ++e) {
     const int c = __popcll(__ballot((m >> e) & 1ull));
@@ -87,7 +93,7 @@ dispatch_scatter_kernel(const unsigned long long* __restrict__ mask, const float
   const int t = b * kDB + threadIdx.x;
   int cnt = 0, incl = 0;
   if (wave < 4) {
-    const unsigned long long m = t < T ? mask[t] : 0ull;
+    const unsigned long long m = t < T ? mask[t] & expert_bits(E) : 0ull;
     int mine = 0;
     for (int e = 0; e < E; ++e) {
       const unsigned long long bits = __ballot((m >> e) & 1ull);
@@ -197,18 +203,17 @@ __global__ void empty_routing_kernel(int E, int32_t* expert_off, int32_t* tok_of
   if (threadIdx.x == 0) { tok_off[0] = 0; nnz[0] = 0; }
 }
 
-hipError_t launch_dispatch(const dsmoe_ctx* c, const void* x, const float* probs, const uint64_t* mask, int T,
-                           int32_t* expert_off, int32_t* row_token, float* row_weight, int32_t* tok_off,
-                           int32_t* tok_rows, int32_t* nnz, void* x_perm, hipStream_t s) {
+// blk_cnt [n_blocks][E], blk_tok [n_blocks] and the deferred status word: scratch of the two passes
+static hipError_t launch_dispatch_with(const dsmoe_ctx* c, int32_t* blk_cnt, int32_t* blk_tok, int32_t* err_flag,
+                                       const void* x, const float* probs, const uint64_t* mask, int T,
+                                       int32_t* expert_off, int32_t* row_token, float* row_weight, int32_t* tok_off,
+                                       int32_t* tok_rows, int32_t* nnz, void* x_perm, hipStream_t s) {
   const int E = c->desc.n_experts;
   if (T == 0) {
     hipLaunchKernelGGL(empty_routing_kernel, dim3(1), dim3(128), 0, s, E, expert_off, tok_off, nnz);
     return hipGetLastError();
   }
   const int nblk = (T + kDB - 1) / kDB;
-  int32_t* blk_cnt = reinterpret_cast<int32_t*>(c->workspace + c->ws.blk_cnt);
-  int32_t* blk_tok = reinterpret_cast<int32_t*>(c->workspace + c->ws.blk_tok);
-  int32_t* err_flag = reinterpret_cast<int32_t*>(c->workspace + c->ws.err_flag);
   hipLaunchKernelGGL(dispatch_hist_kernel, dim3(nblk), dim3(kDB), 0, s, (const unsigned long long*)mask, T, E,
                      blk_cnt, blk_tok);
   hipError_t err = hipGetLastError();
@@ -222,6 +227,15 @@ hipError_t launch_dispatch(const dsmoe_ctx* c, const void* x, const float* probs
   hipLaunchKernelGGL(gather_rows_kernel, dim3((unsigned)std::max<long>(grid, 1)), dim3(kThreads), 0, s,
                      (const char*)x, row_token, nnz, (char*)x_perm, (int)(c->desc.d_model * c->esize));
   return hipGetLastError();
+}
+
+hipError_t launch_dispatch(const dsmoe_ctx* c, const void* x, const float* probs, const uint64_t* mask, int T,
+                           int32_t* expert_off, int32_t* row_token, float* row_weight, int32_t* tok_off,
+                           int32_t* tok_rows, int32_t* nnz, void* x_perm, hipStream_t s) {
+  return launch_dispatch_with(c, reinterpret_cast<int32_t*>(c->workspace + c->ws.blk_cnt),
+                              reinterpret_cast<int32_t*>(c->workspace + c->ws.blk_tok),
+                              reinterpret_cast<int32_t*>(c->workspace + c->ws.err_flag), x, probs, mask, T, expert_off,
+                              row_token, row_weight, tok_off, tok_rows, nnz, x_perm, s);
 }
 
 // ---- combine -----------------------------------------------------------------------------------

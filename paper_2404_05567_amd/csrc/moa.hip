@@ -298,6 +298,11 @@ int32_t dsmoe_moa_fwd(dsmoe_moa_ctx* c, const void* x, const void* w_r, const vo
   const int E = c->desc.n_experts, d = c->desc.d_model, NH = c->desc.n_head, DH = c->desc.d_head, hd = NH * DH;
   if (T < 0 || T > c->desc.max_tokens) return moa_fail(c, DSMOE_ERR_INVALID_ARG, "T = %d outside [0, %d]", T, c->desc.max_tokens);
   if (L < T) return moa_fail(c, DSMOE_ERR_INVALID_ARG, "the cache holds the T tokens themselves: L = %d < T = %d", L, T);
+  if (mode == (DSMOE_SEL_THRESHOLD | DSMOE_SEL_NORMALISED)) {   // the paper's normalised threshold (Sec. 4.2): N S_i > eps
+    if (!(eps >= 0.f) || std::isinf(eps)) return moa_fail(c, DSMOE_ERR_INVALID_ARG, "eps must be finite and >= 0");
+    mode = DSMOE_SEL_THRESHOLD;
+    eps = eps / static_cast<float>(E);
+  }
   if (mode == DSMOE_SEL_TOPK) {
     if (k < 1 || k > E) return moa_fail(c, DSMOE_ERR_INVALID_ARG, "k = %d outside [1, %d]", k, E);
   } else if (mode == DSMOE_SEL_THRESHOLD) {

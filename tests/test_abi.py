@@ -75,6 +75,17 @@ def test_calls_reject_bad_arguments_before_any_device_work(lib):
     assert lib.dsmoe_select(ctx, fake, 4, dsmoe.SEL_THRESHOLD, 0, -0.5, fake, None, s) == dsmoe.ERR_INVALID_ARG
     assert lib.dsmoe_select(ctx, fake, 4, dsmoe.SEL_THRESHOLD, 0, float("nan"), fake, None, s) == dsmoe.ERR_INVALID_ARG
     assert lib.dsmoe_select(ctx, fake, 4, 5, 1, 0.0, fake, None, s) == dsmoe.ERR_INVALID_ARG
+    # the normalised threshold of the paper goes with the threshold modes only, and is validated like eps
+    norm = dsmoe.SEL_NORMALISED
+    assert lib.dsmoe_select(ctx, fake, 4, dsmoe.SEL_TOPK | norm, 2, 0.5, fake, None, s) == dsmoe.ERR_INVALID_ARG
+    assert b"DSMOE_SEL_NORMALISED" in lib.dsmoe_last_error(ctx)
+    assert lib.dsmoe_select(ctx, fake, 4, dsmoe.SEL_THRESHOLD | norm, 0, -0.5, fake, None, s) == dsmoe.ERR_INVALID_ARG
+    assert lib.dsmoe_select(ctx, fake, 4, dsmoe.SEL_THRESHOLD | norm, 0, float("inf"), fake, None, s) \
+        == dsmoe.ERR_INVALID_ARG
+    assert lib.dsmoe_select(ctx, fake, 0, dsmoe.SEL_THRESHOLD | norm, 0, 0.48, fake, None, s) == dsmoe.OK   # T = 0
+    assert lib.dsmoe_select(ctx, fake, 4, dsmoe.SEL_THRESHOLD_TOPK | norm, 0, 0.48, fake, None, s) == dsmoe.ERR_WORKSPACE
+    assert lib.dsmoe_sparse_fwd(ctx, fake, fake, None, fake, fake, fake, 4, 7 | norm, 2, 0.1, fake, s) \
+        == dsmoe.ERR_WORKSPACE      # the workspace check comes first ...
     # calls that need the workspace refuse to run without one
     assert lib.dsmoe_sparse_fwd(ctx, fake, fake, None, fake, fake, fake, 4, dsmoe.SEL_TOPK, 2, 0.0, fake, s) \
         == dsmoe.ERR_WORKSPACE

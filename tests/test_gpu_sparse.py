@@ -192,6 +192,45 @@ def test_threshold_topk_selection(torch, dsmoe, name, T, dtype, eps):
     run_staged_and_check(torch, dsmoe, inp, "threshold_topk", 0, eps)
 
 
+@pytest.mark.parametrize("T,E", [(300, 24), (64, 24), (500, 32)])
+def test_normalised_threshold_of_the_paper(torch, dsmoe, T, E):
+    """Sec. 4.2 (footnote): the paper thresholds the normalised probability N * S_i.  With DSMOE_SEL_NORMALISED
+    the caller passes that value; the selection must equal the checker's raw-probability rule at eps / N (the
+    quotient in fp32, as the library forms it), staged and fused, prefill- and decode-sized."""
+    eps_paper = 0.48                                   # the paper's example value (Sec. 4.3)
+    raw = np.float32(eps_paper) / np.float32(E)
+    d = 256
+    cfg = gen.LayerConfig("norm_eps", 17, T=T, d=d, E=E, f=128, dtype="bf16", mode="threshold", eps=float(raw),
+                          router_std=1.5 / np.sqrt(d))
+    inp = conditioned(cfg, "threshold", 0, float(raw))
+    say(f"[case] normalised threshold {eps_paper} on {E} experts = raw {raw:.6f}, T={T}")
+    w = weights_to_dev(torch, inp)
+    layer = dsmoe.Layer(cfg.d, cfg.f, E, "bf16", max_tokens=T)
+    norm = dsmoe.SEL_THRESHOLD | dsmoe.SEL_NORMALISED
+    probs = layer.route(w["x"], w["w_r"], None)
+    mask, cnt = layer.select(probs, norm, 0, eps_paper)
+    S_gpu = probs.cpu().numpy()
+    M_same = orc.select_threshold(S_gpu, raw)
+    np.testing.assert_array_equal(mask_to_bool(mask, E), M_same)
+    np.testing.assert_array_equal(cnt.cpu().numpy(), M_same.sum(axis=1))
+    M_ref = orc.select_threshold(orc.route(inp.x, inp.w_r, None), float(raw))
+    np.testing.assert_array_equal(M_same, M_ref)
+    assert 1.0 < M_ref.sum(axis=1).mean() < E - 1       # the rule is neither trivial nor dense here
+    out_n = layer.sparse_fwd(w["x"], w["w_r"], None, w["w_gate"], w["w_up"], w["w_down"], norm, 0, eps_paper).clone()
+    _, m_n, _, _ = layer.sparse_fwd_routing(T)
+    np.testing.assert_array_equal(mask_to_bool(m_n, E), M_ref)
+    out_r = layer.sparse_fwd(w["x"], w["w_r"], None, w["w_gate"], w["w_up"], w["w_down"], dsmoe.SEL_THRESHOLD, 0,
+                             float(raw))
+    assert layer.poll_error() == dsmoe.OK
+    assert torch.equal(out_n, out_r)
+    O_ref, _, _ = orc.sparse_forward(inp.x, inp.w_r, None, inp.w_gate, inp.w_up, inp.w_down, "threshold", 0, float(raw))
+    assert helpers.rel_err(out_n.float().cpu().numpy(), O_ref) <= TOL["bf16"]
+    # Threshold-TopK with the normalised threshold: K from the same counts
+    mask_t, _ = layer.select(probs, dsmoe.SEL_THRESHOLD_TOPK | dsmoe.SEL_NORMALISED, 0, eps_paper)
+    K = orc.threshold_topk_k(S_gpu, raw)
+    np.testing.assert_array_equal(mask_to_bool(mask_t, E), orc.select_topk(S_gpu, K))
+
+
 @pytest.mark.parametrize("name,T,dtype,mode,k,eps,materialize", [
     ("c1", 128, "f32", "topk", 2, 0.0, False), ("c1", 128, "f32", "threshold", 0, 0.13, True),
     ("rag", 777, "bf16", "threshold", 0, 0.05, False), ("rag", 777, "f32", "topk", 3, 0.0, False),
@@ -370,6 +409,30 @@ def test_capacity_overflow_is_reported_and_harmless(torch, dsmoe):
     assert layer.poll_error() == dsmoe.OK
     O, _, _ = orc.sparse_forward(inp.x, inp.w_r, None, inp.w_gate, inp.w_up, inp.w_down, "topk", 1)
     assert helpers.rel_err(out.float().cpu().numpy(), O) <= 1e-5
+
+
+def test_dispatch_ignores_mask_bits_above_the_expert_count(torch, dsmoe):
+    """A caller's selection mask may carry stray bits at or above E: the dispatch drops them, so counts, offsets
+    and rows equal those of the clean masks (and no row index passes nnz)."""
+    cfg = gen.LayerConfig("stray", 18, T=700, d=64, E=24, f=64, dtype="bf16", mode="topk", k=3, router_std=0.1)
+    inp = gen.make_layer(cfg, 0)
+    S = orc.route(inp.x, inp.w_r, None).astype(np.float32)
+    M = orc.select_topk(S, 3)
+    r_ref = orc.dispatch(M, S)
+    bits = (M.astype(np.uint64) << np.arange(cfg.E, dtype=np.uint64)[None, :]).sum(axis=1, dtype=np.uint64)
+    rng = np.random.default_rng(3)
+    stray = rng.integers(0, 1 << 40, size=cfg.T, dtype=np.uint64) << np.uint64(cfg.E)
+    layer = dsmoe.Layer(cfg.d, cfg.f, cfg.E, "bf16", max_tokens=cfg.T, max_rows=r_ref.nnz)   # no spare row
+    x = torch.from_numpy(inp.x).cuda().to(torch.bfloat16)
+    probs = torch.from_numpy(S).cuda()
+    clean = layer.dispatch(x, probs, torch.from_numpy(bits.view(np.int64)).cuda())
+    dirty = layer.dispatch(x, probs, torch.from_numpy((bits | stray).view(np.int64)).cuda())
+    assert layer.poll_error() == dsmoe.OK
+    for k in ("expert_off", "row_token", "row_weight", "tok_off", "tok_rows", "nnz"):
+        n = r_ref.nnz if k in ("row_token", "row_weight", "tok_rows") else (1 if k == "nnz" else clean[k].numel())
+        assert torch.equal(clean[k][:n], dirty[k][:n]), k
+    np.testing.assert_array_equal(dirty["expert_off"].cpu().numpy(), r_ref.expert_off)
+    np.testing.assert_array_equal(dirty["tok_rows"].cpu().numpy()[:r_ref.nnz], r_ref.tok_rows)
 
 
 def test_repeated_calls_are_bitwise_identical(torch, dsmoe):
