@@ -124,6 +124,21 @@ int32_t dsmoe_dispatch(dsmoe_ctx* ctx, const void* x, const float* probs, const 
                        int32_t* expert_off, int32_t* row_token, float* row_weight, int32_t* tok_off,
                        int32_t* tok_rows, int32_t* nnz, void* x_perm, void* stream);
 
+/* dsmoe_dispatch for callers that cannot allocate device memory or lend a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, results and error behaviour
+ * as dsmoe_dispatch, but no workspace is needed: the scratch of its kernels (per-block expert histograms,
+ * about 65 KB, and the deferred status word) is a device array inside the library, which every GPU the
+ * library runs on holds until the process ends.  The call allocates nothing and frees nothing.
+ * Limits: T <= DSMOE_STATIC_DISPATCH_MAX_TOKENS (beyond it: DSMOE_ERR_UNSUPPORTED, nothing enqueued).
+ * All calls on one GPU share that GPU's array, whatever their context or stream: calls that overlap in time
+ * on one GPU race and must be serialised by the caller.  Nothing in the array has to start at zero (every
+ * histogram entry a call reads it has written first); the status word is set only by a capacity overflow
+ * and cleared by dsmoe_poll_error, which also reports it (and needs no workspace for that). */
+#define DSMOE_STATIC_DISPATCH_MAX_TOKENS 65536
+int32_t dsmoe_dispatch_static(dsmoe_ctx* ctx, const void* x, const float* probs, const uint64_t* mask,
+                              int32_t T, int32_t* expert_off, int32_t* row_token, float* row_weight,
+                              int32_t* tok_off, int32_t* tok_rows, int32_t* nnz, void* x_perm, void* stream);
+
 /* Per-expert SwiGLU FFN on the dispatched rows (the e_i(X) of Eq. 1):
  * y_perm[r,:] = e_{expert(r)}(x[row_token[r],:]) for r < expert_off[E].
  * Rows are read from x_perm when it is non-NULL, otherwise gathered from x through row_token.

@@ -23,7 +23,8 @@ OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_CAPACITY, ERR_HIP, ERR_
 EXPORTS = [
     "dsmoe_create", "dsmoe_destroy", "dsmoe_last_error", "dsmoe_set_expert_kind", "dsmoe_workspace_bytes",
     "dsmoe_set_workspace",
-    "dsmoe_poll_error", "dsmoe_route", "dsmoe_select", "dsmoe_dispatch", "dsmoe_expert_ffn", "dsmoe_combine",
+    "dsmoe_poll_error", "dsmoe_route", "dsmoe_select", "dsmoe_dispatch", "dsmoe_dispatch_static", "dsmoe_expert_ffn",
+    "dsmoe_combine",
     "dsmoe_sparse_fwd", "dsmoe_sparse_fwd_routing", "dsmoe_dense_saved_bytes", "dsmoe_dense_fwd",
     "dsmoe_dense_bwd_scratch_bytes", "dsmoe_dense_bwd", "dsmoe_mi_loss", "dsmoe_dense_bwd_mi",
     "dsmoe_profile_enable", "dsmoe_profile_read",
@@ -72,6 +73,7 @@ def load_library() -> ctypes.CDLL:
         "dsmoe_route": (c_int32, [P, P, P, P, c_int32, P, P]),
         "dsmoe_select": (c_int32, [P, P, c_int32, c_int32, c_int32, c_float, P, P, P]),
         "dsmoe_dispatch": (c_int32, [P, P, P, P, c_int32, P, P, P, P, P, P, P, P]),
+        "dsmoe_dispatch_static": (c_int32, [P, P, P, P, c_int32, P, P, P, P, P, P, P, P]),
         "dsmoe_expert_ffn": (c_int32, [P] * 10),
         "dsmoe_combine": (c_int32, [P, P, P, P, P, c_int32, P, P]),
         "dsmoe_sparse_fwd": (c_int32, [P, P, P, P, P, P, P, c_int32, c_int32, c_int32, c_float, P, P]),
@@ -184,7 +186,7 @@ class Layer:
             row_weight=self._empty((cap,), t.float32), tok_off=self._empty((T + 1,), t.int32),
             tok_rows=self._empty((cap,), t.int32), nnz=self._empty((4,), t.int32),
             x_perm=self._empty((cap, self.d), self.tdtype) if materialize else None)
-        fn = self.lib.dsmoe_dispatch
+        fn = self.lib.dsmoe_dispatch_static if static else self.lib.dsmoe_dispatch
         self._check(fn(self.ctx, _ptr(x), _ptr(probs), _ptr(mask), T, _ptr(r["expert_off"]),
                     _ptr(r["row_token"]), _ptr(r["row_weight"]), _ptr(r["tok_off"]),
                     _ptr(r["tok_rows"]), _ptr(r["nnz"]), _ptr(r["x_perm"]), _stream()))

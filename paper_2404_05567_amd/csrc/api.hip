@@ -234,16 +234,26 @@ int32_t dsmoe_set_workspace(dsmoe_ctx* c, void* dptr, size_t bytes) {
 
 int32_t dsmoe_poll_error(dsmoe_ctx* c, void* stream) {
   if (!c) return DSMOE_ERR_INVALID_ARG;
-  if (!c->workspace) return fail(c, DSMOE_ERR_WORKSPACE, "no workspace set");
+  // two deferred status words: the workspace's, and the one of dsmoe_dispatch_static once it has run on this device
+  int32_t* flags[2] = {nullptr, nullptr};
+  if (c->workspace) flags[0] = reinterpret_cast<int32_t*>(c->workspace + c->ws.err_flag);
+  HIP_TRY(c, static_dispatch_flag(&flags[1]));
+  if (!flags[0] && !flags[1]) return fail(c, DSMOE_ERR_WORKSPACE, "no workspace set");
   hipStream_t s = static_cast<hipStream_t>(stream);
-  int32_t flag = 0;
-  HIP_TRY(c, hipMemcpyAsync(&flag, c->workspace + c->ws.err_flag, 4, hipMemcpyDeviceToHost, s));
-  HIP_TRY(c, hipStreamSynchronize(s));
-  if (flag != 0) {
-    HIP_TRY(c, hipMemsetAsync(c->workspace + c->ws.err_flag, 0, 4, s));
+  int32_t status = DSMOE_OK;
+  for (int32_t* dflag : flags) {
+    if (!dflag) continue;
+    int32_t flag = 0;
+    HIP_TRY(c, hipMemcpyAsync(&flag, dflag, 4, hipMemcpyDeviceToHost, s));
     HIP_TRY(c, hipStreamSynchronize(s));
-    return fail(c, flag, "dispatched rows exceeded max_rows = %lld", (long long)c->desc.max_rows);
+    if (flag != 0) {
+      HIP_TRY(c, hipMemsetAsync(dflag, 0, 4, s));
+      HIP_TRY(c, hipStreamSynchronize(s));
+      status = flag;
+    }
   }
+  if (status != DSMOE_OK)
+    return fail(c, status, "dispatched rows exceeded max_rows = %lld", (long long)c->desc.max_rows);
   return DSMOE_OK;
 }
 

@@ -19,6 +19,7 @@ typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 constexpr int kMaxExperts = 64;
 constexpr int kDispatchTokensPerBlock = 256;  // tokens handled by one block of the dispatch kernels
 constexpr int kDecodeMaxTokens = 128;         // largest batch served by the weight-streaming (decode) path
+constexpr int kStaticDispatchMaxTokens = DSMOE_STATIC_DISPATCH_MAX_TOKENS;   // largest T of dsmoe_dispatch_static
 
 // Workspace carve-up (byte offsets into the caller's buffer).
 struct WorkspaceLayout {
@@ -104,6 +105,9 @@ hipError_t launch_down_dense(const dsmoe_ctx* c, const void* h, int T, int k_tot
                              hipStream_t s);
 hipError_t launch_shared_rows_gemm(const dsmoe_ctx* c, const void* x, int groups, int rows, int k, int n,
                                    const void* w, void* out, hipStream_t s);
+// address of the deferred status word of dsmoe_dispatch_static on the current device; null while that entry
+// point has not run there
+hipError_t static_dispatch_flag(int32_t** flag);
 // dispatch.hip (combine)
 hipError_t launch_combine(const dsmoe_ctx* c, const void* y_perm, const float* row_weight,
                           const int32_t* tok_off, const int32_t* tok_rows, int T, void* out, hipStream_t s);

@@ -7,6 +7,8 @@
 // (a few KB) instead of waiting for a separate scan kernel.  Ranks inside a block come from wave
 // ballots, so the order (experts ascending, tokens ascending inside an expert) is deterministic.
 #include <algorithm>
+#include <cstdio>
+#include <mutex>
 
 #include "gemm_core.h"
 
@@ -237,6 +239,87 @@ hipError_t launch_dispatch(const dsmoe_ctx* c, const void* x, const float* probs
                               reinterpret_cast<int32_t*>(c->workspace + c->ws.err_flag), x, probs, mask, T, expert_off,
                               row_token, row_weight, tok_off, tok_rows, nnz, x_perm, s);
 }
+
+// ---- dispatch for callers that cannot allocate ------------------------------------------------------
+// The scratch of the two passes (per-block histograms, the deferred status word) lives in a device array of
+// the library instead of a caller-lent workspace.  Every GPU holds its own copy of the array at its own
+// address; host code never uses the array's name as an address, only what hipGetSymbolAddress returned for
+// the device that was current.
+constexpr int kStaticBlocks = kStaticDispatchMaxTokens / kDB;
+constexpr size_t kStaticFlagOff = 0;                                        // int32 [4]
+constexpr size_t kStaticCntOff = 256;                                       // int32 [kStaticBlocks][kMaxExperts]
+constexpr size_t kStaticTokOff = kStaticCntOff + (size_t)kStaticBlocks * kMaxExperts * 4;   // int32 [kStaticBlocks]
+constexpr size_t kStaticBytes = (kStaticTokOff + (size_t)kStaticBlocks * 4 + 255) / 256 * 256;
+static __device__ __align__(256) unsigned char scratch[kStaticBytes];
+
+constexpr int kMaxDevices = 64;
+static std::mutex g_scratch_mu;
+static char* g_scratch_ptr[kMaxDevices];   // address of `scratch` on each device, once asked for
+
+// Address of the current device's copy of the array (asked for once per device, with that device current).
+static hipError_t static_scratch(char** out, bool create) {
+  int dev = -1;
+  if (hipError_t e = hipGetDevice(&dev)) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(g_scratch_mu);
+  if (!g_scratch_ptr[dev] && create) {
+    void* p = nullptr;
+    if (hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch))) return e;
+    g_scratch_ptr[dev] = static_cast<char*>(p);
+  }
+  *out = g_scratch_ptr[dev];
+  return hipSuccess;
+}
+
+hipError_t static_dispatch_flag(int32_t** flag) {
+  char* p = nullptr;
+  if (hipError_t e = static_scratch(&p, false)) return e;
+  *flag = p ? reinterpret_cast<int32_t*>(p + kStaticFlagOff) : nullptr;
+  return hipSuccess;
+}
+
+}  // namespace dsmoe
+
+extern "C" int32_t dsmoe_dispatch_static(dsmoe_ctx* c, const void* x, const float* probs, const uint64_t* mask,
+                                         int32_t T, int32_t* expert_off, int32_t* row_token, float* row_weight,
+                                         int32_t* tok_off, int32_t* tok_rows, int32_t* nnz, void* x_perm,
+                                         void* stream) {
+  using namespace dsmoe;
+  if (!c) return DSMOE_ERR_INVALID_ARG;
+  auto fail = [&](int32_t code, const char* msg) {
+    snprintf(c->err, sizeof(c->err), "dsmoe_dispatch_static: %s", msg);
+    return code;
+  };
+  if (T < 0 || T > c->desc.max_tokens) return fail(DSMOE_ERR_INVALID_ARG, "T outside [0, max_tokens]");
+  if (T > kStaticDispatchMaxTokens)
+    return fail(DSMOE_ERR_UNSUPPORTED, "T exceeds DSMOE_STATIC_DISPATCH_MAX_TOKENS (the library's own scratch array "
+                                       "holds histograms for that many tokens); use dsmoe_dispatch with a workspace");
+  auto bad = [](const void* p, bool required) {
+    return (required && p == nullptr) || (reinterpret_cast<uintptr_t>(p) & 15u) != 0;
+  };
+  if (bad(expert_off, true) || bad(tok_off, true) || bad(nnz, true))
+    return fail(DSMOE_ERR_INVALID_ARG, "expert_off, tok_off and nnz must be non-null and 16-byte aligned");
+  if (T > 0 && (bad(probs, true) || bad(mask, true) || bad(row_token, true) || bad(row_weight, true) ||
+                bad(tok_rows, true) || bad(x_perm, false) || (x_perm && bad(x, true))))
+    return fail(DSMOE_ERR_INVALID_ARG, "null or misaligned pointer");
+  char* base = nullptr;
+  if (hipError_t e = static_scratch(&base, true)) {
+    snprintf(c->err, sizeof(c->err), "dsmoe_dispatch_static: hipGetSymbolAddress: %s", hipGetErrorString(e));
+    return DSMOE_ERR_HIP;
+  }
+  hipError_t e = launch_dispatch_with(c, reinterpret_cast<int32_t*>(base + kStaticCntOff),
+                                      reinterpret_cast<int32_t*>(base + kStaticTokOff),
+                                      reinterpret_cast<int32_t*>(base + kStaticFlagOff), x, probs, mask, T, expert_off,
+                                      row_token, row_weight, tok_off, tok_rows, nnz, x_perm,
+                                      static_cast<hipStream_t>(stream));
+  if (e != hipSuccess) {
+    snprintf(c->err, sizeof(c->err), "dsmoe_dispatch_static: launch: %s", hipGetErrorString(e));
+    return DSMOE_ERR_HIP;
+  }
+  return DSMOE_OK;
+}
+
+namespace dsmoe {
 
 // ---- combine -----------------------------------------------------------------------------------
 // out[t,:] = sum over the token's rows (ascending expert) of row_weight * y_perm[row,:], fp32 accumulate.

@@ -101,6 +101,20 @@ def test_calls_reject_bad_arguments_before_any_device_work(lib):
     bad_alpha = ct.c_float(float("inf"))
     assert lib.dsmoe_dense_bwd_mi(ctx, fake, fake, fake, fake, fake, fake, fake, 4, fake, fake, fake, None, fake, fake,
                                   fake, bad_alpha, s) == dsmoe.ERR_INVALID_ARG
+    # the dispatch that needs no workspace: arguments and its size limit are checked before any device work
+    st = lambda **kw: lib.dsmoe_dispatch_static(ctx, fake, kw.get("probs", fake), fake, kw.get("T", 4), fake, fake, fake,
+                                                kw.get("tok_off", fake), fake, fake, None, s)
+    assert st(T=-1) == dsmoe.ERR_INVALID_ARG
+    assert st(T=129) == dsmoe.ERR_INVALID_ARG                 # beyond the context's max_tokens
+    assert st(probs=None) == dsmoe.ERR_INVALID_ARG
+    assert st(tok_off=odd) == dsmoe.ERR_INVALID_ARG
+    assert b"dsmoe_dispatch_static" in lib.dsmoe_last_error(ctx)
+    rc_big, big = make(lib, max_tokens=1 << 17, max_rows=16)
+    assert rc_big == dsmoe.OK
+    assert lib.dsmoe_dispatch_static(big, fake, fake, fake, (1 << 16) + 1, fake, fake, fake, fake, fake, fake, None, s) \
+        == dsmoe.ERR_UNSUPPORTED
+    assert b"DSMOE_STATIC_DISPATCH_MAX_TOKENS" in lib.dsmoe_last_error(big)
+    assert lib.dsmoe_destroy(big) == dsmoe.OK
     assert lib.dsmoe_set_workspace(ctx, None, 1 << 20) == dsmoe.ERR_INVALID_ARG
     assert lib.dsmoe_set_workspace(ctx, c_void_p(0x1010), 1 << 30) == dsmoe.ERR_INVALID_ARG
     assert lib.dsmoe_set_workspace(ctx, fake, 16) == dsmoe.ERR_WORKSPACE
