@@ -212,6 +212,19 @@ int32_t dsmoe_profile_enable(dsmoe_ctx* ctx, int32_t max_calls);
 int32_t dsmoe_profile_read(dsmoe_ctx* ctx, int32_t* n_calls /* host */, float* gateup_ms /* host */,
                            float* down_ms /* host */);
 
+/* Measured ceilings for benchmarks (not part of the layer; each call synchronises `stream`).
+ * dsmoe_bench_mfma: `blocks` blocks of eight waves run `iters` x 8 independent 32x32x16 bf16 MFMAs per wave on
+ *   register operands taken from `seed` (device, 16 KiB: zeros or random bf16 values - the sustained clock
+ *   depends on the bits that toggle); `sink`: device, blocks * 2 KiB.  Returns milliseconds and the flop count.
+ * dsmoe_bench_stream: `blocks` blocks read (write = 0) or write (write = 1) the window [window, window + bytes)
+ *   once with 16-byte accesses; `moved` receives the bytes actually touched.  `sink`: device, >= 4 bytes.
+ * dsmoe_bench_xcc_ids: out[b] (device int32 [blocks]) = hardware id of the XCD that ran block b of a launch. */
+int32_t dsmoe_bench_mfma(const void* seed, void* sink, int32_t blocks, int32_t iters, float* ms /* host */,
+                         double* flop /* host */, void* stream);
+int32_t dsmoe_bench_stream(void* window, size_t bytes, int32_t write, int32_t blocks, void* sink,
+                           float* ms /* host */, size_t* moved /* host */, void* stream);
+int32_t dsmoe_bench_xcc_ids(int32_t* out, int32_t blocks, void* stream);
+
 /* ---- Mixture-of-Attention-heads layer (Sec. 3.2, "Mixture of Attention Head", Eq. 7-8) -------------
  * Forward only, bf16 only.  E experts; expert i has a query projection W_q[i] and an output projection
  * W_o[i]; the n_head key/value heads of the cache are shared by all experts (grouped-query attention:

@@ -27,7 +27,7 @@ EXPORTS = [
     "dsmoe_combine",
     "dsmoe_sparse_fwd", "dsmoe_sparse_fwd_routing", "dsmoe_dense_saved_bytes", "dsmoe_dense_fwd",
     "dsmoe_dense_bwd_scratch_bytes", "dsmoe_dense_bwd", "dsmoe_mi_loss", "dsmoe_dense_bwd_mi",
-    "dsmoe_profile_enable", "dsmoe_profile_read",
+    "dsmoe_profile_enable", "dsmoe_profile_read", "dsmoe_bench_mfma", "dsmoe_bench_stream", "dsmoe_bench_xcc_ids",
     "dsmoe_moa_create", "dsmoe_moa_destroy", "dsmoe_moa_last_error", "dsmoe_moa_workspace_bytes",
     "dsmoe_moa_set_workspace", "dsmoe_moa_fwd", "dsmoe_moa_routing",
 ]
@@ -86,6 +86,9 @@ def load_library() -> ctypes.CDLL:
         "dsmoe_dense_bwd_mi": (c_int32, [P, P, P, P, P, P, P, P, c_int32, P, P, P, P, P, P, P, c_float, P]),
         "dsmoe_profile_enable": (c_int32, [P, c_int32]),
         "dsmoe_profile_read": (c_int32, [P, POINTER(c_int32), POINTER(c_float), POINTER(c_float)]),
+        "dsmoe_bench_mfma": (c_int32, [P, P, c_int32, c_int32, POINTER(c_float), POINTER(ctypes.c_double), P]),
+        "dsmoe_bench_stream": (c_int32, [P, c_size_t, c_int32, c_int32, P, POINTER(c_float), POINTER(c_size_t), P]),
+        "dsmoe_bench_xcc_ids": (c_int32, [P, c_int32, P]),
         "dsmoe_moa_create": (c_int32, [POINTER(MoaDesc), POINTER(c_void_p)]),
         "dsmoe_moa_destroy": (c_int32, [P]),
         "dsmoe_moa_last_error": (c_char_p, [P]),
@@ -113,6 +116,44 @@ def _ptr(t):
 def _stream():
     import torch
     return c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def bench_mfma(random_operands: bool, blocks: int = 1024, iters: int = 20000):
+    """TFLOP/s of a bare bf16 MFMA loop (dsmoe_bench_mfma) on zero or random register operands."""
+    import torch
+    lib = load_library()
+    seed = (torch.randn(8192, device="cuda:0") if random_operands else torch.zeros(8192, device="cuda:0")).to(torch.bfloat16)
+    sink = torch.empty(blocks * 512, dtype=torch.float32, device="cuda:0")
+    ms, flop = c_float(), ctypes.c_double()
+    rc = lib.dsmoe_bench_mfma(_ptr(seed), _ptr(sink), blocks, iters, byref(ms), byref(flop), _stream())
+    if rc != OK:
+        raise DsmoeError(rc, "dsmoe_bench_mfma")
+    return flop.value / (ms.value * 1e-3) / 1e12
+
+
+def bench_stream(buf, offset: int, nbytes: int, write: bool, blocks: int = 2048):
+    """GB/s of one streaming pass (dsmoe_bench_stream) over bytes [offset, offset + nbytes) of the uint8 tensor buf."""
+    import torch
+    lib = load_library()
+    sink = torch.zeros(4, dtype=torch.float32, device=buf.device)
+    ms, moved = c_float(), c_size_t()
+    rc = lib.dsmoe_bench_stream(c_void_p(buf.data_ptr() + offset), c_size_t(nbytes), int(write), blocks, _ptr(sink),
+                                byref(ms), byref(moved), _stream())
+    if rc != OK:
+        raise DsmoeError(rc, "dsmoe_bench_stream")
+    return moved.value / (ms.value * 1e-3) / 1e9
+
+
+def xcc_ids(blocks: int = 256):
+    """Hardware XCD id of every block of a `blocks`-block launch (torch int32 tensor on the host)."""
+    import torch
+    lib = load_library()
+    out = torch.full((blocks,), -1, dtype=torch.int32, device="cuda:0")
+    rc = lib.dsmoe_bench_xcc_ids(_ptr(out), blocks, _stream())
+    if rc != OK:
+        raise DsmoeError(rc, "dsmoe_bench_xcc_ids")
+    torch.cuda.synchronize()
+    return out.cpu()
 
 
 class Layer:

@@ -16,6 +16,10 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 
+// Hardware id of the XCD (accelerator complex die, each with its own L2) the calling wave runs on: bits 3:0 of
+// the XCC_ID hardware register (register 20).
+__device__ __forceinline__ unsigned xcc_id() { return __builtin_amdgcn_s_getreg((3 << 11) | 20) & 15u; }
+
 constexpr int kMaxExperts = 64;
 constexpr int kDispatchTokensPerBlock = 256;  // tokens handled by one block of the dispatch kernels
 constexpr int kDecodeMaxTokens = 128;         // largest batch served by the weight-streaming (decode) path
