@@ -271,7 +271,8 @@ class Bench:
                     _, _, eo, _ = layer.sparse_fwd_routing(T)
                     eo = eo.cpu().numpy()
                     union.append(int(((eo[1:] - eo[:-1]) > 0).sum()))
-                assert layer.poll_error() == dsmoe.OK
+                rc = layer.poll_error()
+                assert rc == dsmoe.OK, f"deferred status {rc} at T={T} {mode_name}: {layer.lib.dsmoe_last_error(layer.ctx).decode()}"
                 mean_union = sum(union) / len(union)
                 bytes_per_call = mean_union * 3 * d * f * 2 + d * E * 2 + 2 * T * d * 2
                 ms_eager = self.timed(sweep, steps, warmup) / n_sets

@@ -58,7 +58,9 @@ typedef enum {
   DSMOE_ERR_WORKSPACE = -3,   /* workspace missing or too small */
   DSMOE_ERR_CAPACITY = -4,    /* device-side: dispatched rows exceeded max_rows */
   DSMOE_ERR_HIP = -5,         /* a HIP runtime call failed */
-  DSMOE_ERR_NOT_IMPL = -6
+  DSMOE_ERR_NOT_IMPL = -6,
+  DSMOE_ERR_INTERNAL = -7     /* device-side: blocks of a kernel that cooperate through one XCD's L2 did not run
+                                 where expected, or a bounded wait between blocks gave up; output undefined */
 } dsmoe_status;
 
 /* Layer description (host struct). max_tokens bounds T of every call; max_rows bounds the number of
@@ -82,6 +84,12 @@ const char* dsmoe_last_error(const dsmoe_ctx* ctx);
  * GeLU g * Phi(g); W_1 is passed as w_gate, W_2 as w_down; w_up and, in the backward pass, dw_up are
  * ignored (may be NULL).  Applies to every call that evaluates experts. */
 int32_t dsmoe_set_expert_kind(dsmoe_ctx* ctx, int32_t kind);
+
+/* Decode-sized dsmoe_sparse_fwd calls may run as one persistent kernel whose blocks hand results to each other;
+ * a block polls at most `polls` times (default 2^20, roughly a second) for its peers before it gives up and
+ * raises DSMOE_ERR_INTERNAL through dsmoe_poll_error.  Every wait is bounded: the kernel always ends.
+ * polls = 0 makes every such wait give up at once (for tests of the error path). */
+int32_t dsmoe_set_sync_spin_limit(dsmoe_ctx* ctx, int32_t polls);
 
 /* Scratch memory the library needs (intermediate H = silu(G)*U rows, block histograms, the routing
  * objects and permuted outputs of dsmoe_sparse_fwd).  The caller allocates `bytes` of device memory,
@@ -162,7 +170,8 @@ int32_t dsmoe_sparse_fwd(dsmoe_ctx* ctx, const void* x, const void* w_r, const v
                          int32_t mode, int32_t k, float eps, void* out, void* stream);
 
 /* Copies the routing objects of the last dsmoe_sparse_fwd out of the workspace (any argument may be
- * NULL): probs fp32 [T,E], mask u64 [T], expert_off i32 [E+1], row_token i32 [max_rows]. */
+ * NULL; after a decode-sized call whose kernels need no dispatch, the dispatch objects are derived here, on
+ * `stream`, from the scores and masks that call left): probs fp32 [T,E], mask u64 [T], expert_off i32 [E+1], row_token i32 [max_rows]. */
 int32_t dsmoe_sparse_fwd_routing(dsmoe_ctx* ctx, int32_t T, float* probs, uint64_t* mask,
                                  int32_t* expert_off, int32_t* row_token, void* stream);
 

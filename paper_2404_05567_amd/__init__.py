@@ -19,10 +19,11 @@ SEL_NORMALISED = 0x100   # OR into a threshold mode: eps is the paper's normalis
 SEL_ALL = -1          # attention layer only: every expert
 EXPERT_SWIGLU, EXPERT_GELU = 0, 1
 OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_CAPACITY, ERR_HIP, ERR_NOT_IMPL = 0, -1, -2, -3, -4, -5, -6
+ERR_INTERNAL = -7
 
 EXPORTS = [
     "dsmoe_create", "dsmoe_destroy", "dsmoe_last_error", "dsmoe_set_expert_kind", "dsmoe_workspace_bytes",
-    "dsmoe_set_workspace",
+    "dsmoe_set_workspace", "dsmoe_set_sync_spin_limit",
     "dsmoe_poll_error", "dsmoe_route", "dsmoe_select", "dsmoe_dispatch", "dsmoe_dispatch_static", "dsmoe_expert_ffn",
     "dsmoe_combine",
     "dsmoe_sparse_fwd", "dsmoe_sparse_fwd_routing", "dsmoe_dense_saved_bytes", "dsmoe_dense_fwd",
@@ -69,6 +70,7 @@ def load_library() -> ctypes.CDLL:
         "dsmoe_set_expert_kind": (c_int32, [P, c_int32]),
         "dsmoe_workspace_bytes": (c_int32, [P, POINTER(c_size_t)]),
         "dsmoe_set_workspace": (c_int32, [P, P, c_size_t]),
+        "dsmoe_set_sync_spin_limit": (c_int32, [P, c_int32]),
         "dsmoe_poll_error": (c_int32, [P, P]),
         "dsmoe_route": (c_int32, [P, P, P, P, c_int32, P, P]),
         "dsmoe_select": (c_int32, [P, P, c_int32, c_int32, c_int32, c_float, P, P, P]),
@@ -273,6 +275,9 @@ class Layer:
         n, a, b = c_int32(), c_float(), c_float()
         self._check(self.lib.dsmoe_profile_read(self.ctx, byref(n), byref(a), byref(b)))
         return n.value, a.value, b.value
+
+    def set_sync_spin_limit(self, polls: int):
+        self._check(self.lib.dsmoe_set_sync_spin_limit(self.ctx, polls))
 
     def poll_error(self) -> int:
         return self.lib.dsmoe_poll_error(self.ctx, _stream())

@@ -58,8 +58,17 @@ WorkspaceLayout make_layout(const dsmoe_desc& d, size_t esize) {
   w.dec_arrivals = take(decode_arrival_slots(d) * 4);
   w.dec_p1 = take(dec_rows * 2 * d.d_ff * 4);
   w.dec_p2 = take(dec_rows * d.d_model * 4);
+  w.dec_ht = take((d.dtype == DSMOE_BF16 ? (size_t)std::min<int64_t>(d.max_tokens, kDecodeMaxTokens) : 0) * E * d.d_ff * 2);
+  w.dec_sync = take(kDenseSyncTotalWords * 4);
   w.total = o;
   return w;
+}
+
+// counters of the all-expert decode kernel at zero, its publication words at "not yet published"
+hipError_t reset_dense_sync(dsmoe_ctx* c, hipStream_t s) {
+  char* base = c->workspace + c->ws.dec_sync;
+  if (hipError_t e = hipMemsetAsync(base, 0, (size_t)kDensePubWeight * 4, s)) return e;
+  return hipMemsetAsync(base + (size_t)kDensePubWeight * 4, 0xff, (size_t)128 * 64 * 4, s);
 }
 
 // checks shared by every call that enqueues work
@@ -139,6 +148,8 @@ int32_t dsmoe_create(const dsmoe_desc* desc, dsmoe_ctx** out) {
   c->workspace_bytes = 0;
   c->err[0] = 0;
   c->expert_kind = DSMOE_EXPERT_SWIGLU;
+  c->spin_limit = kDefaultSpinLimit;
+  c->routing_pending_T = -1;
   c->n_cu = 256;
   int dev = 0;
   hipDeviceProp_t prop;
@@ -210,6 +221,17 @@ int32_t dsmoe_set_expert_kind(dsmoe_ctx* c, int32_t kind) {
   return DSMOE_OK;
 }
 
+int32_t dsmoe_set_sync_spin_limit(dsmoe_ctx* c, int32_t polls) {
+  if (!c) return DSMOE_ERR_INVALID_ARG;
+  if (polls < 0) return fail(c, DSMOE_ERR_INVALID_ARG, "polls must be >= 0");
+  c->spin_limit = polls;
+  return DSMOE_OK;
+}
+
+#ifdef DSMOE_TRACE
+size_t dsmoe_trace_offset(const dsmoe_ctx* c) { return c->ws.dec_p1; }   // development builds only
+#endif
+
 int32_t dsmoe_workspace_bytes(const dsmoe_ctx* ctx, size_t* bytes) {
   if (!ctx || !bytes) return DSMOE_ERR_INVALID_ARG;
   *bytes = ctx->ws.total;
@@ -228,6 +250,8 @@ int32_t dsmoe_set_workspace(dsmoe_ctx* c, void* dptr, size_t bytes) {
   HIP_TRY(c, hipMemsetAsync(c->workspace + c->ws.err_flag, 0, 16, nullptr));
   // arrival counters of the weight-streaming path: every call leaves them at zero again
   HIP_TRY(c, hipMemsetAsync(c->workspace + c->ws.dec_arrivals, 0, decode_arrival_slots(c->desc) * 4, nullptr));
+  HIP_TRY(c, reset_dense_sync(c, nullptr));
+  c->routing_pending_T = -1;
   HIP_TRY(c, hipStreamSynchronize(nullptr));
   return DSMOE_OK;
 }
@@ -241,6 +265,7 @@ int32_t dsmoe_poll_error(dsmoe_ctx* c, void* stream) {
   if (!flags[0] && !flags[1]) return fail(c, DSMOE_ERR_WORKSPACE, "no workspace set");
   hipStream_t s = static_cast<hipStream_t>(stream);
   int32_t status = DSMOE_OK;
+  int32_t diag[kDenseDiagWords] = {0};
   for (int32_t* dflag : flags) {
     if (!dflag) continue;
     int32_t flag = 0;
@@ -248,10 +273,21 @@ int32_t dsmoe_poll_error(dsmoe_ctx* c, void* stream) {
     HIP_TRY(c, hipStreamSynchronize(s));
     if (flag != 0) {
       HIP_TRY(c, hipMemsetAsync(dflag, 0, 4, s));
+      if (flag == DSMOE_ERR_INTERNAL && dflag == flags[0]) {   // a wait between blocks gave up: counters may be off
+        HIP_TRY(c, hipMemcpyAsync(diag, c->workspace + c->ws.dec_sync + kDenseSyncWords * 4, sizeof(diag),
+                                  hipMemcpyDeviceToHost, s));
+        HIP_TRY(c, hipStreamSynchronize(s));
+        HIP_TRY(c, reset_dense_sync(c, s));
+      }
       HIP_TRY(c, hipStreamSynchronize(s));
       status = flag;
     }
   }
+  if (status == DSMOE_ERR_INTERNAL)
+    return fail(c, status, "decode kernel: %s (block %d, XCD %d, counter %d read %d, wanted %d); the call's output "
+                           "is undefined", diag[0] == 3 ? "an XCD did not run all of its work items"
+                                                        : "a block gave up waiting for its peers",
+                diag[1], diag[2], diag[3], diag[4], diag[5]);
   if (status != DSMOE_OK)
     return fail(c, status, "dispatched rows exceeded max_rows = %lld", (long long)c->desc.max_rows);
   return DSMOE_OK;
@@ -353,6 +389,13 @@ int32_t dsmoe_sparse_fwd(dsmoe_ctx* c, const void* x, const void* w_r, const voi
   int32_t* tok_rows = reinterpret_cast<int32_t*>(w + c->ws.tok_rows);
   int32_t* nnz = reinterpret_cast<int32_t*>(w + c->ws.nnz);
   void* y_perm = w + c->ws.y_perm;
+  c->routing_pending_T = -1;
+  if (decode_dense_applies(c, T, mode, k, eps)) {
+    // decode-sized batch that selects nearly every expert: one persistent kernel, router included
+    HIP_TRY(c, launch_decode_dense(c, x, w_r, b_r, w_gate, w_up, w_down, T, mode, k, eps, out, s));
+    c->routing_pending_T = T;
+    return DSMOE_OK;
+  }
   if (mode == DSMOE_SEL_THRESHOLD_TOPK) {
     int32_t* k_dev = reinterpret_cast<int32_t*>(w + c->ws.k_dev);
     HIP_TRY(c, launch_route(c, x, w_r, b_r, T, probs, DSMOE_SEL_THRESHOLD, 0, eps, mask, cnt_tok, s));
@@ -380,6 +423,17 @@ int32_t dsmoe_sparse_fwd_routing(dsmoe_ctx* c, int32_t T, float* probs, uint64_t
   hipStream_t s = static_cast<hipStream_t>(stream);
   const size_t E = (size_t)c->desc.n_experts;
   char* w = c->workspace;
+  if (c->routing_pending_T >= 0) {
+    // the last forward kept only scores and masks (its kernels need no dispatch): derive the rest now
+    const int Tp = c->routing_pending_T;
+    HIP_TRY(c, launch_dispatch(c, nullptr, reinterpret_cast<const float*>(w + c->ws.probs),
+                               reinterpret_cast<const uint64_t*>(w + c->ws.mask), Tp,
+                               reinterpret_cast<int32_t*>(w + c->ws.expert_off), reinterpret_cast<int32_t*>(w + c->ws.row_token),
+                               reinterpret_cast<float*>(w + c->ws.row_weight), reinterpret_cast<int32_t*>(w + c->ws.tok_off),
+                               reinterpret_cast<int32_t*>(w + c->ws.tok_rows), reinterpret_cast<int32_t*>(w + c->ws.nnz),
+                               nullptr, s));
+    c->routing_pending_T = -1;
+  }
   if (probs && T) HIP_TRY(c, hipMemcpyAsync(probs, w + c->ws.probs, (size_t)T * E * 4, hipMemcpyDeviceToDevice, s));
   if (mask && T) HIP_TRY(c, hipMemcpyAsync(mask, w + c->ws.mask, (size_t)T * 8, hipMemcpyDeviceToDevice, s));
   if (expert_off) HIP_TRY(c, hipMemcpyAsync(expert_off, w + c->ws.expert_off, (E + 1) * 4, hipMemcpyDeviceToDevice, s));

@@ -21,6 +21,21 @@ typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 __device__ __forceinline__ unsigned xcc_id() { return __builtin_amdgcn_s_getreg((3 << 11) | 20) & 15u; }
 
 constexpr int kMaxExperts = 64;
+// counters of the all-expert decode kernel (decode_dense.hip)
+constexpr int kDenseSyncFinished = 1;     // blocks that have finished
+constexpr int kDenseClaimWords = 32;      // bitmap words per XCD and phase: at most 1024 items
+constexpr int kDenseSyncClaim1 = 16;                                        // + 32 XCD: claimed first-phase items
+constexpr int kDenseSyncClaim2 = kDenseSyncClaim1 + 8 * kDenseClaimWords;   // + 32 XCD: claimed second-phase items
+constexpr int kDenseSyncDone1 = kDenseSyncClaim2 + 8 * kDenseClaimWords;    // + 32 XCD: first-phase items whose hidden
+                                                                            // columns are in the XCD's L2
+constexpr int kDenseSyncDone2 = kDenseSyncDone1 + 8 * kDenseClaimWords;     // + 32 XCD: finished second-phase items
+constexpr int kDenseSyncWords = kDenseSyncDone2 + 8 * kDenseClaimWords;
+// behind the counters and the diagnostics: what the in-kernel router publishes for the other blocks
+constexpr int kDensePubCount = kDenseSyncWords + 8;                      // i32 [128]: selected experts of a token (0: not yet)
+constexpr int kDensePubWeight = kDensePubCount + 128;                    // u32 [128][64]: combine weights (all ones: not yet)
+constexpr int kDenseSyncTotalWords = kDensePubWeight + 128 * 64;
+constexpr int kDenseDiagWords = 8;        // behind the counters: what the first failing block saw (reason, block, ...)
+constexpr int kDefaultSpinLimit = 1 << 20;   // polls before a block gives up waiting for its peers
 constexpr int kDispatchTokensPerBlock = 256;  // tokens handled by one block of the dispatch kernels
 constexpr int kDecodeMaxTokens = 128;         // largest batch served by the weight-streaming (decode) path
 constexpr int kStaticDispatchMaxTokens = DSMOE_STATIC_DISPATCH_MAX_TOKENS;   // largest T of dsmoe_dispatch_static
@@ -49,6 +64,8 @@ struct WorkspaceLayout {
   size_t dec_arrivals;   // i32 [decode_arrival_slots]: blocks that have finished a shared result; zero between calls
   size_t dec_p1;      // f32 [decode_row_cap][2 f]      K-chunk partial sums of gate | up
   size_t dec_p2;      // f32 [decode_row_cap][d]        K-chunk partial sums of the down projection
+  size_t dec_ht;      // bf16 [min(max_tokens, 128)][E f]   weighted hidden activations of the all-expert decode kernel
+  size_t dec_sync;    // i32 [kDenseSyncWords]: counters of the all-expert decode kernel; zero between calls
   size_t total;
 };
 
@@ -68,6 +85,9 @@ struct dsmoe_ctx {
   size_t workspace_bytes;
   int n_cu;
   int expert_kind;   // DSMOE_EXPERT_SWIGLU or DSMOE_EXPERT_GELU
+  int spin_limit;    // polls a block of the all-expert decode kernel waits for its peers
+  int routing_pending_T;   // >= 0: the last dsmoe_sparse_fwd (of that many tokens) left scores and masks only;
+                           // dsmoe_sparse_fwd_routing derives the dispatch objects from them on demand
   char err[256];
 };
 
@@ -119,6 +139,12 @@ hipError_t launch_combine(const dsmoe_ctx* c, const void* y_perm, const float* r
 // probabilities and masks the router left in the workspace; also publishes the routing objects there
 hipError_t launch_decode_fwd(const dsmoe_ctx* c, const void* x, const void* w_gate, const void* w_up,
                              const void* w_down, int T, void* out, hipStream_t s);
+// decode_dense.hip: the whole sparse forward (router included) for decode-sized batches that select nearly
+// every expert; leaves scores and masks in the workspace
+bool decode_dense_applies(const dsmoe_ctx* c, int T, int mode, int k, float eps);
+hipError_t launch_decode_dense(const dsmoe_ctx* c, const void* x, const void* w_r, const void* b_r, const void* w_gate,
+                               const void* w_up, const void* w_down, int T, int mode, int k, float eps, void* out,
+                               hipStream_t s);
 // dense.hip
 size_t dense_saved_bytes(const dsmoe_ctx* c, int T);
 size_t dense_bwd_scratch_bytes(const dsmoe_ctx* c, int T);

@@ -49,7 +49,7 @@ struct Gemm;
 #define DSMOE_GEMM_STAGES(GM, st)                                                                            \
   extern __shared__ __align__(16) char dsmoe_dyn_smem[];                                                     \
   DSMOE_STAGE_ARRAYS(st, 4, GM::ST_L, GM::ST_R);                                                             \
-  (void)st##L4; (void)st##L5; (void)st##R4; (void)st##R5; /* placeholders of the four-stage form */          \
+  (void)st##L4; (void)st##L5; (void)st##R4; (void)st##R5; (void)st##L6; (void)st##L7; (void)st##R6; (void)st##R7;          \
   typename GM::Stages st =                                                                                   \
       GM::make_stages(st##L0, st##L1, st##L2, st##L3, st##R0, st##R1, st##R2, st##R3, dsmoe_dyn_smem)
 
@@ -206,7 +206,7 @@ struct Gemm<bf16_t, BM_, BN_, NSRC_, LK, RK, KTAIL> {
     Stages s;
     s.l[0] = (lds_char*)l0; s.l[1] = (lds_char*)l1; s.l[2] = (lds_char*)l2; s.l[3] = (lds_char*)l3;
     s.r[0] = (lds_char*)r0; s.r[1] = (lds_char*)r1; s.r[2] = (lds_char*)r2; s.r[3] = (lds_char*)r3;
-    s.l[4] = s.l[5] = s.r[4] = s.r[5] = nullptr;
+    s.l[4] = s.l[5] = s.r[4] = s.r[5] = s.l[6] = s.l[7] = s.r[6] = s.r[7] = nullptr;
     return s;
   }
 

@@ -61,7 +61,7 @@ struct Interleave {
 };
 
 
-constexpr int kMaxStages3 = 6;   // LDS stages a kernel may use (Tile3's NST: 4 for the MFMA-bound kernels, 6 for streaming)
+constexpr int kMaxStages3 = 8;   // LDS stages a kernel may use (Tile3's NST: 4 for the MFMA-bound kernels, 6 or 8 for streaming)
 
 typedef __attribute__((address_space(1))) const void gvoid_t;
 typedef __attribute__((address_space(3))) void lvoid_t;
@@ -237,16 +237,18 @@ struct DCols {
 struct Stages3 { lds_char* l[kMaxStages3]; lds_char* r[kMaxStages3]; };
 #define DSMOE_STAGE_ARRAYS(st, NST, LB, RB)                                                                  \
   __shared__ __align__(1024) char st##L0[LB], st##L1[LB], st##L2[LB], st##L3[LB], st##L4[(NST) > 4 ? (LB) : 16],  \
-      st##L5[(NST) > 5 ? (LB) : 16];                                                                         \
+      st##L5[(NST) > 5 ? (LB) : 16], st##L6[(NST) > 6 ? (LB) : 16], st##L7[(NST) > 7 ? (LB) : 16];           \
   __shared__ __align__(1024) char st##R0[RB], st##R1[RB], st##R2[RB], st##R3[RB], st##R4[(NST) > 4 ? (RB) : 16],  \
-      st##R5[(NST) > 5 ? (RB) : 16]
+      st##R5[(NST) > 5 ? (RB) : 16], st##R6[(NST) > 6 ? (RB) : 16], st##R7[(NST) > 7 ? (RB) : 16]
 #define DSMOE_TILE3_STAGES(TL, st)                                                                           \
   DSMOE_STAGE_ARRAYS(st, TL::NST, TL::LDS_L, TL::LDS_R);                                                     \
   dsmoe::Stages3 st;                                                                                         \
   st.l[0] = (dsmoe::lds_char*)st##L0; st.l[1] = (dsmoe::lds_char*)st##L1; st.l[2] = (dsmoe::lds_char*)st##L2; \
   st.l[3] = (dsmoe::lds_char*)st##L3; st.l[4] = (dsmoe::lds_char*)st##L4; st.l[5] = (dsmoe::lds_char*)st##L5; \
+  st.l[6] = (dsmoe::lds_char*)st##L6; st.l[7] = (dsmoe::lds_char*)st##L7;                                    \
   st.r[0] = (dsmoe::lds_char*)st##R0; st.r[1] = (dsmoe::lds_char*)st##R1; st.r[2] = (dsmoe::lds_char*)st##R2; \
-  st.r[3] = (dsmoe::lds_char*)st##R3; st.r[4] = (dsmoe::lds_char*)st##R4; st.r[5] = (dsmoe::lds_char*)st##R5
+  st.r[3] = (dsmoe::lds_char*)st##R3; st.r[4] = (dsmoe::lds_char*)st##R4; st.r[5] = (dsmoe::lds_char*)st##R5; \
+  st.r[6] = (dsmoe::lds_char*)st##R6; st.r[7] = (dsmoe::lds_char*)st##R7
 
 // NSRC = 2: the wave's two column tiles are the same 32 columns of source 0 (gate) and source 1 (up).
 // The block's eight waves form a WGM x WGN grid over the tile (WGN_ = 4 or 2).
@@ -254,7 +256,7 @@ template <int BM_, int BN_, int NSRC_ = 1, bool L_KMAJOR = false, bool R_KMAJOR 
           int WGN_ = 4>
 struct Tile3 {
   static constexpr int BM = BM_, BN = BN_, NSRC = NSRC_, BK = kBK2, WGN = WGN_, WGM = 8 / WGN_, NST = NST_;
-  static_assert(NST >= 4 && NST <= kMaxStages3, "four to six stages");
+  static_assert(NST >= 4 && NST <= kMaxStages3, "four to eight stages");
   static constexpr int WM = BM / WGM, WN = BN / WGN;
   static constexpr int MT = WM / 32, NT = WN / 32;
   static_assert(NSRC == 1 || NT == NSRC, "one column tile per source");

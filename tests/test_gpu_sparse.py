@@ -393,6 +393,43 @@ def test_weight_streaming_path_overflow_and_repeatability(torch, dsmoe):
     assert helpers.rel_err(outs[0].float().cpu().numpy(), O) <= TOL["bf16"]
 
 
+def test_all_expert_decode_kernel_alternating_inputs_and_bounded_waits(torch, dsmoe):
+    """The persistent decode kernel (T = 32 .. 128 tokens that select nearly every expert) hands results between
+    blocks through counters that each call must leave reset: alternate two different inputs and two batch sizes
+    many times on one context and require bitwise the results of the first round; then make every wait between
+    blocks give up at once (spin limit 0): the kernel must still end, the deferred status must say so, and the
+    next call must be right again."""
+    cfg = gen.CONFIGS["c3"].with_(T=128)
+    a = conditioned(cfg, "topk", 4, 0.0, variant=1)
+    b = conditioned(cfg.with_(T=40), "threshold", 0, 0.02, variant=2)
+    wa, wb = weights_to_dev(torch, a), weights_to_dev(torch, b)
+    layer = dsmoe.Layer(cfg.d, cfg.f, cfg.E, cfg.dtype, max_tokens=128)
+    call_a = lambda: layer.sparse_fwd(wa["x"], wa["w_r"], None, wa["w_gate"], wa["w_up"], wa["w_down"], dsmoe.SEL_TOPK, 4, 0.0)
+    call_b = lambda: layer.sparse_fwd(wb["x"], wb["w_r"], None, wb["w_gate"], wb["w_up"], wb["w_down"],
+                                      dsmoe.SEL_THRESHOLD, 0, 0.02)
+    ref_a, ref_b = call_a().clone(), call_b().clone()
+    assert layer.poll_error() == dsmoe.OK
+    Oa, _, _ = orc.sparse_forward(a.x, a.w_r, None, a.w_gate, a.w_up, a.w_down, "topk", 4)
+    Ob, _, _ = orc.sparse_forward(b.x, b.w_r, None, b.w_gate, b.w_up, b.w_down, "threshold", 0, 0.02)
+    assert helpers.rel_err(ref_a.float().cpu().numpy(), Oa) <= TOL["bf16"]
+    assert helpers.rel_err(ref_b.float().cpu().numpy(), Ob) <= TOL["bf16"]
+    for i in range(40):                                   # back to back, no synchronisation in between
+        oa, ob = call_a(), call_b()
+        if i % 8 == 7:
+            assert torch.equal(oa, ref_a) and torch.equal(ob, ref_b), i
+    assert torch.equal(oa, ref_a) and torch.equal(ob, ref_b)
+    assert layer.poll_error() == dsmoe.OK
+    # every wait gives up at once: the call ends, is reported, and leaves the context usable
+    layer.set_sync_spin_limit(0)
+    call_a()
+    torch.cuda.synchronize()
+    assert layer.poll_error() == dsmoe.ERR_INTERNAL
+    assert b"gave up" in layer.lib.dsmoe_last_error(layer.ctx)
+    layer.set_sync_spin_limit(1 << 20)
+    assert torch.equal(call_a(), ref_a)
+    assert layer.poll_error() == dsmoe.OK
+
+
 def test_capacity_overflow_is_reported_and_harmless(torch, dsmoe):
     cfg = gen.CONFIGS["c1"]
     inp = gen.make_layer(cfg, 0)
