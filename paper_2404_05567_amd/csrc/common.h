@@ -22,7 +22,6 @@ __device__ __forceinline__ unsigned xcc_id() { return __builtin_amdgcn_s_getreg(
 
 constexpr int kMaxExperts = 64;
 // counters of the all-expert decode kernel (decode_dense.hip)
-constexpr int kDenseSyncFinished = 1;     // blocks that have finished
 constexpr int kDenseClaimWords = 32;      // bitmap words per XCD and phase: at most 1024 items
 constexpr int kDenseSyncClaim1 = 16;                                        // + 32 XCD: claimed first-phase items
 constexpr int kDenseSyncClaim2 = kDenseSyncClaim1 + 8 * kDenseClaimWords;   // + 32 XCD: claimed second-phase items

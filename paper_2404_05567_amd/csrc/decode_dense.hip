@@ -378,28 +378,24 @@ __global__ void __launch_bounds__(kThreads2) decode_dense_kernel(const DenseDeco
   }
   DSMOE_MARK(11);
 
-  // The block that finishes last checks that every XCD ran all its items (an XCD that received no block at all
-  // would have run none) and leaves every counter at zero and every publication word unset for the next call.
-  __syncthreads();
-  if (threadIdx.x == 0)
-    sItem[0] = __hip_atomic_fetch_add(a.sync + kDenseSyncFinished, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  __syncthreads();
-  if (sItem[0] == (int)gridDim.x - 1) {
-    if (threadIdx.x < 8 && !ItemClaims::none_unclaimed(a.sync + kDenseSyncDone2 + threadIdx.x * kDenseClaimWords, items2))
-      raise_internal(a.sync, a.err_flag, 3, kDenseSyncDone2 + threadIdx.x * kDenseClaimWords, 0, items2);
-    __syncthreads();
-    for (int i = threadIdx.x; i < kDenseSyncWords; i += kThreads2)
-      __hip_atomic_store(a.sync + i, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    for (int i = threadIdx.x; i < T; i += kThreads2)
-      __hip_atomic_store(cpub + i, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    for (int i = threadIdx.x; i < T * kMaxExperts; i += kThreads2)
-      __hip_atomic_store(wpub + i, kNotPublished, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  }
 }
 
-// out[t, :] = sum of the K-range partial outputs in ascending order (fixed: bitwise reproducible)
+// out[t, :] = sum of the K-range partial outputs in ascending order (fixed: bitwise reproducible).  The kernel
+// also closes the call of the persistent kernel before it: it checks that every XCD ran all its second-phase
+// items (an XCD that received no block at all would have run none) and leaves every counter at zero and every
+// publication word unset for the next call.
 __global__ void __launch_bounds__(256) decode_dense_reduce_kernel(const float* __restrict__ part, int nparts, int T, int d,
-                                                                  bf16_t* __restrict__ out) {
+                                                                  bf16_t* __restrict__ out, int32_t* __restrict__ sync,
+                                                                  int32_t* __restrict__ err_flag, int items2) {
+  const int bid = blockIdx.y * gridDim.x + blockIdx.x, nb = gridDim.x * gridDim.y;
+  if (bid == 0 && threadIdx.x < 8 &&
+      !ItemClaims::none_unclaimed(sync + kDenseSyncDone2 + threadIdx.x * kDenseClaimWords, items2))
+    raise_internal(sync, err_flag, 3, kDenseSyncDone2 + threadIdx.x * kDenseClaimWords, 0, items2);
+  __syncthreads();
+  unsigned* wpub = reinterpret_cast<unsigned*>(sync + kDensePubWeight);
+  for (int i = bid * 256 + threadIdx.x; i < kDenseSyncWords; i += nb * 256) sync[i] = 0;
+  for (int i = bid * 256 + threadIdx.x; i < T; i += nb * 256) sync[kDensePubCount + i] = 0;
+  for (int i = bid * 256 + threadIdx.x; i < T * kMaxExperts; i += nb * 256) wpub[i] = kNotPublished;
   const int t = blockIdx.x, c0 = (blockIdx.y * 256 + threadIdx.x) * 4;
   if (c0 >= d) return;
   const float* p = part + (size_t)t * d + c0;
@@ -477,7 +473,8 @@ hipError_t launch_decode_dense(const dsmoe_ctx* c, const void* x, const void* w_
     else decode_dense_kernel<false, 64><<<dim3(grid), dim3(kThreads2), 0, s>>>(a);
   }
   if (hipError_t e = hipGetLastError()) return e;
-  decode_dense_reduce_kernel<<<dim3(T, (a.d + 1023) / 1024), dim3(256), 0, s>>>(a.part, 8 * a.KS, T, a.d, (bf16_t*)out);
+  decode_dense_reduce_kernel<<<dim3(T, (a.d + 1023) / 1024), dim3(256), 0, s>>>(
+      a.part, 8 * a.KS, T, a.d, (bf16_t*)out, a.sync, a.err_flag, (a.d + 127) / 128 * a.KS);
   return hipGetLastError();
 }
 
