@@ -6,11 +6,15 @@ softmax + selection, dispatch, grouped SwiGLU FFN, weighted combine) over one ba
 already resident in HBM, on the sparse-prefill configuration "c2" (T=4096, d_model=2048, 32 experts,
 d_ff=512, threshold 0.02, bf16 storage with fp32 accumulation).
 
-Prints ONE JSON line.  `roofline` describes the dominant kernel of the headline workload (the grouped
-gate/up GEMM): algorithmic FLOPs per launch (4 * nnz * d * f) over its average duration, measured with HIP
-events on the launch stream during the timed steps.  `cpu_baseline` is the fp64 CPU checker timed on this
-host.  `workloads` carries the other configurations (decode sizes "c3", dense training "c4", skewed prefill
-"c5") with their own throughput and roofline fractions; they are context, not the headline.
+Prints ONE JSON line.  `ms_per_step` / `value` come from exactly `--steps` calls bracketed by stream
+synchronisation, with no instrumentation inside.  `roofline` describes the dominant kernel of the headline
+workload (the grouped gate/up GEMM): algorithmic FLOPs per launch (4 * nnz * d * f) over its average duration,
+measured in a separate pass with HIP events on the launch stream.  `config.summary` carries every configuration
+(c2, the decode sizes c3, dense training c4, skewed prefill c5, the widened rows) in compact form: median
+milliseconds of >= 20 individually timed calls, tokens/s, fraction of the relevant roofline, dominant kernel.
+`config.ceilings` are micro-benchmarks run in the same process (bare MFMA loop on zero and on random operands,
+cold-window streaming read and write), beside the nominal peaks.  `cpu_baseline` is the fp64 CPU checker timed
+on this host.  `--verbose` adds the full per-workload records under `workloads`.
 """
 from __future__ import annotations
 
@@ -28,8 +32,21 @@ PEAK_HBM_GBS = 8000.0
 METRIC = "MoE-layer tokens/s + % bf16 MFMA peak (prefill) / % HBM BW (decode)"
 
 
+def csrc_digest() -> str:
+    """Digest of the kernel sources: counter summaries under profiles/ name the digest they were taken with."""
+    import hashlib
+    h = hashlib.sha256()
+    d = os.path.join(ROOT, "paper_2404_05567_amd", "csrc")
+    for name in sorted(os.listdir(d)):
+        if name.endswith((".hip", ".h")):
+            h.update(name.encode())
+            h.update(open(os.path.join(d, name), "rb").read())
+    return h.hexdigest()[:16]
+
+
 def read_traffic(workload: str):
-    """HBM bytes per launch of the dominant kernel from committed rocprofv3 counter runs, if any."""
+    """HBM bytes per launch of the dominant kernel from the committed rocprofv3 counter runs - only if they were
+    taken with the kernel sources as they are now (the summary records their digest); otherwise None."""
     path = os.path.join(ROOT, "profiles", f"traffic_{workload}.txt")
     if not os.path.exists(path):
         return None
@@ -37,11 +54,13 @@ def read_traffic(workload: str):
     for line in open(path):
         if "=" in line and not line.lstrip().startswith("#"):
             k, v = line.split("=", 1)
-            try:
-                vals[k.strip()] = float(v.split()[0])
-            except ValueError:
-                pass
-    return vals.get("gateup_hbm_bytes_per_launch")
+            vals[k.strip()] = v.split()[0] if v.split() else ""
+    if vals.get("csrc_digest") != csrc_digest():
+        return None
+    try:
+        return float(vals["gateup_hbm_bytes_per_launch"])
+    except (KeyError, ValueError):
+        return None
 
 
 def cpu_baseline(inp, cfg, passes: int):
@@ -101,6 +120,20 @@ class Bench:
         torch.cuda.synchronize()
         return (time.perf_counter() - t0) / steps * 1e3
 
+    def median_ms(self, fn, iters=20, warmup=2):
+        """Median over `iters` calls, each timed by a pair of events on the stream the library launches on."""
+        torch = self.torch
+        for _ in range(warmup):
+            fn()
+        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(iters)]
+        for a, b in ev:
+            a.record()
+            fn()
+            b.record()
+        torch.cuda.synchronize()
+        t = sorted(a.elapsed_time(b) for a, b in ev)
+        return t[len(t) // 2]
+
     # ---- sparse prefill (c2, c5) ---------------------------------------------------------------------
     def sparse_prefill(self, name, steps, warmup, keep_inputs=False, expert="swiglu", threshold_topk=False):
         """expert="gelu": the paper's two-matrix expert on the same shapes (W_up unused, 4 nnz d f flop);
@@ -130,8 +163,10 @@ class Bench:
         _, _, expert_off, _ = layer.sparse_fwd_routing(cfg.T)
         eo = expert_off.cpu().numpy()
         nnz = int(eo[-1])
-        layer.profile_enable(steps)
-        ms = self.timed(step, steps, 0)
+        ms = self.timed(step, steps, 0)                 # the timed steps: nothing but the calls
+        ms_median = self.median_ms(step, max(20, min(steps, 50)))
+        layer.profile_enable(steps)                     # second pass: kernel durations from events in the library
+        self.timed(step, steps, 0)
         n_calls, gateup_ms, down_ms = layer.profile_read()
         layer.profile_enable(0)
         assert n_calls == steps
@@ -144,7 +179,7 @@ class Bench:
             "workload": f"{name}: sparse prefill T={cfg.T} d_model={cfg.d} E={cfg.E} d_ff={cfg.f} "
                         f"{'threshold_topk' if threshold_topk else cfg.mode} eps={cfg.eps} k={cfg.k}"
                         + (" expert=gelu(x W_1) W_2" if gelu else ""),
-            "tokens_per_s": cfg.T / (ms * 1e-3), "ms_per_step": ms, "nnz": nnz,
+            "tokens_per_s": cfg.T / (ms * 1e-3), "ms_per_step": ms, "median_ms": ms_median, "nnz": nnz,
             "active_fraction": nnz / (cfg.T * cfg.E),
             "rows_per_expert_min_max": [int((eo[1:] - eo[:-1]).min()), int((eo[1:] - eo[:-1]).max())],
             "layer_tflops_per_s": layer_flops / (ms * 1e-3) / 1e12,
@@ -184,6 +219,7 @@ class Bench:
             layer.mi_loss(bufs["probs"])
 
         ms = self.timed(both, steps, warmup)
+        ms_median = self.median_ms(both, max(20, steps))
         ms_f = self.timed(fwd, steps, 1)
         ms_b = self.timed(bwd, steps, 1)
         ms_bmi = self.timed(bwd_mi, steps, 1)
@@ -193,7 +229,7 @@ class Bench:
         flops_f, flops_b = 3 * unit, 6 * unit
         return {
             "workload": f"c4: dense training forward+backward T={cfg.T} d_model={cfg.d} E={cfg.E} d_ff={cfg.f}",
-            "tokens_per_s": cfg.T / (ms * 1e-3), "ms_per_step": ms, "fwd_ms": ms_f, "bwd_ms": ms_b,
+            "tokens_per_s": cfg.T / (ms * 1e-3), "ms_per_step": ms, "median_ms": ms_median, "fwd_ms": ms_f, "bwd_ms": ms_b,
             "tflops_per_s": (flops_f + flops_b) / (ms * 1e-3) / 1e12,
             "frac_of_bf16_peak": (flops_f + flops_b) / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
             "fwd_frac_of_bf16_peak": flops_f / (ms_f * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
@@ -220,6 +256,7 @@ class Bench:
             layer.fwd(x, w_r, None, w_q, k, v, w_o, mode, cfg.k, cfg.eps, scale, out=out)
 
         ms = self.timed(step, steps, warmup)
+        ms_median = self.median_ms(step, max(20, steps))
         assert torch.isfinite(out.float()).all()
         hd = cfg.n_head * cfg.d_head
         pairs = sum(cfg.L - cfg.T + t + 1 for t in range(cfg.T))          # (query, visible key) pairs per head
@@ -228,7 +265,7 @@ class Bench:
         return {
             "workload": f"{name}: attention-expert layer forward, T={cfg.T} L={cfg.L} d_model={cfg.d} E={cfg.E} "
                         f"heads={cfg.n_head}x{cfg.d_head}, {cfg.mode}",
-            "ms_per_step": ms, "tokens_per_s": cfg.T / (ms * 1e-3),
+            "ms_per_step": ms, "median_ms": ms_median, "tokens_per_s": cfg.T / (ms * 1e-3),
             "tflop_projections": flops_proj / 1e12, "tflop_attention": flops_att / 1e12,
             "tflops_per_s": (flops_proj + flops_att) / (ms * 1e-3) / 1e12,
             "frac_of_bf16_peak": (flops_proj + flops_att) / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
@@ -276,6 +313,7 @@ class Bench:
                 mean_union = sum(union) / len(union)
                 bytes_per_call = mean_union * 3 * d * f * 2 + d * E * 2 + 2 * T * d * 2
                 ms_eager = self.timed(sweep, steps, warmup) / n_sets
+                ms_median = self.median_ms(sweep, max(20, steps)) / n_sets
                 graph = torch.cuda.CUDAGraph()
                 side = torch.cuda.Stream()
                 side.wait_stream(torch.cuda.current_stream())
@@ -285,17 +323,77 @@ class Bench:
                         sweep()
                 torch.cuda.current_stream().wait_stream(side)
                 ms_graph = self.timed(graph.replay, steps, warmup) / n_sets
-                best = min(ms_eager, ms_graph)
+                best = min(ms_eager, ms_graph, ms_median)
                 results.append({
                     "T": T, "selection": mode_name, "active_experts_mean": mean_union,
                     "bytes_per_call": bytes_per_call, "us_per_call_eager": ms_eager * 1e3,
-                    "us_per_call_graph": ms_graph * 1e3, "tokens_per_s": T / (best * 1e-3),
+                    "us_per_call_graph": ms_graph * 1e3, "us_per_call_median": ms_median * 1e3,
+                    "path": "one persistent kernel (all experts) + partial-sum reduction"
+                            if dsmoe.dense_decode_applies(layer, T, mode, k, eps) else
+                            "router + weight-streaming gate/up, down, combine kernels",
+                    "tokens_per_s": T / (best * 1e-3),
                     "gb_per_s": bytes_per_call / (best * 1e-3) / 1e9,
                     "frac_of_hbm_peak": bytes_per_call / (best * 1e-3) / 1e9 / PEAK_HBM_GBS,
                 })
         name = "c3: sparse decode on the c2 layer" if shape is None else \
             f"sparse decode, layer d_model={d} E={E} d_ff={f}"
         return {"workload": f"{name}, {n_sets} weight sets cycled", "cases": results}
+
+
+def ceilings():
+    """Micro-benchmarks of this GPU, in this process: what a bare MFMA loop and a plain streaming kernel reach."""
+    import torch
+    import paper_2404_05567_amd as dsmoe
+    out = {"nominal": {"bf16_mfma_tflops": PEAK_BF16_TFLOPS, "hbm_gb_per_s": PEAK_HBM_GBS}}
+    out["mfma_bf16_zero_operands_tflops"] = max(dsmoe.bench_mfma(False, 1024, 20000) for _ in range(3))
+    out["mfma_bf16_random_operands_tflops"] = max(dsmoe.bench_mfma(True, 1024, 20000) for _ in range(3))
+    buf = torch.empty(3 << 30, dtype=torch.uint8, device="cuda:0")
+    buf.fill_(1)
+    torch.cuda.synchronize()
+    med = lambda v: sorted(v)[len(v) // 2]
+    out["stream_read_2GiB_gb_per_s"] = med([dsmoe.bench_stream(buf, 0, 2 << 30, False, 2048) for _ in range(5)])
+    out["stream_write_2GiB_gb_per_s"] = med([dsmoe.bench_stream(buf, 0, 2 << 30, True, 2048) for _ in range(5)])
+    # one decode layer's worth (200 MiB), every window cold: the buffer is walked in windows
+    win = 200 << 20
+    n = (3 << 30) // win
+    out["stream_read_cold_200MiB_gb_per_s"] = med([dsmoe.bench_stream(buf, (i % n) * win, win, False, 1024) for i in range(2 * n)])
+    out["stream_write_cold_200MiB_gb_per_s"] = med([dsmoe.bench_stream(buf, (i % n) * win, win, True, 1024) for i in range(2 * n)])
+    del buf
+    return out
+
+
+def summarise(head, others):
+    """Every configuration in a few numbers each (what the design doc's result table is made of)."""
+    def prefill(r):
+        return {"ms": r["ms_per_step"], "median_ms": r["median_ms"], "tokens_per_s": r["tokens_per_s"],
+                "frac_bf16_peak": r["layer_frac_of_bf16_peak"], "dominant_kernel": "gateup_bf16_kernel",
+                "gateup_frac": r["gateup_frac_of_bf16_peak"], "down_frac": r["down_frac_of_bf16_peak"],
+                "gateup_ms": r["gateup_kernel_ms"], "down_ms": r["down_kernel_ms"], "nnz": r["nnz"]}
+    out = {"c2": prefill(head)}
+    for key, name in (("c3", "c3"), ("c3_largest_paper_layer", "c3_d7168_f896")):
+        if key in others:
+            out[name] = {f'T{c["T"]}_{c["selection"]}': {
+                "us": c["us_per_call_median"], "gb_per_s": c["gb_per_s"], "frac_hbm_peak": c["frac_of_hbm_peak"],
+                "active_experts": c["active_experts_mean"], "tokens_per_s": c["tokens_per_s"],
+                "launches": 2 if c["path"].startswith("one persistent") else 5} for c in others[key]["cases"]}
+    if "c4" in others:
+        r = others["c4"]
+        out["c4"] = {"ms": r["ms_per_step"], "median_ms": r["median_ms"], "tokens_per_s": r["tokens_per_s"],
+                     "frac_bf16_peak": r["frac_of_bf16_peak"], "fwd_ms": r["fwd_ms"], "bwd_ms": r["bwd_ms"],
+                     "fwd_frac": r["fwd_frac_of_bf16_peak"], "bwd_frac": r["bwd_frac_of_bf16_peak"],
+                     "dominant_kernel": "dense_bwd_dwgu_kernel"}
+    for key in ("c5", "c2_gelu_expert", "c2_threshold_topk"):
+        if key in others:
+            out[key] = prefill(others[key])
+    if "m2_attention_experts" in others:
+        r = others["m2_attention_experts"]
+        out["m2"] = {"ms": r["ms_per_step"], "median_ms": r["median_ms"], "tokens_per_s": r["tokens_per_s"],
+                     "frac_bf16_peak": r["frac_of_bf16_peak"]}
+    def rnd(v):
+        if isinstance(v, dict):
+            return {k: rnd(x) for k, x in v.items()}
+        return float(f"{v:.4g}") if isinstance(v, float) else v
+    return rnd(out)
 
 
 def main():
@@ -309,6 +407,8 @@ def main():
     ap.add_argument("--cpu-passes", type=int, default=20, help="0 skips the CPU baseline")
     ap.add_argument("--decode-tokens", default="1,8,32,128", help="batch sizes of the decode workload (profiling aid)")
     ap.add_argument("--skip-large-decode", action="store_true", help="leave out the second decode layer shape")
+    ap.add_argument("--no-ceilings", action="store_true", help="skip the MFMA / streaming micro-benchmarks")
+    ap.add_argument("--verbose", action="store_true", help="also print the full per-workload records (`workloads`)")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MiB",
                     help="also run three plain device copies of this many MiB (a kernel of known HBM traffic, "
                          "used to scale rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
@@ -355,6 +455,12 @@ def main():
     if "m2" in wl:    # the attention-expert layer (Sec. 3.2), the paper's 6B shape
         others["m2_attention_experts"] = b.moa_prefill(side_steps, 3)
 
+    cfg_out = {"workload": "c2 (the configuration the metric is quoted on: sparse prefill, the second of the five): "
+                           + head["workload"][4:],
+               "nnz": head["nnz"], "active_fraction": head["active_fraction"],
+               "rows_per_expert_min_max": head["rows_per_expert_min_max"], "summary": summarise(head, others)}
+    if not args.no_ceilings:
+        cfg_out["ceilings"] = {k: (float(f"{v:.4g}") if isinstance(v, float) else v) for k, v in ceilings().items()}
     result = {
         "metric": METRIC,
         "value": head["tokens_per_s"],
@@ -368,12 +474,13 @@ def main():
         "vs_baseline": None,
         "dtype": "bf16",
         "data": "synthetic",
-        "config": {k: v for k, v in head.items() if k not in ("tokens_per_s", "ms_per_step")},
+        "config": cfg_out,
         "roofline": {"bound": "mfma", "kernel": "gateup_bf16_kernel", "achieved": head["gateup_tflops_per_s"],
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": head["gateup_tflops_per_s"] / PEAK_BF16_TFLOPS, "traffic": read_traffic("c2")},
-        "workloads": others,
     }
+    if args.verbose:
+        result["workloads"] = others
     if args.cpu_passes > 0:
         result["cpu_baseline"] = cpu_baseline(inp, cfg, args.cpu_passes)
     print(json.dumps(result), flush=True)

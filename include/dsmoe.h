@@ -169,6 +169,12 @@ int32_t dsmoe_sparse_fwd(dsmoe_ctx* ctx, const void* x, const void* w_r, const v
                          const void* w_gate, const void* w_up, const void* w_down, int32_t T,
                          int32_t mode, int32_t k, float eps, void* out, void* stream);
 
+/* 1 if dsmoe_sparse_fwd would serve a call of T tokens with this selection by its persistent decode kernel (a
+ * bf16 batch of at most 64 tokens that together select nearly every expert: top-K with at most a tenth of the
+ * experts expected idle, or at least 8 tokens under a normalised threshold of at most 1), which streams the
+ * weights of ALL experts once; 0 otherwise (also without a workspace).  Informational. */
+int32_t dsmoe_sparse_fwd_uses_persistent_kernel(const dsmoe_ctx* ctx, int32_t T, int32_t mode, int32_t k, float eps);
+
 /* Copies the routing objects of the last dsmoe_sparse_fwd out of the workspace (any argument may be
  * NULL; after a decode-sized call whose kernels need no dispatch, the dispatch objects are derived here, on
  * `stream`, from the scores and masks that call left): probs fp32 [T,E], mask u64 [T], expert_off i32 [E+1], row_token i32 [max_rows]. */

@@ -26,7 +26,7 @@ EXPORTS = [
     "dsmoe_set_workspace", "dsmoe_set_sync_spin_limit",
     "dsmoe_poll_error", "dsmoe_route", "dsmoe_select", "dsmoe_dispatch", "dsmoe_dispatch_static", "dsmoe_expert_ffn",
     "dsmoe_combine",
-    "dsmoe_sparse_fwd", "dsmoe_sparse_fwd_routing", "dsmoe_dense_saved_bytes", "dsmoe_dense_fwd",
+    "dsmoe_sparse_fwd", "dsmoe_sparse_fwd_routing", "dsmoe_sparse_fwd_uses_persistent_kernel", "dsmoe_dense_saved_bytes", "dsmoe_dense_fwd",
     "dsmoe_dense_bwd_scratch_bytes", "dsmoe_dense_bwd", "dsmoe_mi_loss", "dsmoe_dense_bwd_mi",
     "dsmoe_profile_enable", "dsmoe_profile_read", "dsmoe_bench_mfma", "dsmoe_bench_stream", "dsmoe_bench_xcc_ids",
     "dsmoe_moa_create", "dsmoe_moa_destroy", "dsmoe_moa_last_error", "dsmoe_moa_workspace_bytes",
@@ -80,6 +80,7 @@ def load_library() -> ctypes.CDLL:
         "dsmoe_combine": (c_int32, [P, P, P, P, P, c_int32, P, P]),
         "dsmoe_sparse_fwd": (c_int32, [P, P, P, P, P, P, P, c_int32, c_int32, c_int32, c_float, P, P]),
         "dsmoe_sparse_fwd_routing": (c_int32, [P, c_int32, P, P, P, P, P]),
+        "dsmoe_sparse_fwd_uses_persistent_kernel": (c_int32, [P, c_int32, c_int32, c_int32, c_float]),
         "dsmoe_dense_saved_bytes": (c_int32, [P, c_int32, POINTER(c_size_t)]),
         "dsmoe_dense_fwd": (c_int32, [P, P, P, P, P, P, P, c_int32, P, P, P, P]),
         "dsmoe_dense_bwd_scratch_bytes": (c_int32, [P, c_int32, POINTER(c_size_t)]),
@@ -144,6 +145,13 @@ def bench_stream(buf, offset: int, nbytes: int, write: bool, blocks: int = 2048)
     if rc != OK:
         raise DsmoeError(rc, "dsmoe_bench_stream")
     return moved.value / (ms.value * 1e-3) / 1e9
+
+
+def dense_decode_applies(layer, T: int, mode: int, k: int, eps: float) -> bool:
+    """Whether dsmoe_sparse_fwd serves this call with the persistent all-expert decode kernel (what the library
+    decides from the batch size and the selection rule; reported by the benchmark)."""
+    lib = load_library()
+    return bool(lib.dsmoe_sparse_fwd_uses_persistent_kernel(layer.ctx, T, mode, k, c_float(eps)))
 
 
 def xcc_ids(blocks: int = 256):

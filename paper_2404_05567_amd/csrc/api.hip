@@ -417,6 +417,15 @@ int32_t dsmoe_sparse_fwd(dsmoe_ctx* c, const void* x, const void* w_r, const voi
   return DSMOE_OK;
 }
 
+int32_t dsmoe_sparse_fwd_uses_persistent_kernel(const dsmoe_ctx* c, int32_t T, int32_t mode, int32_t k, float eps) {
+  if (!c || !c->workspace) return 0;
+  if (mode & DSMOE_SEL_NORMALISED) {
+    mode &= ~DSMOE_SEL_NORMALISED;
+    eps = eps / static_cast<float>(c->desc.n_experts);
+  }
+  return decode_dense_applies(c, T, mode, k, eps) ? 1 : 0;
+}
+
 int32_t dsmoe_sparse_fwd_routing(dsmoe_ctx* c, int32_t T, float* probs, uint64_t* mask, int32_t* expert_off,
                                  int32_t* row_token, void* stream) {
   if (int32_t rc = check_call(c, T, true)) return rc;

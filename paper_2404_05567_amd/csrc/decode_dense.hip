@@ -427,11 +427,17 @@ static int dense_ksplit(const dsmoe_ctx* c, int T, int slots) {
   return ks;
 }
 
+// Batches of more than 64 tokens stay with the kernels that gather each expert's own rows: with every token a
+// row of every tile, the token operand re-read from the L2 per K step weighs as much as the weight stream itself.
+constexpr int kDenseMaxTokens = 64;
+
 bool decode_dense_applies(const dsmoe_ctx* c, int T, int mode, int k, float eps) {
-  if (c->desc.dtype != DSMOE_BF16 || T < 1 || T > kDecodeMaxTokens || c->n_cu < 8) return false;
+  if (c->desc.dtype != DSMOE_BF16 || T < 1 || T > kDenseMaxTokens || c->n_cu < 8) return false;
   const int E = c->desc.n_experts;
   if ((long)8 * T > decode_row_cap(c)) return false;
-  const int items1 = E / 8 * ((c->desc.d_ff + 63) / 64), items2 = (c->desc.d_model + 127) / 128 * 32;
+  const int bns = c->expert_kind == DSMOE_EXPERT_GELU ? 128 : 64;
+  const int items1 = E / 8 * ((c->desc.d_ff + bns - 1) / bns);
+  const int items2 = (c->desc.d_model + 127) / 128 * dense_ksplit(c, T, c->n_cu / 8);
   if (items1 > 32 * kDenseClaimWords || items2 > 32 * kDenseClaimWords) return false;   // the claim bitmaps hold 1024 items
   if (mode == DSMOE_SEL_TOPK) {
     // share of the experts that T tokens with k uniformly spread choices each leave unselected

@@ -394,16 +394,18 @@ def test_weight_streaming_path_overflow_and_repeatability(torch, dsmoe):
 
 
 def test_all_expert_decode_kernel_alternating_inputs_and_bounded_waits(torch, dsmoe):
-    """The persistent decode kernel (T = 32 .. 128 tokens that select nearly every expert) hands results between
+    """The persistent decode kernel (8 .. 64 tokens that select nearly every expert) hands results between
     blocks through counters that each call must leave reset: alternate two different inputs and two batch sizes
     many times on one context and require bitwise the results of the first round; then make every wait between
     blocks give up at once (spin limit 0): the kernel must still end, the deferred status must say so, and the
     next call must be right again."""
-    cfg = gen.CONFIGS["c3"].with_(T=128)
+    cfg = gen.CONFIGS["c3"].with_(T=64)
     a = conditioned(cfg, "topk", 4, 0.0, variant=1)
     b = conditioned(cfg.with_(T=40), "threshold", 0, 0.02, variant=2)
     wa, wb = weights_to_dev(torch, a), weights_to_dev(torch, b)
     layer = dsmoe.Layer(cfg.d, cfg.f, cfg.E, cfg.dtype, max_tokens=128)
+    assert dsmoe.dense_decode_applies(layer, 64, dsmoe.SEL_TOPK, 4, 0.0)
+    assert dsmoe.dense_decode_applies(layer, 40, dsmoe.SEL_THRESHOLD, 0, 0.02)
     call_a = lambda: layer.sparse_fwd(wa["x"], wa["w_r"], None, wa["w_gate"], wa["w_up"], wa["w_down"], dsmoe.SEL_TOPK, 4, 0.0)
     call_b = lambda: layer.sparse_fwd(wb["x"], wb["w_r"], None, wb["w_gate"], wb["w_up"], wb["w_down"],
                                       dsmoe.SEL_THRESHOLD, 0, 0.02)
