@@ -21,11 +21,13 @@ FLAGS = [
 ]
 
 
-def build(verbose: bool = True, extra_flags=()) -> str:
+def build(verbose: bool = True, extra_flags=(), lib_path: str = LIB, obj_dir: str = CSRC, link_flags=()) -> str:
+    """Compiles every source for gfx950 and links them into lib_path (default: the in-tree libdsmoe.so).
+    obj_dir / lib_path / link_flags let a test build an instrumented copy elsewhere."""
     objs = []
     procs = []
     for src in SOURCES:
-        obj = os.path.join(CSRC, src.replace(".hip", ".o"))
+        obj = os.path.join(obj_dir, src.replace(".hip", ".o"))
         cmd = [HIPCC, *FLAGS, *extra_flags, "-c", os.path.join(CSRC, src), "-o", obj]
         procs.append((src, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))
         objs.append(obj)
@@ -40,10 +42,10 @@ def build(verbose: bool = True, extra_flags=()) -> str:
             sys.stderr.write(f"[build] {src}:\n{out}\n")
     if failed:
         raise RuntimeError("hipcc failed")
-    subprocess.check_call([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs])
+    subprocess.check_call([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", *link_flags, "-o", lib_path, *objs])
     if verbose:
-        sys.stderr.write(f"[build] wrote {LIB}\n")
-    return LIB
+        sys.stderr.write(f"[build] wrote {lib_path}\n")
+    return lib_path
 
 
 if __name__ == "__main__":
