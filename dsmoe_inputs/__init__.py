@@ -113,7 +113,7 @@ class LayerInputs:
 
 
 # stream ids (one independent Philox counter block per tensor)
-_S_X, _S_WR, _S_WG, _S_WU, _S_WD, _S_DO, _S_PERM, _S_REDRAW = range(8)
+_S_X, _S_WR, _S_WG, _S_WU, _S_WD, _S_DO, _S_PERM, _S_REDRAW, _S_MOA_DO = range(9)
 
 
 def make_router(cfg: LayerConfig, variant: int = 0):
@@ -234,3 +234,8 @@ def make_moa(cfg: MoaConfig, variant: int = 0) -> MoaInputs:
         v=_store(n(_S_DO, (cfg.n_head, cfg.L, cfg.d_head)), cfg.dtype),
         w_o=_store(n(_S_WD, (cfg.E, hd, cfg.d)) * std, cfg.dtype),
     )
+
+
+def make_moa_upstream_grad(cfg: MoaConfig, variant: int = 0) -> np.ndarray:
+    """Upstream gradient d_out [T, d] for the attention layer's dense-training backward."""
+    return _store(_rng(cfg, variant, _S_MOA_DO).standard_normal((cfg.T, cfg.d), dtype=np.float32), cfg.dtype)

@@ -241,7 +241,7 @@ int32_t dsmoe_bench_stream(void* window, size_t bytes, int32_t write, int32_t bl
 int32_t dsmoe_bench_xcc_ids(int32_t* out, int32_t blocks, void* stream);
 
 /* ---- Mixture-of-Attention-heads layer (Sec. 3.2, "Mixture of Attention Head", Eq. 7-8) -------------
- * Forward only, bf16 only.  E experts; expert i has a query projection W_q[i] and an output projection
+ * bf16 only.  E experts; expert i has a query projection W_q[i] and an output projection
  * W_o[i]; the n_head key/value heads of the cache are shared by all experts (grouped-query attention:
  * head j of every expert attends to K[j], V[j]).  For a token x with router scores S (softmax of
  * x W_r + b_r, as in the MLP layer) and selected set A:
@@ -257,7 +257,8 @@ int32_t dsmoe_bench_xcc_ids(int32_t* out, int32_t blocks, void* stream);
  * w_q [E, d, n_head*d_head]; k_cache, v_cache [n_head, L, d_head]; w_o [E, n_head*d_head, d]; out [T,d].
  * Limits: E a multiple of 8 and <= 64, d a multiple of 64, d_head 64 or 128, L >= T >= 0,
  * T <= max_tokens.  The context owns no device memory; dsmoe_moa_set_workspace lends it
- * dsmoe_moa_workspace_bytes bytes (router scores, masks, Q and the weighted attention outputs).
+ * dsmoe_moa_workspace_bytes bytes (router scores, masks, Q, the attention outputs with and without their
+ * weights, the softmax denominators).
  * mode: DSMOE_SEL_TOPK (k), DSMOE_SEL_THRESHOLD (eps) or DSMOE_SEL_ALL.  Errors as for the MLP layer
  * (status code, message from dsmoe_moa_last_error); one call at a time per context. */
 #define DSMOE_SEL_ALL (-1)
@@ -276,6 +277,28 @@ int32_t dsmoe_moa_fwd(dsmoe_moa_ctx* ctx, const void* x, const void* w_r, const 
 /* Copies the router scores (fp32 [T,E]) and selection masks (bit e of mask[t]; all experts for
  * DSMOE_SEL_ALL) of the last dsmoe_moa_fwd call out of the workspace; either pointer may be NULL. */
 int32_t dsmoe_moa_routing(dsmoe_moa_ctx* ctx, int32_t T, float* probs, uint64_t* mask, void* stream);
+
+/* Dense-training backward of the attention layer (Sec. 3.2, "Dense Training": every expert active and
+ * weighted by its score; gradients of Eq. 7-8, the score gradient as in Eq. 3 with the attention experts in
+ * the place of the MLP experts).  For the upstream gradient d_out [T,d] of
+ *     out = sum_i S_i sum_j softmax(scale Q_ij K_j^T) V_j W_o[i][j]
+ * it returns the gradients with respect to x, the router, both projections and the shared cache:
+ *     dx [T,d] bf16;  dw_r [d,E], db_r [E] (may be NULL), dw_q [E, d, n_head*d_head],
+ *     dw_o [E, n_head*d_head, d], dk and dv [n_head, L, d_head]: fp32, overwritten (not accumulated).
+ * It must directly follow, on the same stream, the dsmoe_moa_fwd call with mode DSMOE_SEL_ALL and the same
+ * x, weights, cache, T, L and scale: that call leaves the scores, the queries, the attention outputs and
+ * the logarithms of the softmax denominators in the workspace, and this one reads them (any other call
+ * in between, or another T, L or scale, is DSMOE_ERR_INVALID_ARG).  T >= 1.
+ * `scratch`: caller-owned device memory of dsmoe_moa_bwd_scratch_bytes(T, L) bytes, 256-byte aligned,
+ * contents irrelevant before and after (its largest part is the attention probabilities of all experts,
+ * E * T * n_head * L bf16 values).  No floating-point atomics: sums over experts and tokens are
+ * contractions in a fixed order, results are bitwise reproducible.  All pointers device, 16-byte aligned;
+ * nothing is allocated; work is enqueued on `stream`. */
+int32_t dsmoe_moa_bwd_scratch_bytes(const dsmoe_moa_ctx* ctx, int32_t T, int32_t L, size_t* bytes /* host */);
+int32_t dsmoe_moa_bwd(dsmoe_moa_ctx* ctx, const void* x, const void* w_r, const void* w_q, const void* k_cache,
+                      const void* v_cache, const void* w_o, const void* d_out, int32_t T, int32_t L, float scale,
+                      void* scratch, void* dx, float* dw_r, float* db_r, float* dw_q, float* dw_o, float* dk,
+                      float* dv, void* stream);
 
 #ifdef __cplusplus
 }

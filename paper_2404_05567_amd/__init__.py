@@ -30,7 +30,7 @@ EXPORTS = [
     "dsmoe_dense_bwd_scratch_bytes", "dsmoe_dense_bwd", "dsmoe_mi_loss", "dsmoe_dense_bwd_mi",
     "dsmoe_profile_enable", "dsmoe_profile_read", "dsmoe_bench_mfma", "dsmoe_bench_stream", "dsmoe_bench_xcc_ids",
     "dsmoe_moa_create", "dsmoe_moa_destroy", "dsmoe_moa_last_error", "dsmoe_moa_workspace_bytes",
-    "dsmoe_moa_set_workspace", "dsmoe_moa_fwd", "dsmoe_moa_routing",
+    "dsmoe_moa_set_workspace", "dsmoe_moa_fwd", "dsmoe_moa_routing", "dsmoe_moa_bwd_scratch_bytes", "dsmoe_moa_bwd",
 ]
 
 
@@ -99,6 +99,8 @@ def load_library() -> ctypes.CDLL:
         "dsmoe_moa_set_workspace": (c_int32, [P, P, c_size_t]),
         "dsmoe_moa_fwd": (c_int32, [P, P, P, P, P, P, P, P, c_int32, c_int32, c_int32, c_int32, c_float, c_float, P, P]),
         "dsmoe_moa_routing": (c_int32, [P, c_int32, P, P, P]),
+        "dsmoe_moa_bwd_scratch_bytes": (c_int32, [P, c_int32, c_int32, POINTER(c_size_t)]),
+        "dsmoe_moa_bwd": (c_int32, [P, P, P, P, P, P, P, P, c_int32, c_int32, c_float, P, P, P, P, P, P, P, P, P]),
     }
     for name, (res, args) in sig.items():
         fn = getattr(lib, name)
@@ -355,7 +357,7 @@ class Layer:
 
 
 class MoaLayer:
-    """One `dsmoe_moa_ctx` plus its workspace (Mixture-of-Attention-heads layer, forward, bf16)."""
+    """One `dsmoe_moa_ctx` plus its workspace (Mixture-of-Attention-heads layer, bf16)."""
 
     def __init__(self, d_model: int, n_experts: int, n_head: int, d_head: int, max_tokens: int, device="cuda:0"):
         import torch
@@ -404,3 +406,31 @@ class MoaLayer:
         mask = t.empty((T,), dtype=t.int64, device=self.device)
         self._check(self.lib.dsmoe_moa_routing(self.ctx, T, _ptr(probs), _ptr(mask), _stream()))
         return probs, mask
+
+    def bwd_scratch_bytes(self, T: int, L: int) -> int:
+        n = c_size_t()
+        self._check(self.lib.dsmoe_moa_bwd_scratch_bytes(self.ctx, T, L, byref(n)))
+        return n.value
+
+    def bwd(self, x, w_r, w_q, k_cache, v_cache, w_o, d_out, scale: float = 1.0, scratch=None, grads=None,
+            want_db_r: bool = True):
+        """Gradients of the dense-training forward (`fwd` with mode SEL_ALL, called right before with the same
+        arguments).  Returns a dict dx, dw_r, db_r, dw_q, dw_o, dk, dv; `scratch` / `grads` may be reused."""
+        t = self.torch
+        T, L = x.shape[0], k_cache.shape[1]
+        hd = self.n_head * self.d_head
+        if scratch is None:
+            scratch = t.empty(self.bwd_scratch_bytes(T, L) + 256, dtype=t.uint8, device=self.device)
+        base = (scratch.data_ptr() + 255) // 256 * 256
+        if grads is None:
+            f = dict(dtype=t.float32, device=self.device)
+            grads = dict(dx=t.empty((T, self.d), dtype=t.bfloat16, device=self.device),
+                         dw_r=t.empty((self.d, self.E), **f), db_r=t.empty((self.E,), **f) if want_db_r else None,
+                         dw_q=t.empty((self.E, self.d, hd), **f), dw_o=t.empty((self.E, hd, self.d), **f),
+                         dk=t.empty((self.n_head, L, self.d_head), **f), dv=t.empty((self.n_head, L, self.d_head), **f))
+        g = grads
+        self._check(self.lib.dsmoe_moa_bwd(self.ctx, _ptr(x), _ptr(w_r), _ptr(w_q), _ptr(k_cache), _ptr(v_cache),
+                                           _ptr(w_o), _ptr(d_out), T, L, scale, c_void_p(base), _ptr(g["dx"]),
+                                           _ptr(g["dw_r"]), _ptr(g["db_r"]), _ptr(g["dw_q"]), _ptr(g["dw_o"]),
+                                           _ptr(g["dk"]), _ptr(g["dv"]), _stream()))
+        return grads

@@ -12,19 +12,10 @@
 #include <cstdio>
 #include <new>
 
-#include "common.h"
 #include "gemm_core.h"
+#include "moa_internal.h"
 
 using namespace dsmoe;
-
-struct dsmoe_moa_ctx {
-  dsmoe_moa_desc desc;
-  dsmoe_ctx inner;          // descriptor and CU count for the shared launchers; owns nothing
-  char* workspace;
-  size_t workspace_bytes;
-  size_t o_probs, o_mask, o_cnt, o_q, o_cs, total;
-  char err[256];
-};
 
 namespace {
 
@@ -64,7 +55,8 @@ template <int DH>
 __global__ void __launch_bounds__(256, 2)
 moa_attention_kernel(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
                      const float* __restrict__ probs, const unsigned long long* __restrict__ mask,
-                     bf16_t* __restrict__ Cs, int T, int L, int E, int NH, float scale_log2e) {
+                     bf16_t* __restrict__ Cs, bf16_t* __restrict__ C_raw, float* __restrict__ lse, int T, int L, int E,
+                     int NH, float scale_log2e) {
   constexpr int BQ = 128, BKEY = 32, NS = DH / 16, NDT = DH / 32;
   constexpr int KP = DH * 2 + 16;        // bytes per key row of the K tile (16-byte skew: conflict-free 16-byte reads)
   constexpr int VP = BKEY * 2 + 8;       // bytes per dv row of the transposed V tile (9 x 8 bytes: conflict-free)
@@ -211,6 +203,18 @@ moa_attention_kernel(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K,
     for (int g = 0; g < 4; ++g)
       store4(crow + 32 * dt + 8 * g, o[dt][4 * g] * wgt, o[dt][4 * g + 1] * wgt, o[dt][4 * g + 2] * wgt,
              o[dt][4 * g + 3] * wgt);
+  if (C_raw == nullptr) return;
+  // kept for the backward pass of dense training: the unweighted outputs and, per row, log2 of the softmax
+  // denominator in the units of the scaled scores (P = 2^(score - lse))
+  const float inv = 1.f / l_tot;
+  bf16_t* rrow = C_raw + (size_t)t * E * hd + ((size_t)e * NH + j) * DH + 4 * h;
+#pragma unroll
+  for (int dt = 0; dt < NDT; ++dt)
+#pragma unroll
+    for (int g = 0; g < 4; ++g)
+      store4(rrow + 32 * dt + 8 * g, o[dt][4 * g] * inv, o[dt][4 * g + 1] * inv, o[dt][4 * g + 2] * inv,
+             o[dt][4 * g + 3] * inv);
+  if (h == 0) lse[((size_t)e * NH + j) * T + t] = m_run + __builtin_amdgcn_logf(l_tot);
 }
 
 size_t align256(size_t v) { return (v + 255) / 256 * 256; }
@@ -242,7 +246,11 @@ int32_t dsmoe_moa_create(const dsmoe_moa_desc* desc, dsmoe_moa_ctx** out) {
   c->o_cnt = take(T * 4);
   c->o_q = take(E * T * hd * 2);
   c->o_cs = take(T * E * hd * 2);
+  c->o_c = take(T * E * hd * 2);
+  c->o_lse = take(E * desc->n_head * T * 4);
   c->total = o;
+  c->saved_T = c->saved_L = -1;
+  c->saved_scale = 0.f;
   // the shared launchers read the shape and the CU count from an MLP-layer context
   dsmoe_ctx& in = c->inner;
   in.desc.d_model = desc->d_model;
@@ -312,6 +320,7 @@ int32_t dsmoe_moa_fwd(dsmoe_moa_ctx* c, const void* x, const void* w_r, const vo
   }
   if (!std::isfinite(scale)) return moa_fail(c, DSMOE_ERR_INVALID_ARG, "scale must be finite");
   if (!c->workspace) return moa_fail(c, DSMOE_ERR_WORKSPACE, "no workspace set (dsmoe_moa_set_workspace)");
+  c->saved_T = c->saved_L = -1;
   if (T == 0) return DSMOE_OK;
   MOA_PTR(c, x); MOA_PTR(c, w_r); MOA_PTR(c, w_q); MOA_PTR(c, k_cache); MOA_PTR(c, v_cache); MOA_PTR(c, w_o); MOA_PTR(c, out);
   if (b_r && misaligned16(b_r)) return moa_fail(c, DSMOE_ERR_INVALID_ARG, "pointer not 16-byte aligned: b_r");
@@ -322,6 +331,11 @@ int32_t dsmoe_moa_fwd(dsmoe_moa_ctx* c, const void* x, const void* w_r, const vo
   bf16_t* q = reinterpret_cast<bf16_t*>(c->workspace + c->o_q);
   bf16_t* cs = reinterpret_cast<bf16_t*>(c->workspace + c->o_cs);
   const bool all = mode == DSMOE_SEL_ALL;
+  bf16_t* c_raw = all ? reinterpret_cast<bf16_t*>(c->workspace + c->o_c) : nullptr;
+  float* lse = reinterpret_cast<float*>(c->workspace + c->o_lse);
+  c->saved_T = all ? T : -1;      // what dsmoe_moa_bwd may rely on
+  c->saved_L = all ? L : -1;
+  c->saved_scale = scale;
 
   // every expert selected = the E highest scores: the masks are then all ones
   MOA_HIP(c, launch_route(&c->inner, x, w_r, b_r, T, probs, all ? DSMOE_SEL_TOPK : mode, all ? E : k, eps, mask, cnt, s));
@@ -331,10 +345,10 @@ int32_t dsmoe_moa_fwd(dsmoe_moa_ctx* c, const void* x, const void* w_r, const vo
   const unsigned long long* mk = reinterpret_cast<const unsigned long long*>(mask);
   if (DH == 64)
     moa_attention_kernel<64><<<grid, dim3(256), 0, s>>>(q, (const bf16_t*)k_cache, (const bf16_t*)v_cache, probs, mk, cs,
-                                                        T, L, E, NH, sl2e);
+                                                        c_raw, lse, T, L, E, NH, sl2e);
   else
     moa_attention_kernel<128><<<grid, dim3(256), 0, s>>>(q, (const bf16_t*)k_cache, (const bf16_t*)v_cache, probs, mk, cs,
-                                                         T, L, E, NH, sl2e);
+                                                         c_raw, lse, T, L, E, NH, sl2e);
   MOA_HIP(c, hipGetLastError());
   MOA_HIP(c, launch_down_dense(&c->inner, cs, T, E * hd, w_o, out, s));
   return DSMOE_OK;

@@ -160,6 +160,21 @@ def test_attention_layer_entry_points_validate_on_the_host(lib):
     assert call(x=None) == dsmoe.ERR_INVALID_ARG
     assert call(x=odd) == dsmoe.ERR_INVALID_ARG
     assert call(T=0) == dsmoe.OK
+    # backward: scratch size query, and the call is refused unless the dense forward of the same shape came before
+    nb = c_size_t()
+    assert lib.dsmoe_moa_bwd_scratch_bytes(ctx, 4, 8, byref(nb)) == dsmoe.OK
+    assert nb.value >= 8 * 4 * 2 * 32 * 2       # at least the attention probabilities, key axis padded to 32
+    assert lib.dsmoe_moa_bwd_scratch_bytes(ctx, 4, 3, byref(nb)) == dsmoe.ERR_INVALID_ARG
+    assert lib.dsmoe_moa_bwd_scratch_bytes(None, 4, 8, byref(nb)) == dsmoe.ERR_INVALID_ARG
+    bwd = lambda **kw: lib.dsmoe_moa_bwd(ctx, fake, fake, fake, fake, fake, fake, fake, kw.get("T", 4), kw.get("L", 8),
+                                         kw.get("scale", one), fake, fake, fake, None, fake, fake, fake, fake, s)
+    assert bwd(T=0) == dsmoe.ERR_INVALID_ARG
+    assert bwd(T=65) == dsmoe.ERR_INVALID_ARG
+    assert bwd(L=3) == dsmoe.ERR_INVALID_ARG
+    assert bwd(scale=ct.c_float(float("inf"))) == dsmoe.ERR_INVALID_ARG
+    assert bwd() == dsmoe.ERR_INVALID_ARG and b"dsmoe_moa_fwd" in lib.dsmoe_moa_last_error(ctx)
+    assert lib.dsmoe_moa_bwd(None, fake, fake, fake, fake, fake, fake, fake, 4, 8, one, fake, fake, fake, None, fake,
+                             fake, fake, fake, s) == dsmoe.ERR_INVALID_ARG
     assert lib.dsmoe_moa_destroy(ctx) == dsmoe.OK
     assert lib.dsmoe_moa_destroy(None) == dsmoe.ERR_INVALID_ARG
 

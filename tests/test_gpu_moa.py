@@ -139,3 +139,85 @@ def test_m2_full_size_prefill_sampled(torch, dsmoe):
     err = helpers.rel_err(o[sample], ref)
     say(f"  sampled rel err {err:.3e}")
     assert err <= TOL
+
+
+# --------------------------------------------------------------------------------------------------
+# Dense-training backward (Sec. 3.2, "Dense Training"; gradients of Eq. 7-8, score gradient as in Eq. 3)
+# --------------------------------------------------------------------------------------------------
+GRADS = (("dx", "dX"), ("dw_r", "dW_r"), ("db_r", "db_r"), ("dw_q", "dW_q"), ("dw_o", "dW_o"), ("dk", "dK"), ("dv", "dV"))
+
+
+def fwd_bwd(torch, dsmoe, layer, inp, d_out, scale):
+    args = [dev(torch, a) for a in (inp.x, inp.w_r, inp.w_q, inp.k, inp.v, inp.w_o)]
+    x, w_r, w_q, k, v, w_o = args
+    out = layer.fwd(x, w_r, dev(torch, inp.b_r), w_q, k, v, w_o, dsmoe.SEL_ALL, 0, 0.0, float(scale))
+    g = layer.bwd(x, w_r, w_q, k, v, w_o, dev(torch, d_out), float(scale))
+    torch.cuda.synchronize()
+    return out, g
+
+
+def check_backward(torch, dsmoe, cfg, scale=None, variant=0):
+    scale = 1.0 / np.sqrt(cfg.d_head) if scale is None else scale
+    inp = gen.make_moa(cfg, variant)
+    d_out = gen.make_moa_upstream_grad(cfg, variant)
+    say(f"[case] moa backward {cfg.name} T={cfg.T} L={cfg.L} d={cfg.d} E={cfg.E} heads={cfg.n_head}x{cfg.d_head} "
+        f"scale={scale:.4f}")
+    layer = dsmoe.MoaLayer(cfg.d, cfg.E, cfg.n_head, cfg.d_head, max_tokens=cfg.T)
+    out, g = fwd_bwd(torch, dsmoe, layer, inp, d_out, scale)
+    O_ref, _, _ = moa.moa_forward(inp.x, inp.w_r, inp.b_r, inp.w_q, inp.k, inp.v, inp.w_o, "dense", scale=scale)
+    assert helpers.rel_err(out.float().cpu().numpy(), O_ref) <= TOL
+    ref = moa.moa_dense_backward(inp.x, inp.w_r, inp.b_r, inp.w_q, inp.k, inp.v, inp.w_o, d_out, scale)
+    for name, rname in GRADS:
+        err = helpers.rel_err(g[name].float().cpu().numpy(), ref[rname])
+        say(f"  {name}: rel err {err:.3e}")
+        assert err <= TOL, name
+    return layer, inp, d_out, g
+
+
+def test_backward_m1_and_bitwise_repeat(torch, dsmoe):
+    cfg = gen.MOA_CONFIGS["m1"].with_(mode="dense")
+    layer, inp, d_out, g = check_backward(torch, dsmoe, cfg)
+    _, g2 = fwd_bwd(torch, dsmoe, layer, inp, d_out, 1.0 / np.sqrt(cfg.d_head))
+    for name, _ in GRADS:
+        assert torch.equal(g[name], g2[name]), name
+
+
+@pytest.mark.parametrize("T,L,n_head,d_head", [(1, 1, 2, 64), (1, 37, 1, 128), (129, 129, 2, 64), (300, 555, 2, 128),
+                                               (257, 700, 3, 64)])
+def test_backward_ragged_shapes(torch, dsmoe, T, L, n_head, d_head):
+    cfg = gen.MoaConfig("bwd_ragged", 16, T=T, L=L, d=256, E=8, n_head=n_head, d_head=d_head, dtype="bf16", mode="dense",
+                        router_std=0.1)
+    check_backward(torch, dsmoe, cfg)
+
+
+def test_backward_sixteen_and_sixtyfour_experts_and_unit_scale(torch, dsmoe):
+    check_backward(torch, dsmoe, gen.MoaConfig("bwd_e16", 17, T=200, L=200, d=512, E=16, n_head=2, d_head=64, dtype="bf16",
+                                               mode="dense", router_std=0.1))
+    check_backward(torch, dsmoe, gen.MoaConfig("bwd_e64", 18, T=100, L=300, d=256, E=64, n_head=1, d_head=64, dtype="bf16",
+                                               mode="dense", router_std=0.1), scale=1.0)
+
+
+def test_backward_needs_the_matching_dense_forward(torch, dsmoe):
+    cfg = gen.MOA_CONFIGS["m1"].with_(mode="dense")
+    inp = gen.make_moa(cfg)
+    d_out = dev(torch, gen.make_moa_upstream_grad(cfg))
+    layer = dsmoe.MoaLayer(cfg.d, cfg.E, cfg.n_head, cfg.d_head, max_tokens=cfg.T)
+    x, w_r, w_q, k, v, w_o = [dev(torch, a) for a in (inp.x, inp.w_r, inp.w_q, inp.k, inp.v, inp.w_o)]
+    with pytest.raises(dsmoe.DsmoeError) as e:      # no forward yet
+        layer.bwd(x, w_r, w_q, k, v, w_o, d_out, 1.0)
+    assert e.value.code == dsmoe.ERR_INVALID_ARG
+    layer.fwd(x, w_r, None, w_q, k, v, w_o, dsmoe.SEL_TOPK, 2, 0.0, 1.0)
+    with pytest.raises(dsmoe.DsmoeError):           # a sparse forward keeps nothing for the backward pass
+        layer.bwd(x, w_r, w_q, k, v, w_o, d_out, 1.0)
+    layer.fwd(x, w_r, None, w_q, k, v, w_o, dsmoe.SEL_ALL, 0, 0.0, 1.0)
+    with pytest.raises(dsmoe.DsmoeError):           # another scale
+        layer.bwd(x, w_r, w_q, k, v, w_o, d_out, 0.5)
+    layer.bwd(x, w_r, w_q, k, v, w_o, d_out, 1.0)
+    torch.cuda.synchronize()
+
+
+def test_m2_full_size_dense_training_backward(torch, dsmoe):
+    """The 6B shape at 2048 tokens, forward and backward; the checker's backward at this size takes a few seconds
+    per expert in fp64, so every gradient is compared in full."""
+    cfg = gen.MOA_CONFIGS["m2"]
+    check_backward(torch, dsmoe, cfg)
