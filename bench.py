@@ -262,7 +262,29 @@ class Bench:
         pairs = sum(cfg.L - cfg.T + t + 1 for t in range(cfg.T))          # (query, visible key) pairs per head
         flops_proj = 2 * 2 * cfg.T * cfg.d * cfg.E * hd + 2 * cfg.T * cfg.d * cfg.E
         flops_att = 4 * cfg.E * cfg.n_head * cfg.d_head * pairs
+
+        # dense training of the same layer: forward (every expert active) + backward
+        d_out = to(gen.make_moa_upstream_grad(cfg))
+        scratch = torch.empty(layer.bwd_scratch_bytes(cfg.T, cfg.L) + 256, dtype=torch.uint8, device=self.dev)
+        grads = layer.bwd(x, w_r, w_q, k, v, w_o, d_out, scale, scratch=scratch) if mode == dsmoe.SEL_ALL else None
+        train = {}
+        if grads is not None:
+            def train_step():
+                layer.fwd(x, w_r, None, w_q, k, v, w_o, dsmoe.SEL_ALL, 0, 0.0, scale, out=out)
+                layer.bwd(x, w_r, w_q, k, v, w_o, d_out, scale, scratch=scratch, grads=grads)
+
+            ms_t = self.timed(train_step, steps, warmup)
+            ms_t_median = self.median_ms(train_step, max(20, steps))
+            assert all(torch.isfinite(g.float()).all() for g in grads.values())
+            # backward: two products per projection and forward product (input and weight gradient); the attention
+            # itself costs 2.5x its forward (scores again, dV, dP, dQ, dK against QK^T and PV)
+            flops_bwd = 2 * (2 * 2 * cfg.T * cfg.d * cfg.E * hd) + 2.5 * flops_att + 2 * 2 * cfg.T * cfg.d * cfg.E
+            train = {"train_ms_per_step": ms_t, "train_median_ms": ms_t_median, "train_tokens_per_s": cfg.T / (ms_t * 1e-3),
+                     "train_tflop": (flops_proj + flops_att + flops_bwd) / 1e12,
+                     "train_frac_of_bf16_peak": (flops_proj + flops_att + flops_bwd) / (ms_t * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+                     "bwd_scratch_bytes": int(scratch.numel())}
         return {
+            **train,
             "workload": f"{name}: attention-expert layer forward, T={cfg.T} L={cfg.L} d_model={cfg.d} E={cfg.E} "
                         f"heads={cfg.n_head}x{cfg.d_head}, {cfg.mode}",
             "ms_per_step": ms, "median_ms": ms_median, "tokens_per_s": cfg.T / (ms * 1e-3),
@@ -389,6 +411,9 @@ def summarise(head, others):
         r = others["m2_attention_experts"]
         out["m2"] = {"ms": r["ms_per_step"], "median_ms": r["median_ms"], "tokens_per_s": r["tokens_per_s"],
                      "frac_bf16_peak": r["frac_of_bf16_peak"]}
+        if "train_ms_per_step" in r:
+            out["m2"].update({"train_fwd_bwd_ms": r["train_ms_per_step"], "train_median_ms": r["train_median_ms"],
+                              "train_tokens_per_s": r["train_tokens_per_s"], "train_frac_bf16_peak": r["train_frac_of_bf16_peak"]})
     def rnd(v):
         if isinstance(v, dict):
             return {k: rnd(x) for k, x in v.items()}

@@ -27,7 +27,7 @@ using namespace dsmoe;
 
 namespace {
 
-enum { kEpiPlain = 0, kEpiProbs = 1, kEpiSoftmaxBwd = 2, kEpiAdd = 3 };
+enum { kEpiPlain = 0, kEpiProbs = 1, kEpiSoftmaxBwd = 2 };
 
 // out[b][m][n] = alpha * sum_k L_b[m][k] R_b[k][n], b = (b1, b2), with optional epilogues.
 // "rows" operands are k-contiguous (element [m][k] at base + m ld + k), "cols" operands are stored [k][m].
@@ -39,10 +39,11 @@ struct BatchedArgs {
   int seg_k;                                  // rows x rows only: K is cut in segments of seg_k ...
   long long segL, segR;                       // ... that lie segL / segR elements apart (0: one contiguous run)
   float alpha;
+  int tiles_per_batch;                        // tiles of a batch member that are computed (causal epilogues leave some out)
   const float* rowv;                          // kEpiProbs: lse [b][M];  kEpiSoftmaxBwd: delta [b][M]
   int pos0;                                   // both: column n is visible to row m iff n <= pos0 + m
   int causal_k;                               // the left operand is zero for k > pos0 + m: stop the contraction there
-  const float* addend; long long ld_add;      // kEpiAdd: out = alpha acc + addend[m][n]
+  int causal_k0;                              // cols x cols: the left operand is zero for k < m - pos0: start there
   const void* zeros;
 };
 
@@ -51,11 +52,27 @@ __global__ void __launch_bounds__(kThreads2) batched_gemm_kernel(const BatchedAr
   typedef Gemm<bf16_t, 256, 256, 1, LK, RK, LK || RK> GM;
   DSMOE_GEMM_STAGES(GM, st);
   const int n_mt = (a.M + GM::BM - 1) / GM::BM, n_nt = (a.N + GM::BN - 1) / GM::BN;
+  (void)n_mt;
   TileWalker tw;
-  tw.init(a.nb1 * a.nb2 * n_mt * n_nt);
+  constexpr bool causal = EPI == kEpiProbs || EPI == kEpiSoftmaxBwd;
+  tw.init(a.nb1 * a.nb2 * a.tiles_per_batch);
   int idx;
   while (tw.next(idx)) {
-    const int nt = idx % n_nt, mt = (idx / n_nt) % n_mt, b = idx / (n_nt * n_mt);
+    // A tile wholly behind the causal diagonal would hold zeros.  It is neither computed nor stored (the products
+    // that read the probabilities leave the same tiles out: causal_k, causal_k0), and not dealt out either: row
+    // tile mt has the column tiles up to its last visible key.
+    const int b = idx / a.tiles_per_batch;
+    int nt = idx % a.tiles_per_batch, mt = 0;
+    if constexpr (causal) {
+      for (; mt < n_mt - 1; ++mt) {
+        const int c = min(n_nt, (a.pos0 + mt * GM::BM + GM::BM - 1) / GM::BN + 1);
+        if (nt < c) break;
+        nt -= c;
+      }
+    } else {
+      mt = nt / n_nt;
+      nt = nt % n_nt;
+    }
     const int b1 = b / a.nb2, b2 = b % a.nb2;
     const int m0 = mt * GM::BM, n0 = nt * GM::BN;
     const bf16_t* Lb = a.L + b1 * a.sL1 + b2 * a.sL2;
@@ -63,62 +80,74 @@ __global__ void __launch_bounds__(kThreads2) batched_gemm_kernel(const BatchedAr
     char* Ob = static_cast<char*>(a.out) + (size_t)(b1 * a.sO1 + b2 * a.sO2) * (OUT_F32 ? 4 : 2);
     typename GM::Acc acc;
     GM::zero(acc);
-    // a tile wholly behind the causal diagonal holds zeros: no product
-    constexpr bool causal = EPI == kEpiProbs || EPI == kEpiSoftmaxBwd;
-    if (!(causal && n0 > a.pos0 + m0 + GM::BM - 1)) {
+    {
       typename GM::LSrc L;
       typename GM::RSrc R;
-      if constexpr (LK) GM::l_cols(L, Lb + m0, (size_t)a.ldl, a.M - m0, a.K, a.zeros);
+      int K = a.K;
+      if constexpr (LK && RK) {
+        if (a.causal_k0) {
+          const int k0 = max(0, m0 - a.pos0) / GM::BK * GM::BK;
+          Lb += (size_t)k0 * a.ldl;
+          Rb += (size_t)k0 * a.ldr;
+          K -= k0;
+        }
+      }
+      if constexpr (LK) GM::l_cols(L, Lb + m0, (size_t)a.ldl, a.M - m0, K, a.zeros);
       else GM::l_rows(L, min(GM::BM, a.M - m0), (size_t)a.segL * 2, [&](int r) { return Lb + (size_t)(m0 + r) * a.ldl; });
       if constexpr (RK) {
         const bf16_t* const base[1] = {Rb + n0};
-        GM::r_cols(R, base, (size_t)a.ldr, a.N - n0, a.K, a.zeros);
+        GM::r_cols(R, base, (size_t)a.ldr, a.N - n0, K, a.zeros);
       } else {
         GM::r_rows(R, min(GM::BN, a.N - n0), (size_t)a.segR * 2, [&](int r) { return Rb + (size_t)(n0 + r) * a.ldr; });
       }
-      const int k_end = a.causal_k ? min(a.K, a.pos0 + m0 + GM::BM) : a.K;
+      const int k_end = a.causal_k ? min(K, a.pos0 + m0 + GM::BM) : K;
       const int nkt = (k_end + GM::BK - 1) / GM::BK;
       GM::mainloop(acc, L, R, nkt, a.seg_k > 0 ? a.seg_k / GM::BK : 1 << 30, st);
     }
-    GM::for_each_chunk(acc, st, [&](int m, int n, const float (&v)[1][GM::CHUNK]) {
-      const int row = m0 + m, col = n0 + n;
-      if (row >= a.M || col >= a.N) return;
-      float o[GM::CHUNK];
-      if constexpr (EPI == kEpiProbs) {
-        const float lse = a.rowv[(size_t)b * a.M + row];
+    // what a chunk's epilogue reads from memory is requested a 32-row block ahead of its use
+    float rv[GM::NJ];
+    u32x4 q0[GM::NJ];
+    GM::for_each_chunk_loaded(
+        acc, st,
+        [&](int j, int m, int n) {
+          const int row = m0 + m, col = n0 + n;
+          if (row >= a.M || col >= a.N) return;
+          if constexpr (EPI == kEpiProbs || EPI == kEpiSoftmaxBwd) rv[j] = a.rowv[(size_t)b * a.M + row];
+          if constexpr (EPI == kEpiSoftmaxBwd) q0[j] = load_raw(reinterpret_cast<const bf16_t*>(Ob) + (size_t)row * a.ldo + col);
+        },
+        [&](int j, int m, int n, const float (&v)[1][GM::CHUNK]) {
+          const int row = m0 + m, col = n0 + n;
+          if (row >= a.M || col >= a.N) return;
+          float o[GM::CHUNK];
+          if constexpr (EPI == kEpiProbs) {
 #pragma unroll
-        for (int i = 0; i < GM::CHUNK; ++i)
-          o[i] = col + i <= a.pos0 + row ? __builtin_amdgcn_exp2f(fminf(v[0][i] * a.alpha - lse, 0.f)) : 0.f;
-      } else if constexpr (EPI == kEpiSoftmaxBwd) {
-        const float delta = a.rowv[(size_t)b * a.M + row];
-        float p[GM::CHUNK];
-        load_chunk(reinterpret_cast<const bf16_t*>(Ob) + (size_t)row * a.ldo + col, p);
+            for (int i = 0; i < GM::CHUNK; ++i)
+              o[i] = col + i <= a.pos0 + row ? __builtin_amdgcn_exp2f(fminf(v[0][i] * a.alpha - rv[j], 0.f)) : 0.f;
+          } else if constexpr (EPI == kEpiSoftmaxBwd) {
+            float p[GM::CHUNK];
+            unpack_chunk(q0[j], p, (const bf16_t*)nullptr);
 #pragma unroll
-        for (int i = 0; i < GM::CHUNK; ++i) o[i] = col + i <= a.pos0 + row ? p[i] * (v[0][i] - delta) * a.alpha : 0.f;
-      } else if constexpr (EPI == kEpiAdd) {
-        float ad[GM::CHUNK];
+            for (int i = 0; i < GM::CHUNK; ++i) o[i] = col + i <= a.pos0 + row ? p[i] * (v[0][i] - rv[j]) * a.alpha : 0.f;
+          } else {
 #pragma unroll
-        for (int i = 0; i < GM::CHUNK; i += 4) {
-          const f32x4 q = __builtin_bit_cast(f32x4, ldg16(a.addend + (size_t)row * a.ld_add + col + i));
-          ad[i] = q.x; ad[i + 1] = q.y; ad[i + 2] = q.z; ad[i + 3] = q.w;
-        }
-#pragma unroll
-        for (int i = 0; i < GM::CHUNK; ++i) o[i] = v[0][i] * a.alpha + ad[i];
-      } else {
-#pragma unroll
-        for (int i = 0; i < GM::CHUNK; ++i) o[i] = v[0][i] * a.alpha;
-      }
-      if constexpr (OUT_F32) store_chunk(reinterpret_cast<float*>(Ob) + (size_t)row * a.ldo + col, o);
-      else store_chunk(reinterpret_cast<bf16_t*>(Ob) + (size_t)row * a.ldo + col, o);
-    });
+            for (int i = 0; i < GM::CHUNK; ++i) o[i] = v[0][i] * a.alpha;
+          }
+          if constexpr (OUT_F32) store_chunk(reinterpret_cast<float*>(Ob) + (size_t)row * a.ldo + col, o);
+          else store_chunk(reinterpret_cast<bf16_t*>(Ob) + (size_t)row * a.ldo + col, o);
+        });
   }
 }
 
 template <bool LK, bool RK, bool OUT_F32, int EPI = kEpiPlain>
 hipError_t launch_batched(const dsmoe_ctx* c, const BatchedArgs& a, hipStream_t s) {
-  const long tiles = (long)a.nb1 * a.nb2 * ((a.M + 255) / 256) * ((a.N + 255) / 256);
+  const int n_mt = (a.M + 255) / 256, n_nt = (a.N + 255) / 256;
+  BatchedArgs b = a;
+  b.tiles_per_batch = 0;
+  for (int mt = 0; mt < n_mt; ++mt)
+    b.tiles_per_batch += EPI == kEpiPlain ? n_nt : std::min(n_nt, (a.pos0 + mt * 256 + 255) / 256 + 1);
+  const long tiles = (long)a.nb1 * a.nb2 * b.tiles_per_batch;
   const int grid = (int)((std::min<long>(tiles, c->n_cu) + 7) / 8 * 8);
-  batched_gemm_kernel<LK, RK, OUT_F32, EPI><<<dim3(grid), dim3(kThreads2), 0, s>>>(a);
+  batched_gemm_kernel<LK, RK, OUT_F32, EPI><<<dim3(grid), dim3(kThreads2), 0, s>>>(b);
   return hipGetLastError();
 }
 
@@ -159,10 +188,10 @@ __global__ void __launch_bounds__(256) moa_score_grad_kernel(const bf16_t* __res
   if (lane == 0) dS[(size_t)t * E + e] = total;
 }
 
-// dZ = S (dS - sum_k S_k dS_k): one wave per token, one lane per expert; also dZ in bf16, padded to EP columns
+// dZ = S (dS - sum_k S_k dS_k): one wave per token, one lane per expert
 __global__ void __launch_bounds__(256) moa_softmax_bwd_kernel(const float* __restrict__ S, const float* __restrict__ dS,
-                                                             int T, int E, int EP, float* __restrict__ dZ,
-                                                             bf16_t* __restrict__ dZt, unsigned* __restrict__ zeros) {
+                                                             int T, int E, float* __restrict__ dZ,
+                                                             unsigned* __restrict__ zeros) {
   if (blockIdx.x == 0 && threadIdx.x < 64) zeros[threadIdx.x] = 0u;   // the zero page of the token-contracted products
   const int lane = threadIdx.x & 63;
   const int t = blockIdx.x * 4 + (threadIdx.x >> 6);
@@ -173,17 +202,73 @@ __global__ void __launch_bounds__(256) moa_softmax_bwd_kernel(const float* __res
   for (int o = 32; o > 0; o >>= 1) dot += __shfl_xor(dot, o, 64);
   const float dz = s * (ds - dot);
   if (lane < E) dZ[(size_t)t * E + lane] = dz;
-  if (lane < EP) dZt[(size_t)t * EP + lane] = (bf16_t)(lane < E ? dz : 0.f);
 }
 
-// router term of dX in fp32: add[t][n] = sum_e dZ[t][e] W_r[n][e]
+// dX = (sum_e dQ_e W_q[e]^T, handed over in fp32) + dZ W_r^T, rounded once: dx[t][n] = dxf[t][n] + sum_e dZ[t][e] W_r[n][e].
+// A thread keeps its row of W_r in registers and walks kRouterTok tokens, whose dZ rows are the same for the whole block.
+constexpr int kRouterTok = 32;
 __global__ void __launch_bounds__(256) moa_router_dx_kernel(const float* __restrict__ dZ, const bf16_t* __restrict__ w_r, int T,
-                                                           int d, int E, float* __restrict__ add) {
-  const int t = blockIdx.x, n = blockIdx.y * 256 + threadIdx.x;
+                                                           int d, int E, const float* __restrict__ dxf,
+                                                           bf16_t* __restrict__ dx) {
+  const int n = blockIdx.y * 256 + threadIdx.x, t0 = blockIdx.x * kRouterTok;
   if (n >= d) return;
-  float acc = 0.f;
-  for (int e = 0; e < E; ++e) acc = fmaf(dZ[(size_t)t * E + e], (float)w_r[(size_t)n * E + e], acc);
-  add[(size_t)t * d + n] = acc;
+  float w[kMaxExperts];
+#pragma unroll
+  for (int c = 0; c < kMaxExperts / 8; ++c) {
+    float v[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    if (8 * c < E) load_chunk(w_r + (size_t)n * E + 8 * c, v);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) w[8 * c + i] = v[i];
+  }
+  for (int t = t0; t < min(T, t0 + kRouterTok); ++t) {
+    const float* z = dZ + (size_t)t * E;
+    float acc = dxf[(size_t)t * d + n];
+#pragma unroll
+    for (int c = 0; c < kMaxExperts / 8; ++c)
+      if (8 * c < E) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) acc = fmaf(z[8 * c + i], w[8 * c + i], acc);
+      }
+    dx[(size_t)t * d + n] = (bf16_t)acc;
+  }
+}
+
+// dW_r = X^T dZ as partial sums over token ranges: part[split][n][e] = sum over the split's tokens of
+// X[t][n] dZ[t][e]; a thread owns two neighbouring columns n and eight experts (blockIdx.z picks the eight).
+__global__ void __launch_bounds__(256) moa_router_dw_kernel(const bf16_t* __restrict__ x, const float* __restrict__ dZ, int T,
+                                                           int d, int E, int tok_per_split, float* __restrict__ part) {
+  const int n = 2 * (blockIdx.x * 256 + threadIdx.x), e0 = 8 * blockIdx.z;
+  if (n >= d) return;
+  const int t0 = blockIdx.y * tok_per_split, t1 = min(T, t0 + tok_per_split);
+  float a0[8], a1[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) a0[i] = a1[i] = 0.f;
+  for (int t = t0; t < t1; ++t) {
+    const unsigned xv = *reinterpret_cast<const unsigned*>(x + (size_t)t * d + n);
+    const float x0 = __uint_as_float(xv << 16), x1 = __uint_as_float(xv & 0xffff0000u);
+    const float* z = dZ + (size_t)t * E + e0;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      a0[i] = fmaf(x0, z[i], a0[i]);
+      a1[i] = fmaf(x1, z[i], a1[i]);
+    }
+  }
+  float* o = part + ((size_t)blockIdx.y * d + n) * E + e0;
+  store4(o, a0[0], a0[1], a0[2], a0[3]);
+  store4(o + 4, a0[4], a0[5], a0[6], a0[7]);
+  store4(o + E, a1[0], a1[1], a1[2], a1[3]);
+  store4(o + E + 4, a1[4], a1[5], a1[6], a1[7]);
+}
+
+// out[g][i] = sum over s < n_part of part[(g * n_part + s) * n + i], in order; g = blockIdx.y, 4 values per thread
+__global__ void __launch_bounds__(256) moa_sum_parts_kernel(const float* __restrict__ part, int n_part, size_t n,
+                                                           float* __restrict__ out) {
+  const size_t i = 4 * ((size_t)blockIdx.x * 256 + threadIdx.x);
+  if (i >= n) return;
+  const float* p = part + (size_t)blockIdx.y * n_part * n + i;
+  f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+  for (int sp = 0; sp < n_part; ++sp) acc += __builtin_bit_cast(f32x4, ldg16(p + sp * n));
+  store4(out + (size_t)blockIdx.y * n + i, acc.x, acc.y, acc.z, acc.w);
 }
 
 // db_r[e] = sum_t dZ[t][e]: one block per expert, strided partial sums, then a fixed-order tree
@@ -213,12 +298,13 @@ __global__ void __launch_bounds__(256) moa_zero_pad_kernel(bf16_t* __restrict__ 
 
 size_t al256(size_t v) { return (v + 255) / 256 * 256; }
 
-struct BwdScratch { size_t zeros, dcs, dc, delta, ds, p, dq, dz, dzt, add, total; int Lp, EP; };
+struct BwdScratch { size_t zeros, dcs, dc, delta, ds, p, dq, dz, dxf, part, total; int Lp, tok_per_split, n_split; };
 BwdScratch bwd_scratch(const dsmoe_moa_desc& d, int T, int L) {
   const size_t E = d.n_experts, hd = (size_t)d.n_head * d.d_head, Tn = T;
   BwdScratch l;
   l.Lp = (L + 31) / 32 * 32;
-  l.EP = (d.n_experts + 31) / 32 * 32;
+  l.tok_per_split = std::max(64, (T + 63) / 64);          // token ranges of the router weight gradient: at most 64
+  l.n_split = (T + l.tok_per_split - 1) / l.tok_per_split;
   size_t o = 0;
   auto take = [&](size_t bytes) { const size_t at = o; o = al256(o + bytes); return at; };
   l.zeros = take(256);
@@ -229,8 +315,9 @@ BwdScratch bwd_scratch(const dsmoe_moa_desc& d, int T, int L) {
   l.p = take(E * Tn * d.n_head * (size_t)l.Lp * 2);
   l.dq = take(E * Tn * hd * 2);
   l.dz = take(Tn * E * 4);
-  l.dzt = take(Tn * l.EP * 2);
-  l.add = take(Tn * (size_t)d.d_model * 4);
+  l.dxf = take(Tn * (size_t)d.d_model * 4);
+  // per-expert partial sums of dK / dV ([n_head][E][L][d_head]), then the router weight gradient's ([n_split][d][E])
+  l.part = take(std::max(E * (size_t)L * hd * 4, (size_t)l.n_split * d.d_model * E * 4));
   l.total = o;
   return l;
 }
@@ -283,8 +370,8 @@ int32_t dsmoe_moa_bwd(dsmoe_moa_ctx* c, const void* x, const void* w_r, const vo
   bf16_t* P = reinterpret_cast<bf16_t*>(w + sc.p);
   bf16_t* dQ = reinterpret_cast<bf16_t*>(w + sc.dq);
   float* dZ = reinterpret_cast<float*>(w + sc.dz);
-  bf16_t* dZt = reinterpret_cast<bf16_t*>(w + sc.dzt);
-  float* add = reinterpret_cast<float*>(w + sc.add);
+  float* part = reinterpret_cast<float*>(w + sc.part);
+  float* dxf = reinterpret_cast<float*>(w + sc.dxf);
   const void* zeros = w + sc.zeros;
   const long long ldp = (long long)NH * sc.Lp;
   const int pos0 = L - T;
@@ -311,7 +398,7 @@ int32_t dsmoe_moa_bwd(dsmoe_moa_ctx* c, const void* x, const void* w_r, const vo
   }
   moa_score_grad_kernel<<<dim3((unsigned)(((long)T * E + 3) / 4)), dim3(256), 0, s>>>(C, dCs, S, dS, dC, delta, T, E, NH, DH);
   MOA_TRY(hipGetLastError());
-  moa_softmax_bwd_kernel<<<dim3((T + 3) / 4), dim3(256), 0, s>>>(S, dS, T, E, sc.EP, dZ, dZt,
+  moa_softmax_bwd_kernel<<<dim3((T + 3) / 4), dim3(256), 0, s>>>(S, dS, T, E, dZ,
                                                                  reinterpret_cast<unsigned*>(w + sc.zeros));
   MOA_TRY(hipGetLastError());
   // dW_o[e] = Cs_e^T dO  (contraction over tokens)
@@ -335,12 +422,21 @@ int32_t dsmoe_moa_bwd(dsmoe_moa_ctx* c, const void* x, const void* w_r, const vo
     a.nb1 = E; a.nb2 = NH; a.M = T; a.N = L; a.K = DH; a.alpha = sl2e; a.rowv = lse; a.pos0 = pos0;
     MOA_TRY((launch_batched<false, false, false, kEpiProbs>(ic, a, s)));
   }
-  // dV_j = sum over (e, t) of P^T dC  (contraction over the stacked expert-token rows)
+  // dV_j = sum_e P_ej^T dC_ej: one contraction over tokens per (head, expert) into fp32 partial sums, added in
+  // expert order afterwards.  Tokens before the key tile's first position see none of its keys: they are left out.
+  const size_t kv_elems = (size_t)L * DH;
+  auto sum_over_experts = [&](float* out) {
+    moa_sum_parts_kernel<<<dim3((unsigned)((kv_elems / 4 + 255) / 256), NH), dim3(256), 0, s>>>(part, E, kv_elems, out);
+    return hipGetLastError();
+  };
   {
     BatchedArgs a = plain_args();
-    a.L = P; a.ldl = ldp; a.sL1 = sc.Lp; a.R = dC; a.ldr = hd; a.sR1 = DH; a.out = dv; a.ldo = DH; a.sO1 = (long long)L * DH;
-    a.nb1 = NH; a.M = L; a.N = DH; a.K = E * T; a.zeros = zeros;
+    a.L = P; a.ldl = ldp; a.sL1 = sc.Lp; a.sL2 = (long long)T * ldp;
+    a.R = dC; a.ldr = hd; a.sR1 = DH; a.sR2 = (long long)T * hd;
+    a.out = part; a.ldo = DH; a.sO1 = (long long)E * kv_elems; a.sO2 = (long long)kv_elems;
+    a.nb1 = NH; a.nb2 = E; a.M = L; a.N = DH; a.K = T; a.zeros = zeros; a.causal_k0 = 1; a.pos0 = pos0;
     MOA_TRY((launch_batched<true, true, true>(ic, a, s)));
+    MOA_TRY(sum_over_experts(dv));
   }
   // dA = P (dC V_j^T - delta) scale, in place of P
   {
@@ -360,12 +456,15 @@ int32_t dsmoe_moa_bwd(dsmoe_moa_ctx* c, const void* x, const void* w_r, const vo
     a.nb1 = E; a.nb2 = NH; a.M = T; a.N = DH; a.K = L; a.zeros = zeros; a.causal_k = 1; a.pos0 = pos0;
     MOA_TRY((launch_batched<false, true, false>(ic, a, s)));
   }
-  // dK_j = sum over (e, t) of dA^T Q
+  // dK_j = sum_e dA_ej^T Q_ej, the same way
   {
     BatchedArgs a = plain_args();
-    a.L = P; a.ldl = ldp; a.sL1 = sc.Lp; a.R = Q; a.ldr = hd; a.sR1 = DH; a.out = dk; a.ldo = DH; a.sO1 = (long long)L * DH;
-    a.nb1 = NH; a.M = L; a.N = DH; a.K = E * T; a.zeros = zeros;
+    a.L = P; a.ldl = ldp; a.sL1 = sc.Lp; a.sL2 = (long long)T * ldp;
+    a.R = Q; a.ldr = hd; a.sR1 = DH; a.sR2 = (long long)T * hd;
+    a.out = part; a.ldo = DH; a.sO1 = (long long)E * kv_elems; a.sO2 = (long long)kv_elems;
+    a.nb1 = NH; a.nb2 = E; a.M = L; a.N = DH; a.K = T; a.zeros = zeros; a.causal_k0 = 1; a.pos0 = pos0;
     MOA_TRY((launch_batched<true, true, true>(ic, a, s)));
+    MOA_TRY(sum_over_experts(dk));
   }
   // dW_q[e] = X^T dQ_e
   {
@@ -374,26 +473,27 @@ int32_t dsmoe_moa_bwd(dsmoe_moa_ctx* c, const void* x, const void* w_r, const vo
     a.nb1 = E; a.M = d; a.N = hd; a.K = T; a.zeros = zeros;
     MOA_TRY((launch_batched<true, true, true>(ic, a, s)));
   }
-  // router: dW_r = X^T dZ, db_r = sum_t dZ, and its term of dX
-  {
-    BatchedArgs a = plain_args();
-    a.L = X; a.ldl = d; a.R = dZt; a.ldr = sc.EP; a.out = dw_r; a.ldo = E; a.M = d; a.N = E; a.K = T; a.zeros = zeros;
-    MOA_TRY((launch_batched<true, true, true>(ic, a, s)));
-  }
+  // router: dW_r = X^T dZ (partial sums over token ranges, added in order), db_r = sum_t dZ, and its term of dX
+  moa_router_dw_kernel<<<dim3((d / 2 + 255) / 256, sc.n_split, E / 8), dim3(256), 0, s>>>(X, dZ, T, d, E, sc.tok_per_split, part);
+  MOA_TRY(hipGetLastError());
+  moa_sum_parts_kernel<<<dim3((unsigned)(((size_t)d * E / 4 + 255) / 256)), dim3(256), 0, s>>>(part, sc.n_split, (size_t)d * E,
+                                                                                           dw_r);
+  MOA_TRY(hipGetLastError());
   if (db_r) {
     moa_router_db_kernel<<<dim3(E), dim3(256), 0, s>>>(dZ, T, E, db_r);
     MOA_TRY(hipGetLastError());
   }
-  moa_router_dx_kernel<<<dim3(T, (d + 255) / 256), dim3(256), 0, s>>>(dZ, static_cast<const bf16_t*>(w_r), T, d, E, add);
-  MOA_TRY(hipGetLastError());
-  // dX = sum_e dQ_e W_q[e]^T + dZ W_r^T: one contraction over (expert, hd) in E segments
+  // dX = sum_e dQ_e W_q[e]^T (one contraction over (expert, hd) in E segments, fp32) + dZ W_r^T
   {
     BatchedArgs a = plain_args();
     a.L = dQ; a.ldl = hd; a.segL = (long long)T * hd;
     a.R = static_cast<const bf16_t*>(w_q); a.ldr = hd; a.segR = (long long)d * hd;
-    a.seg_k = hd; a.out = dx; a.ldo = d; a.M = T; a.N = d; a.K = E * hd; a.addend = add; a.ld_add = d;
-    MOA_TRY((launch_batched<false, false, false, kEpiAdd>(ic, a, s)));
+    a.seg_k = hd; a.out = dxf; a.ldo = d; a.M = T; a.N = d; a.K = E * hd;
+    MOA_TRY((launch_batched<false, false, true>(ic, a, s)));
   }
+  moa_router_dx_kernel<<<dim3((T + kRouterTok - 1) / kRouterTok, (d + 255) / 256), dim3(256), 0, s>>>(
+      dZ, static_cast<const bf16_t*>(w_r), T, d, E, dxf, static_cast<bf16_t*>(dx));
+  MOA_TRY(hipGetLastError());
 #undef MOA_TRY
   return DSMOE_OK;
 }
