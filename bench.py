@@ -350,9 +350,8 @@ class Bench:
                     "T": T, "selection": mode_name, "active_experts_mean": mean_union,
                     "bytes_per_call": bytes_per_call, "us_per_call_eager": ms_eager * 1e3,
                     "us_per_call_graph": ms_graph * 1e3, "us_per_call_median": ms_median * 1e3,
-                    "path": "one persistent kernel (all experts) + partial-sum reduction"
-                            if dsmoe.dense_decode_applies(layer, T, mode, k, eps) else
-                            "router + weight-streaming gate/up, down, combine kernels",
+                    "path": DECODE_PATHS[dsmoe.sparse_fwd_path(layer, T, mode, k, eps)][0],
+                    "launches": DECODE_PATHS[dsmoe.sparse_fwd_path(layer, T, mode, k, eps)][1],
                     "tokens_per_s": T / (best * 1e-3),
                     "gb_per_s": bytes_per_call / (best * 1e-3) / 1e9,
                     "frac_of_hbm_peak": bytes_per_call / (best * 1e-3) / 1e9 / PEAK_HBM_GBS,
@@ -397,7 +396,7 @@ def summarise(head, others):
             out[name] = {f'T{c["T"]}_{c["selection"]}': {
                 "us": c["us_per_call_median"], "gb_per_s": c["gb_per_s"], "frac_hbm_peak": c["frac_of_hbm_peak"],
                 "active_experts": c["active_experts_mean"], "tokens_per_s": c["tokens_per_s"],
-                "launches": 2 if c["path"].startswith("one persistent") else 5} for c in others[key]["cases"]}
+                "launches": c["launches"]} for c in others[key]["cases"]}
     if "c4" in others:
         r = others["c4"]
         out["c4"] = {"ms": r["ms_per_step"], "median_ms": r["median_ms"], "tokens_per_s": r["tokens_per_s"],
@@ -419,6 +418,15 @@ def summarise(head, others):
             return {k: rnd(x) for k, x in v.items()}
         return float(f"{v:.4g}") if isinstance(v, float) else v
     return rnd(out)
+
+
+# kernels dsmoe_sparse_fwd runs for a decode-sized call, by the library's own choice: description, launches
+DECODE_PATHS = {
+    0: ("router, dispatch, grouped GEMMs, combine", 6),
+    1: ("router + weight-streaming gate/up, down, combine kernels", 4),
+    2: ("one persistent kernel (all experts, router included) + partial-sum reduction", 2),
+    3: ("few-token kernels: router + gate/up partial sums, activation + down partial sums, reduction", 3),
+}
 
 
 def main():

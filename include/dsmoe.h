@@ -175,6 +175,16 @@ int32_t dsmoe_sparse_fwd(dsmoe_ctx* ctx, const void* x, const void* w_r, const v
  * weights of ALL experts once; 0 otherwise (also without a workspace).  Informational. */
 int32_t dsmoe_sparse_fwd_uses_persistent_kernel(const dsmoe_ctx* ctx, int32_t T, int32_t mode, int32_t k, float eps);
 
+/* Which kernels dsmoe_sparse_fwd would run for a call of T tokens with this selection (Sec. 4.4 separates the
+ * compute-bound prefill from the I/O-bound decoding; the library picks by batch size).  Informational; -1 for an
+ * invalid request or without a workspace.  All paths compute Eq. 1 on the same routing. */
+#define DSMOE_PATH_GROUPED 0     /* dispatch + grouped MFMA GEMMs + combine (prefill) */
+#define DSMOE_PATH_STREAMING 1   /* at most 128 tokens (bf16): weight-streaming MFMA kernels, K-split partial sums */
+#define DSMOE_PATH_ALL_EXPERTS 2 /* the persistent kernel of dsmoe_sparse_fwd_uses_persistent_kernel */
+#define DSMOE_PATH_FEW_TOKENS 3  /* at most 4 tokens (bf16, top-K or threshold): three kernels, router included, that
+                                  * stream the selected experts' weight rows through the vector ALUs */
+int32_t dsmoe_sparse_fwd_path(const dsmoe_ctx* ctx, int32_t T, int32_t mode, int32_t k, float eps);
+
 /* Copies the routing objects of the last dsmoe_sparse_fwd out of the workspace (any argument may be
  * NULL; after a decode-sized call whose kernels need no dispatch, the dispatch objects are derived here, on
  * `stream`, from the scores and masks that call left): probs fp32 [T,E], mask u64 [T], expert_off i32 [E+1], row_token i32 [max_rows]. */

@@ -26,7 +26,7 @@ EXPORTS = [
     "dsmoe_set_workspace", "dsmoe_set_sync_spin_limit",
     "dsmoe_poll_error", "dsmoe_route", "dsmoe_select", "dsmoe_dispatch", "dsmoe_dispatch_static", "dsmoe_expert_ffn",
     "dsmoe_combine",
-    "dsmoe_sparse_fwd", "dsmoe_sparse_fwd_routing", "dsmoe_sparse_fwd_uses_persistent_kernel", "dsmoe_dense_saved_bytes", "dsmoe_dense_fwd",
+    "dsmoe_sparse_fwd", "dsmoe_sparse_fwd_routing", "dsmoe_sparse_fwd_uses_persistent_kernel", "dsmoe_sparse_fwd_path", "dsmoe_dense_saved_bytes", "dsmoe_dense_fwd",
     "dsmoe_dense_bwd_scratch_bytes", "dsmoe_dense_bwd", "dsmoe_mi_loss", "dsmoe_dense_bwd_mi",
     "dsmoe_profile_enable", "dsmoe_profile_read", "dsmoe_bench_mfma", "dsmoe_bench_stream", "dsmoe_bench_xcc_ids",
     "dsmoe_moa_create", "dsmoe_moa_destroy", "dsmoe_moa_last_error", "dsmoe_moa_workspace_bytes",
@@ -81,6 +81,7 @@ def load_library() -> ctypes.CDLL:
         "dsmoe_sparse_fwd": (c_int32, [P, P, P, P, P, P, P, c_int32, c_int32, c_int32, c_float, P, P]),
         "dsmoe_sparse_fwd_routing": (c_int32, [P, c_int32, P, P, P, P, P]),
         "dsmoe_sparse_fwd_uses_persistent_kernel": (c_int32, [P, c_int32, c_int32, c_int32, c_float]),
+        "dsmoe_sparse_fwd_path": (c_int32, [P, c_int32, c_int32, c_int32, c_float]),
         "dsmoe_dense_saved_bytes": (c_int32, [P, c_int32, POINTER(c_size_t)]),
         "dsmoe_dense_fwd": (c_int32, [P, P, P, P, P, P, P, c_int32, P, P, P, P]),
         "dsmoe_dense_bwd_scratch_bytes": (c_int32, [P, c_int32, POINTER(c_size_t)]),
@@ -154,6 +155,14 @@ def dense_decode_applies(layer, T: int, mode: int, k: int, eps: float) -> bool:
     decides from the batch size and the selection rule; reported by the benchmark)."""
     lib = load_library()
     return bool(lib.dsmoe_sparse_fwd_uses_persistent_kernel(layer.ctx, T, mode, k, c_float(eps)))
+
+
+PATH_GROUPED, PATH_STREAMING, PATH_ALL_EXPERTS, PATH_FEW_TOKENS = 0, 1, 2, 3
+
+
+def sparse_fwd_path(layer, T: int, mode: int, k: int, eps: float) -> int:
+    """Which kernels dsmoe_sparse_fwd runs for such a call (one of the PATH_* values)."""
+    return int(load_library().dsmoe_sparse_fwd_path(layer.ctx, T, mode, k, c_float(eps)))
 
 
 def xcc_ids(blocks: int = 256):

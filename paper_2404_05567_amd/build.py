@@ -9,7 +9,7 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libdsmoe.so")
-SOURCES = ["api.hip", "router.hip", "router_stats.hip", "dispatch.hip", "expert_ffn.hip", "decode.hip", "decode_dense.hip", "dense.hip", "moa.hip", "moa_bwd.hip",
+SOURCES = ["api.hip", "router.hip", "router_stats.hip", "dispatch.hip", "expert_ffn.hip", "decode.hip", "decode_dense.hip", "decode_tiny.hip", "dense.hip", "moa.hip", "moa_bwd.hip",
            "bench_kernels.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [

@@ -60,6 +60,8 @@ WorkspaceLayout make_layout(const dsmoe_desc& d, size_t esize) {
   w.dec_p2 = take(dec_rows * d.d_model * 4);
   w.dec_ht = take((d.dtype == DSMOE_BF16 ? (size_t)std::min<int64_t>(d.max_tokens, kDecodeMaxTokens) : 0) * E * d.d_ff * 2);
   w.dec_sync = take(kDenseSyncTotalWords * 4);
+  w.tiny_p1 = take(decode_tiny_p1_bytes(d));
+  w.tiny_p2 = take(decode_tiny_p2_bytes(d));
   w.total = o;
   return w;
 }
@@ -396,6 +398,12 @@ int32_t dsmoe_sparse_fwd(dsmoe_ctx* c, const void* x, const void* w_r, const voi
     c->routing_pending_T = T;
     return DSMOE_OK;
   }
+  if (decode_tiny_applies(c, T, mode)) {
+    // a handful of tokens: three kernels, router included, that stream the selected experts' weight rows
+    HIP_TRY(c, launch_decode_tiny(c, x, w_r, b_r, w_gate, w_up, w_down, T, mode, k, eps, out, s));
+    c->routing_pending_T = T;
+    return DSMOE_OK;
+  }
   if (mode == DSMOE_SEL_THRESHOLD_TOPK) {
     int32_t* k_dev = reinterpret_cast<int32_t*>(w + c->ws.k_dev);
     HIP_TRY(c, launch_route(c, x, w_r, b_r, T, probs, DSMOE_SEL_THRESHOLD, 0, eps, mask, cnt_tok, s));
@@ -424,6 +432,19 @@ int32_t dsmoe_sparse_fwd_uses_persistent_kernel(const dsmoe_ctx* c, int32_t T, i
     eps = eps / static_cast<float>(c->desc.n_experts);
   }
   return decode_dense_applies(c, T, mode, k, eps) ? 1 : 0;
+}
+
+int32_t dsmoe_sparse_fwd_path(const dsmoe_ctx* c, int32_t T, int32_t mode, int32_t k, float eps) {
+  if (!c || !c->workspace || T < 0 || T > c->desc.max_tokens) return -1;
+  if (mode & DSMOE_SEL_NORMALISED) {
+    mode &= ~DSMOE_SEL_NORMALISED;
+    eps = eps / static_cast<float>(c->desc.n_experts);
+  }
+  if (mode != DSMOE_SEL_TOPK && mode != DSMOE_SEL_THRESHOLD && mode != DSMOE_SEL_THRESHOLD_TOPK) return -1;
+  if (decode_dense_applies(c, T, mode, k, eps)) return DSMOE_PATH_ALL_EXPERTS;
+  if (decode_tiny_applies(c, T, mode)) return DSMOE_PATH_FEW_TOKENS;
+  if (c->desc.dtype == DSMOE_BF16 && T >= 1 && T <= kDecodeMaxTokens) return DSMOE_PATH_STREAMING;
+  return DSMOE_PATH_GROUPED;
 }
 
 int32_t dsmoe_sparse_fwd_routing(dsmoe_ctx* c, int32_t T, float* probs, uint64_t* mask, int32_t* expert_off,

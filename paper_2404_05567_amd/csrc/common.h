@@ -65,6 +65,8 @@ struct WorkspaceLayout {
   size_t dec_p2;      // f32 [decode_row_cap][d]        K-chunk partial sums of the down projection
   size_t dec_ht;      // bf16 [min(max_tokens, 128)][E f]   weighted hidden activations of the all-expert decode kernel
   size_t dec_sync;    // i32 [kDenseSyncWords]: counters of the all-expert decode kernel; zero between calls
+  size_t tiny_p1;     // f32 [2 * 256][min(max_tokens, 4)][2 f]   partial gate | up sums of the few-token kernels
+  size_t tiny_p2;     // f32 [256][min(max_tokens, 4)][d]         their partial outputs
   size_t total;
 };
 
@@ -141,6 +143,13 @@ hipError_t launch_decode_fwd(const dsmoe_ctx* c, const void* x, const void* w_ga
 // decode_dense.hip: the whole sparse forward (router included) for decode-sized batches that select nearly
 // every expert; leaves scores and masks in the workspace
 bool decode_dense_applies(const dsmoe_ctx* c, int T, int mode, int k, float eps);
+// decode_tiny.hip: at most 4 tokens, router included, weights streamed through the vector ALUs
+size_t decode_tiny_p1_bytes(const dsmoe_desc& d);
+size_t decode_tiny_p2_bytes(const dsmoe_desc& d);
+bool decode_tiny_applies(const dsmoe_ctx* c, int T, int mode);
+hipError_t launch_decode_tiny(const dsmoe_ctx* c, const void* x, const void* w_r, const void* b_r, const void* w_gate,
+                              const void* w_up, const void* w_down, int T, int mode, int k, float eps, void* out,
+                              hipStream_t s);
 hipError_t launch_decode_dense(const dsmoe_ctx* c, const void* x, const void* w_r, const void* b_r, const void* w_gate,
                                const void* w_up, const void* w_down, int T, int mode, int k, float eps, void* out,
                                hipStream_t s);

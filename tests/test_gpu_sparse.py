@@ -545,3 +545,70 @@ def test_largest_layer_of_the_paper(torch, dsmoe, T):
     cfg = gen.LayerConfig(f"ds_moe_19b_T{T}", 15, T=T, d=7168, E=32, f=896, dtype="bf16", mode="topk", k=4,
                           router_std=1.5 / np.sqrt(7168))
     full_size_check(torch, dsmoe, cfg.name, n_sample=min(T, 64), max_rows=4 * T, cfg=cfg)
+
+
+# --------------------------------------------------------------------------------------------------
+# at most 4 tokens: the three few-token kernels (router included, weight rows through the vector ALUs)
+# --------------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("T,d,E,f,mode,k,eps,expert", [
+    (1, 2048, 32, 512, "topk", 4, 0.0, "swiglu"),
+    (1, 2048, 32, 512, "topk", 1, 0.0, "swiglu"),          # one active expert: its rows spread over every block
+    (2, 7168, 32, 896, "threshold", 0, 0.03, "swiglu"),    # the largest layer of the paper: two chunks of a W_down row per thread
+    (3, 2048, 32, 512, "threshold", 0, 0.02, "swiglu"),
+    (4, 256, 64, 64, "topk", 2, 0.0, "swiglu"),            # 64 experts, narrow rows: many rows per pass
+    (3, 512, 8, 4096, "topk", 1, 0.0, "swiglu"),           # one weight row per pass
+    (4, 4096, 16, 128, "topk", 3, 0.0, "swiglu"),
+    (4, 1024, 16, 256, "topk", 2, 0.0, "gelu"),
+    (2, 1024, 16, 256, "threshold", 0, 0.05, "gelu"),
+])
+def test_few_token_kernels(torch, dsmoe, T, d, E, f, mode, k, eps, expert):
+    cfg = gen.LayerConfig("few", 19, T=T, d=d, E=E, f=f, dtype="bf16", mode=mode, k=k, eps=eps,
+                          router_std=1.5 / np.sqrt(d))
+    inp = conditioned(cfg, mode, k, eps, variant=T)
+    if expert == "gelu":
+        inp.w_up = None
+    say(f"[case] few tokens T={T} d={d} E={E} f={f} {mode} k={k} eps={eps} {expert}")
+    w = weights_to_dev(torch, inp)
+    layer = dsmoe.Layer(d, f, E, "bf16", max_tokens=T, expert=expert)
+    code = mode_code(dsmoe, mode)
+    assert dsmoe.sparse_fwd_path(layer, T, code, k, eps) == dsmoe.PATH_FEW_TOKENS
+    args = (w["x"], w["w_r"], w["b_r"], w["w_gate"], w["w_up"], w["w_down"], code, k, eps)
+    out = layer.sparse_fwd(*args).clone()
+    assert layer.poll_error() == dsmoe.OK
+    probs, mask, eo, rt = layer.sparse_fwd_routing(T)
+    torch.cuda.synchronize()
+    O_ref, S_ref, M_ref = orc.sparse_forward(inp.x, inp.w_r, inp.b_r, inp.w_gate, inp.w_up, inp.w_down, mode, k, eps)
+    assert helpers.rel_err(probs.cpu().numpy(), S_ref) <= 1e-5
+    np.testing.assert_array_equal(mask_to_bool(mask, E), M_ref)
+    r_ref = orc.dispatch(M_ref, S_ref)
+    np.testing.assert_array_equal(eo.cpu().numpy(), r_ref.expert_off)
+    np.testing.assert_array_equal(rt.cpu().numpy()[:r_ref.nnz], r_ref.row_token)
+    err = helpers.rel_err(out.float().cpu().numpy(), O_ref)
+    say(f"  rel err {err:.3e}")
+    assert err <= TOL["bf16"]
+    for _ in range(2):                                         # bitwise reproducible
+        assert torch.equal(layer.sparse_fwd(*args), out)
+
+
+def test_few_token_kernels_threshold_nobody_reaches_and_overflow(torch, dsmoe):
+    cfg = gen.CONFIGS["c3"].with_(T=4, E=32)
+    inp = gen.make_layer(cfg, 3)
+    w = weights_to_dev(torch, inp)
+    layer = dsmoe.Layer(cfg.d, cfg.f, cfg.E, "bf16", max_tokens=4)
+    # a threshold no score reaches: every token keeps its best expert alone
+    out = layer.sparse_fwd(w["x"], w["w_r"], None, w["w_gate"], w["w_up"], w["w_down"], dsmoe.SEL_THRESHOLD, 0, 0.99)
+    assert layer.poll_error() == dsmoe.OK
+    _, mask, _, _ = layer.sparse_fwd_routing(4)
+    O, S, M = orc.sparse_forward(inp.x, inp.w_r, None, inp.w_gate, inp.w_up, inp.w_down, "threshold", 0, 0.99)
+    assert (M.sum(axis=1) == 1).all()
+    np.testing.assert_array_equal(mask_to_bool(mask, cfg.E), M)
+    assert helpers.rel_err(out.float().cpu().numpy(), O) <= TOL["bf16"]
+    # more selected pairs than rows: reported, output zero, and the next call is fine
+    small = dsmoe.Layer(cfg.d, cfg.f, cfg.E, "bf16", max_tokens=4, max_rows=10)
+    out = small.sparse_fwd(w["x"], w["w_r"], None, w["w_gate"], w["w_up"], w["w_down"], dsmoe.SEL_TOPK, 4, 0.0)
+    assert small.poll_error() == dsmoe.ERR_CAPACITY
+    assert float(out.float().abs().max().item()) == 0.0
+    out = small.sparse_fwd(w["x"], w["w_r"], None, w["w_gate"], w["w_up"], w["w_down"], dsmoe.SEL_TOPK, 2, 0.0)
+    assert small.poll_error() == dsmoe.OK
+    O, _, _ = orc.sparse_forward(inp.x, inp.w_r, None, inp.w_gate, inp.w_up, inp.w_down, "topk", 2)
+    assert helpers.rel_err(out.float().cpu().numpy(), O) <= TOL["bf16"]
