@@ -160,7 +160,9 @@ BatchedArgs plain_args() {
 
 // One wave per (token, expert): grad S = <C, dCs> (Eq. 3), dC = S dCs in the [E][T][hd] layout of Q, and the
 // per-head terms delta = <dC, C> of the softmax backward.
-__global__ void __launch_bounds__(256) moa_score_grad_kernel(const bf16_t* __restrict__ C, const bf16_t* __restrict__ dCs,
+// dCs arrives as n_part fp32 partial sums (K split of its product), part_stride values apart.
+__global__ void __launch_bounds__(256) moa_score_grad_kernel(const bf16_t* __restrict__ C, const float* __restrict__ dCs,
+                                                            int n_part, size_t part_stride,
                                                             const float* __restrict__ S, float* __restrict__ dS,
                                                             bf16_t* __restrict__ dC, float* __restrict__ delta, int T,
                                                             int E, int NH, int DH) {
@@ -170,13 +172,15 @@ __global__ void __launch_bounds__(256) moa_score_grad_kernel(const bf16_t* __res
   const int t = (int)(w / E), e = (int)(w % E), hd = NH * DH;
   const float s = S[(size_t)t * E + e];
   const bf16_t* c = C + ((size_t)t * E + e) * hd;
-  const bf16_t* g = dCs + ((size_t)t * E + e) * hd;
+  const float* g = dCs + ((size_t)t * E + e) * hd;
   bf16_t* o = dC + ((size_t)e * T + t) * hd;
   float total = 0.f;
   for (int j = 0; j < NH; ++j) {
     float part = 0.f;
     for (int i = lane; i < DH; i += 64) {
-      const float cv = (float)c[j * DH + i], gv = (float)g[j * DH + i];
+      const float cv = (float)c[j * DH + i];
+      float gv = g[j * DH + i];
+      if (n_part == 2) gv += g[part_stride + j * DH + i];
       part = fmaf(cv, gv, part);
       o[j * DH + i] = (bf16_t)(s * gv);
     }
@@ -209,7 +213,7 @@ __global__ void __launch_bounds__(256) moa_softmax_bwd_kernel(const float* __res
 constexpr int kRouterTok = 32;
 __global__ void __launch_bounds__(256) moa_router_dx_kernel(const float* __restrict__ dZ, const bf16_t* __restrict__ w_r, int T,
                                                            int d, int E, const float* __restrict__ dxf,
-                                                           bf16_t* __restrict__ dx) {
+                                                           int n_part, bf16_t* __restrict__ dx) {
   const int n = blockIdx.y * 256 + threadIdx.x, t0 = blockIdx.x * kRouterTok;
   if (n >= d) return;
   float w[kMaxExperts];
@@ -223,6 +227,7 @@ __global__ void __launch_bounds__(256) moa_router_dx_kernel(const float* __restr
   for (int t = t0; t < min(T, t0 + kRouterTok); ++t) {
     const float* z = dZ + (size_t)t * E;
     float acc = dxf[(size_t)t * d + n];
+    if (n_part == 2) acc += dxf[(size_t)T * d + (size_t)t * d + n];
 #pragma unroll
     for (int c = 0; c < kMaxExperts / 8; ++c)
       if (8 * c < E) {
@@ -308,14 +313,14 @@ BwdScratch bwd_scratch(const dsmoe_moa_desc& d, int T, int L) {
   size_t o = 0;
   auto take = [&](size_t bytes) { const size_t at = o; o = al256(o + bytes); return at; };
   l.zeros = take(256);
-  l.dcs = take(Tn * E * hd * 2);
+  l.dcs = take(2 * Tn * E * hd * 4);            // two K halves in fp32
   l.dc = take(E * Tn * hd * 2);
   l.delta = take(E * d.n_head * Tn * 4);
   l.ds = take(Tn * E * 4);
   l.p = take(E * Tn * d.n_head * (size_t)l.Lp * 2);
   l.dq = take(E * Tn * hd * 2);
   l.dz = take(Tn * E * 4);
-  l.dxf = take(Tn * (size_t)d.d_model * 4);
+  l.dxf = take(2 * Tn * (size_t)d.d_model * 4);
   // per-expert partial sums of dK / dV ([n_head][E][L][d_head]), then the router weight gradient's ([n_split][d][E])
   l.part = take(std::max(E * (size_t)L * hd * 4, (size_t)l.n_split * d.d_model * E * 4));
   l.total = o;
@@ -363,7 +368,7 @@ int32_t dsmoe_moa_bwd(dsmoe_moa_ctx* c, const void* x, const void* w_r, const vo
   const bf16_t* Cs = reinterpret_cast<const bf16_t*>(c->workspace + c->o_cs);
   const bf16_t* C = reinterpret_cast<const bf16_t*>(c->workspace + c->o_c);
   const float* lse = reinterpret_cast<const float*>(c->workspace + c->o_lse);
-  bf16_t* dCs = reinterpret_cast<bf16_t*>(w + sc.dcs);
+  float* dCs = reinterpret_cast<float*>(w + sc.dcs);
   bf16_t* dC = reinterpret_cast<bf16_t*>(w + sc.dc);
   float* delta = reinterpret_cast<float*>(w + sc.delta);
   float* dS = reinterpret_cast<float*>(w + sc.ds);
@@ -389,14 +394,20 @@ int32_t dsmoe_moa_bwd(dsmoe_moa_ctx* c, const void* x, const void* w_r, const vo
     }                                                                                                \
   } while (0)
 
+  // The two products with only T x d or T x E hd outputs are cut in two K halves when their tiles would leave half
+  // the CUs idle; the halves are fp32 partial sums that the next kernel adds.
+  auto k_halves = [&](long m, long n) { return 2 * ((m + 255) / 256) * ((n + 255) / 256) <= ic->n_cu ? 2 : 1; };
   // dCs = dO W_o^T  ([T, d] x [E hd, d]^T)
+  const int ks_c = k_halves(T, (long)E * hd);
   {
     BatchedArgs a = plain_args();
-    a.L = dO; a.ldl = d; a.R = static_cast<const bf16_t*>(w_o); a.ldr = d; a.out = dCs; a.ldo = (long long)E * hd;
-    a.M = T; a.N = E * hd; a.K = d;
-    MOA_TRY((launch_batched<false, false, false>(ic, a, s)));
+    a.L = dO; a.ldl = d; a.sL2 = d / ks_c; a.R = static_cast<const bf16_t*>(w_o); a.ldr = d; a.sR2 = d / ks_c;
+    a.out = dCs; a.ldo = (long long)E * hd; a.sO2 = (long long)T * E * hd;
+    a.nb2 = ks_c; a.M = T; a.N = E * hd; a.K = d / ks_c;
+    MOA_TRY((launch_batched<false, false, true>(ic, a, s)));
   }
-  moa_score_grad_kernel<<<dim3((unsigned)(((long)T * E + 3) / 4)), dim3(256), 0, s>>>(C, dCs, S, dS, dC, delta, T, E, NH, DH);
+  moa_score_grad_kernel<<<dim3((unsigned)(((long)T * E + 3) / 4)), dim3(256), 0, s>>>(C, dCs, ks_c, (size_t)T * E * hd, S, dS, dC,
+                                                                                  delta, T, E, NH, DH);
   MOA_TRY(hipGetLastError());
   moa_softmax_bwd_kernel<<<dim3((T + 3) / 4), dim3(256), 0, s>>>(S, dS, T, E, dZ,
                                                                  reinterpret_cast<unsigned*>(w + sc.zeros));
@@ -484,15 +495,18 @@ int32_t dsmoe_moa_bwd(dsmoe_moa_ctx* c, const void* x, const void* w_r, const vo
     MOA_TRY(hipGetLastError());
   }
   // dX = sum_e dQ_e W_q[e]^T (one contraction over (expert, hd) in E segments, fp32) + dZ W_r^T
+  const int ks_x = k_halves(T, d);
   {
     BatchedArgs a = plain_args();
     a.L = dQ; a.ldl = hd; a.segL = (long long)T * hd;
     a.R = static_cast<const bf16_t*>(w_q); a.ldr = hd; a.segR = (long long)d * hd;
-    a.seg_k = hd; a.out = dxf; a.ldo = d; a.M = T; a.N = d; a.K = E * hd;
+    a.seg_k = hd; a.out = dxf; a.ldo = d; a.M = T; a.N = d;
+    a.nb2 = ks_x; a.K = E / ks_x * hd; a.sL2 = (long long)(E / ks_x) * a.segL; a.sR2 = (long long)(E / ks_x) * a.segR;
+    a.sO2 = (long long)T * d;
     MOA_TRY((launch_batched<false, false, true>(ic, a, s)));
   }
   moa_router_dx_kernel<<<dim3((T + kRouterTok - 1) / kRouterTok, (d + 255) / 256), dim3(256), 0, s>>>(
-      dZ, static_cast<const bf16_t*>(w_r), T, d, E, dxf, static_cast<bf16_t*>(dx));
+      dZ, static_cast<const bf16_t*>(w_r), T, d, E, dxf, ks_x, static_cast<bf16_t*>(dx));
   MOA_TRY(hipGetLastError());
 #undef MOA_TRY
   return DSMOE_OK;
