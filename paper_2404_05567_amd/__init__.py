@@ -11,7 +11,10 @@ import os
 from ctypes import POINTER, byref, c_char_p, c_float, c_int32, c_int64, c_size_t, c_void_p
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_PKG, "libdsmoe.so")
+# DSMOE_LIBRARY names another build of the same sources to load instead (the conservative-waits build that a GPU test
+# compares the library with); by default the in-tree libdsmoe.so.
+LIB_PATH = os.environ.get("DSMOE_LIBRARY") or os.path.join(_PKG, "libdsmoe.so")
+LIB_CHECKED_PATH = os.path.join(_PKG, "libdsmoe_checked.so")
 
 F32, BF16 = 0, 1
 SEL_TOPK, SEL_THRESHOLD, SEL_THRESHOLD_TOPK = 0, 1, 2

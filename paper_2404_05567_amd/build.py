@@ -9,6 +9,8 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libdsmoe.so")
+# the same sources with every hand-counted wait replaced by a full wait (what a GPU test compares the library with)
+LIB_CHECKED = os.path.join(PKG, "libdsmoe_checked.so")
 SOURCES = ["api.hip", "router.hip", "router_stats.hip", "dispatch.hip", "expert_ffn.hip", "decode.hip", "decode_dense.hip", "decode_tiny.hip", "dense.hip", "moa.hip", "moa_bwd.hip",
            "bench_kernels.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
@@ -48,5 +50,14 @@ def build(verbose: bool = True, extra_flags=(), lib_path: str = LIB, obj_dir: st
     return lib_path
 
 
+def build_checked(verbose: bool = True) -> str:
+    """The conservative-waits build of the same sources (objects under csrc/checked/)."""
+    obj_dir = os.path.join(CSRC, "checked")
+    os.makedirs(obj_dir, exist_ok=True)
+    return build(verbose, extra_flags=("-DDSMOE_CONSERVATIVE_WAITS",), lib_path=LIB_CHECKED, obj_dir=obj_dir)
+
+
 if __name__ == "__main__":
     build(extra_flags=sys.argv[1:])
+    if not sys.argv[1:]:
+        build_checked()

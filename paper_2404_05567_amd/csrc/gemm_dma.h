@@ -83,26 +83,39 @@ __device__ __forceinline__ u32x2 lds_read_tr16(const lds_char* p) {
 // round trip per row block.  The caller guarantees that no load in flight targets the bytes read (the epilogues
 // use the wave's own slices of the last two stages, loads in flight go to the first ones).  LDS operations of a
 // wave execute in order, so the reads see the wave's earlier writes.
+//
+// -DDSMOE_CONSERVATIVE_WAITS builds the same sources with none of these assumptions: every counted wait becomes a
+// wait for ALL vector-memory and LDS operations of the wave, and the accessors below first wait for everything in
+// flight.  Slower, but independent of how many loads are in flight where.  Every sum in the library has a fixed
+// order, so the two builds must agree bit for bit; a GPU test compares them.
+#ifdef DSMOE_CONSERVATIVE_WAITS
+#define DSMOE_FREE_PREFIX "s_waitcnt vmcnt(0) lgkmcnt(0)\n\t"
+constexpr bool kConservativeWaits = true;
+#else
+#define DSMOE_FREE_PREFIX ""
+constexpr bool kConservativeWaits = false;
+#endif
 __device__ __forceinline__ u32x4 lds_read16_free(const lds_char* p) {
   u32x4 v;
-  asm volatile("ds_read_b128 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=v"(v) : "v"(p) : "memory");
+  asm volatile(DSMOE_FREE_PREFIX "ds_read_b128 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=v"(v) : "v"(p) : "memory");
   return v;
 }
 __device__ __forceinline__ void lds_write8_free(lds_char* p, u32x2 v) {
-  asm volatile("ds_write_b64 %0, %1" : : "v"(p), "v"(v) : "memory");
+  asm volatile(DSMOE_FREE_PREFIX "ds_write_b64 %0, %1" : : "v"(p), "v"(v) : "memory");
 }
 __device__ __forceinline__ void lds_write16_free(lds_char* p, u32x4 v) {
-  asm volatile("ds_write_b128 %0, %1" : : "v"(p), "v"(v) : "memory");
+  asm volatile(DSMOE_FREE_PREFIX "ds_write_b128 %0, %1" : : "v"(p), "v"(v) : "memory");
 }
 __device__ __forceinline__ void lds_read16x2_free(const lds_char* p0, const lds_char* p1, u32x4& a, u32x4& b) {
-  asm volatile("ds_read_b128 %0, %2\n\tds_read_b128 %1, %3\n\ts_waitcnt lgkmcnt(0)"
+  asm volatile(DSMOE_FREE_PREFIX "ds_read_b128 %0, %2\n\tds_read_b128 %1, %3\n\ts_waitcnt lgkmcnt(0)"
                : "=&v"(a), "=&v"(b) : "v"(p0), "v"(p1) : "memory");
 }
 
 // s_waitcnt on the vector-memory counter alone (N outstanding loads allowed), optionally also on all LDS reads
 template <int N, bool LGKM0>
 __device__ __forceinline__ void wait_vm() {
-  __builtin_amdgcn_s_waitcnt((N & 0xF) | ((N >> 4) << 14) | (7 << 4) | ((LGKM0 ? 0 : 15) << 8));
+  if constexpr (kConservativeWaits) __builtin_amdgcn_s_waitcnt(7 << 4);   // vmcnt(0) lgkmcnt(0)
+  else __builtin_amdgcn_s_waitcnt((N & 0xF) | ((N >> 4) << 14) | (7 << 4) | ((LGKM0 ? 0 : 15) << 8));
 }
 
 // The thread index as a value the compiler cannot trace back to threadIdx: what is derived from it is
