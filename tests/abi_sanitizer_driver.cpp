@@ -69,6 +69,8 @@ int main() {
   EXPECT(dsmoe_select(c, ff, 0, DSMOE_SEL_THRESHOLD, 0, 0.1f, fu, nullptr, nullptr), DSMOE_OK);
   EXPECT(dsmoe_sparse_fwd(c, fake, fake, nullptr, fake, fake, fake, 4, DSMOE_SEL_TOPK, 2, 0.f, fake, nullptr), DSMOE_ERR_WORKSPACE);
   EXPECT(dsmoe_sparse_fwd_uses_persistent_kernel(c, 32, DSMOE_SEL_TOPK, 4, 0.f), 0);
+  EXPECT(dsmoe_sparse_fwd_path(c, 32, DSMOE_SEL_TOPK, 4, 0.f), -1);          // no workspace yet
+  EXPECT(dsmoe_sparse_fwd_path(nullptr, 32, DSMOE_SEL_TOPK, 4, 0.f), -1);
   EXPECT(dsmoe_expert_ffn(c, fake, nullptr, fi, fi, fake, fake, fake, fake, nullptr), DSMOE_ERR_WORKSPACE);
   EXPECT(dsmoe_combine(c, nullptr, ff, fi, fi, 4, fake, nullptr), DSMOE_ERR_INVALID_ARG);
   EXPECT(dsmoe_combine(c, fake, ff, fi, fi, 0, fake, nullptr), DSMOE_OK);
@@ -137,6 +139,23 @@ int main() {
   EXPECT(dsmoe_moa_fwd(m, fake, fake, nullptr, fake, fake, fake, fake, 4, 8, DSMOE_SEL_TOPK, 2, 0.f, NAN, fake, nullptr),
          DSMOE_ERR_INVALID_ARG);
   EXPECT(dsmoe_moa_fwd(m, fake, fake, nullptr, fake, fake, fake, fake, 0, 8, DSMOE_SEL_TOPK, 2, 0.f, 1.f, fake, nullptr), DSMOE_OK);
+  // backward: size query, and every refusal that happens on the host
+  size_t sb = 0;
+  EXPECT(dsmoe_moa_bwd_scratch_bytes(m, 4, 8, &sb), DSMOE_OK);
+  EXPECT(sb > 0, 1);
+  EXPECT(dsmoe_moa_bwd_scratch_bytes(m, 4, 8, nullptr), DSMOE_ERR_INVALID_ARG);
+  EXPECT(dsmoe_moa_bwd_scratch_bytes(m, 9, 8, &sb), DSMOE_ERR_INVALID_ARG);
+  EXPECT(dsmoe_moa_bwd(nullptr, fake, fake, fake, fake, fake, fake, fake, 4, 8, 1.f, fake, fake, ff, nullptr, ff, ff, ff, ff, nullptr),
+         DSMOE_ERR_INVALID_ARG);
+  EXPECT(dsmoe_moa_bwd(m, fake, fake, fake, fake, fake, fake, fake, 0, 8, 1.f, fake, fake, ff, nullptr, ff, ff, ff, ff, nullptr),
+         DSMOE_ERR_INVALID_ARG);
+  EXPECT(dsmoe_moa_bwd(m, fake, fake, fake, fake, fake, fake, fake, 4, 3, 1.f, fake, fake, ff, nullptr, ff, ff, ff, ff, nullptr),
+         DSMOE_ERR_INVALID_ARG);
+  EXPECT(dsmoe_moa_bwd(m, fake, fake, fake, fake, fake, fake, fake, 4, 8, INFINITY, fake, fake, ff, nullptr, ff, ff, ff, ff, nullptr),
+         DSMOE_ERR_INVALID_ARG);
+  EXPECT(dsmoe_moa_bwd(m, fake, fake, fake, fake, fake, fake, fake, 4, 8, 1.f, fake, fake, ff, nullptr, ff, ff, ff, ff, nullptr),
+         DSMOE_ERR_INVALID_ARG);   // no dense forward came before
+  EXPECT(std::strstr(dsmoe_moa_last_error(m), "dsmoe_moa_fwd") != nullptr, 1);
   EXPECT(dsmoe_moa_destroy(m), DSMOE_OK);
 
   if (failures) {
