@@ -612,3 +612,41 @@ def test_few_token_kernels_threshold_nobody_reaches_and_overflow(torch, dsmoe):
     assert small.poll_error() == dsmoe.OK
     O, _, _ = orc.sparse_forward(inp.x, inp.w_r, None, inp.w_gate, inp.w_up, inp.w_down, "topk", 2)
     assert helpers.rel_err(out.float().cpu().numpy(), O) <= TOL["bf16"]
+
+
+def test_few_token_kernels_with_router_bias_and_smallest_layer(torch, dsmoe):
+    """A skewed router (bias per expert) through the in-kernel router, and the smallest layer the library accepts."""
+    for T, d, E, f, zipf in ((3, 1024, 32, 256, 1.5), (2, 64, 8, 64, 0.0), (4, 64, 64, 64, 2.0)):
+        cfg = gen.LayerConfig("few_bias", 24, T=T, d=d, E=E, f=f, dtype="bf16", mode="topk", k=2, eps=0.0,
+                              router_std=1.0 / np.sqrt(d), zipf_s=zipf)
+        inp = conditioned(cfg, "topk", 2, 0.0, variant=T)
+        assert (inp.b_r is not None) == (zipf > 0)
+        w = weights_to_dev(torch, inp)
+        layer = dsmoe.Layer(d, f, E, "bf16", max_tokens=T)
+        assert dsmoe.sparse_fwd_path(layer, T, dsmoe.SEL_TOPK, 2, 0.0) == dsmoe.PATH_FEW_TOKENS
+        out = layer.sparse_fwd(w["x"], w["w_r"], w["b_r"], w["w_gate"], w["w_up"], w["w_down"], dsmoe.SEL_TOPK, 2, 0.0)
+        assert layer.poll_error() == dsmoe.OK
+        _, mask, _, _ = layer.sparse_fwd_routing(T)
+        O, S, M = orc.sparse_forward(inp.x, inp.w_r, inp.b_r, inp.w_gate, inp.w_up, inp.w_down, "topk", 2, 0.0)
+        np.testing.assert_array_equal(mask_to_bool(mask, E), M)
+        assert helpers.rel_err(out.float().cpu().numpy(), O) <= TOL["bf16"]
+
+
+def test_the_library_reports_which_kernels_a_call_would_run(torch, dsmoe):
+    cfg = gen.CONFIGS["c3"]
+    layer = dsmoe.Layer(cfg.d, cfg.f, cfg.E, "bf16", max_tokens=4096)
+    path = lambda T, mode, k, eps: dsmoe.sparse_fwd_path(layer, T, mode, k, eps)
+    assert path(1, dsmoe.SEL_TOPK, 4, 0.0) == dsmoe.PATH_FEW_TOKENS
+    assert path(4, dsmoe.SEL_THRESHOLD, 0, 0.02) == dsmoe.PATH_FEW_TOKENS
+    assert path(4, dsmoe.SEL_THRESHOLD_TOPK, 0, 0.02) == dsmoe.PATH_STREAMING     # the few-token kernels route themselves
+    assert path(8, dsmoe.SEL_TOPK, 4, 0.0) == dsmoe.PATH_STREAMING
+    assert path(8, dsmoe.SEL_THRESHOLD, 0, 0.02) == dsmoe.PATH_ALL_EXPERTS
+    assert path(8, dsmoe.SEL_THRESHOLD | dsmoe.SEL_NORMALISED, 0, 0.64) == dsmoe.PATH_ALL_EXPERTS
+    assert path(32, dsmoe.SEL_TOPK, 4, 0.0) == dsmoe.PATH_ALL_EXPERTS
+    assert path(64, dsmoe.SEL_TOPK, 1, 0.0) == dsmoe.PATH_STREAMING               # too many experts stay idle
+    assert path(128, dsmoe.SEL_TOPK, 4, 0.0) == dsmoe.PATH_STREAMING
+    assert path(129, dsmoe.SEL_TOPK, 4, 0.0) == dsmoe.PATH_GROUPED
+    assert path(0, dsmoe.SEL_TOPK, 4, 0.0) == dsmoe.PATH_GROUPED
+    assert path(5000, dsmoe.SEL_TOPK, 4, 0.0) == -1 and path(8, 77, 4, 0.0) == -1
+    f32 = dsmoe.Layer(256, 64, 8, "f32", max_tokens=64)
+    assert dsmoe.sparse_fwd_path(f32, 1, dsmoe.SEL_TOPK, 2, 0.0) == dsmoe.PATH_GROUPED
