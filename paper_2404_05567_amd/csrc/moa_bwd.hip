@@ -159,7 +159,8 @@ BatchedArgs plain_args() {
 }
 
 // One wave per (token, expert): grad S = <C, dCs> (Eq. 3), dC = S dCs in the [E][T][hd] layout of Q, and the
-// per-head terms delta = <dC, C> of the softmax backward.
+// per-head terms delta = <dC, C> of the softmax backward.  A lane owns 8 consecutive values; the d_head / 8 lanes
+// of a head add up along a fixed shuffle tree.
 // dCs arrives as n_part fp32 partial sums (K split of its product), part_stride values apart.
 __global__ void __launch_bounds__(256) moa_score_grad_kernel(const bf16_t* __restrict__ C, const float* __restrict__ dCs,
                                                             int n_part, size_t part_stride,
@@ -169,25 +170,37 @@ __global__ void __launch_bounds__(256) moa_score_grad_kernel(const bf16_t* __res
   const int lane = threadIdx.x & 63;
   const long w = (long)blockIdx.x * 4 + (threadIdx.x >> 6);
   if (w >= (long)T * E) return;
-  const int t = (int)(w / E), e = (int)(w % E), hd = NH * DH;
+  const int t = (int)(w / E), e = (int)(w % E), hd = NH * DH, lph = DH / 8;     // lanes per head: 8 or 16
   const float s = S[(size_t)t * E + e];
   const bf16_t* c = C + ((size_t)t * E + e) * hd;
   const float* g = dCs + ((size_t)t * E + e) * hd;
   bf16_t* o = dC + ((size_t)e * T + t) * hd;
   float total = 0.f;
-  for (int j = 0; j < NH; ++j) {
+  for (int c0 = 0; c0 < hd; c0 += 512) {                 // 64 lanes x 8 values per pass
+    const int i = c0 + 8 * lane;
     float part = 0.f;
-    for (int i = lane; i < DH; i += 64) {
-      const float cv = (float)c[j * DH + i];
-      float gv = g[j * DH + i];
-      if (n_part == 2) gv += g[part_stride + j * DH + i];
-      part = fmaf(cv, gv, part);
-      o[j * DH + i] = (bf16_t)(s * gv);
-    }
+    if (i < hd) {
+      float cv[8], gv[8], gw[8], ov[8];
+      load_chunk(c + i, cv);
+      load_chunk(g + i, gv);
+      if (n_part == 2) {
+        load_chunk(g + part_stride + i, gw);
 #pragma unroll
-    for (int sft = 32; sft > 0; sft >>= 1) part += __shfl_xor(part, sft, 64);
-    if (lane == 0) delta[((size_t)e * NH + j) * T + t] = s * part;
-    total += part;
+        for (int k = 0; k < 8; ++k) gv[k] += gw[k];
+      }
+#pragma unroll
+      for (int k = 0; k < 8; ++k) {
+        part = fmaf(cv[k], gv[k], part);
+        ov[k] = s * gv[k];
+      }
+      store_chunk(o + i, ov);
+    }
+    for (int sft = 1; sft < lph; sft <<= 1) part += __shfl_xor(part, sft, 64);   // the lanes of one head
+    if (i < hd && lane % lph == 0) delta[((size_t)e * NH + i / DH) * T + t] = s * part;
+    float all = lane % lph == 0 ? part : 0.f;                                     // one value per head
+#pragma unroll
+    for (int sft = 32; sft > 0; sft >>= 1) all += __shfl_xor(all, sft, 64);
+    total += all;
   }
   if (lane == 0) dS[(size_t)t * E + e] = total;
 }
@@ -248,6 +261,7 @@ __global__ void __launch_bounds__(256) moa_router_dw_kernel(const bf16_t* __rest
   float a0[8], a1[8];
 #pragma unroll
   for (int i = 0; i < 8; ++i) a0[i] = a1[i] = 0.f;
+#pragma unroll 8
   for (int t = t0; t < t1; ++t) {
     const unsigned xv = *reinterpret_cast<const unsigned*>(x + (size_t)t * d + n);
     const float x0 = __uint_as_float(xv << 16), x1 = __uint_as_float(xv & 0xffff0000u);
@@ -272,6 +286,7 @@ __global__ void __launch_bounds__(256) moa_sum_parts_kernel(const float* __restr
   if (i >= n) return;
   const float* p = part + (size_t)blockIdx.y * n_part * n + i;
   f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll 8
   for (int sp = 0; sp < n_part; ++sp) acc += __builtin_bit_cast(f32x4, ldg16(p + sp * n));
   store4(out + (size_t)blockIdx.y * n + i, acc.x, acc.y, acc.z, acc.w);
 }
