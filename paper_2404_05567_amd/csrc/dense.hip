@@ -72,9 +72,15 @@ ScratchLayout scratch_layout(const dsmoe_ctx* c, int T) {
 
 __device__ __forceinline__ float sigmoid_f(float g) { return __builtin_amdgcn_rcpf(1.f + __expf(-g)); }
 // exact GeLU g * Phi(g) and its derivative Phi(g) + g * phi(g) (the two-matrix expert of Sec. 4.1)
-__device__ __forceinline__ float gelu_cdf_f(float g) { return 0.5f * (1.f + erff(g * 0.70710678118654752f)); }
+// Phi(g) and gelu'(g) = Phi(g) + g phi(g); for bf16 storage the cheaper Phi of gemm_core.h
+template <typename T>
+__device__ __forceinline__ float gelu_cdf_f(float g) {
+  if constexpr (std::is_same_v<T, bf16_t>) return gelu_cdf_bf16_f(g);
+  else return 0.5f * (1.f + erff(g * 0.70710678118654752f));
+}
+template <typename T>
 __device__ __forceinline__ float gelu_prime_f(float g) {
-  return gelu_cdf_f(g) + g * 0.3989422804014327f * __expf(-0.5f * g * g);
+  return gelu_cdf_f<T>(g) + g * 0.3989422804014327f * __expf(-0.5f * g * g);
 }
 
 // ---- forward: gate / up products of every expert on every token --------------------------------------
@@ -187,7 +193,7 @@ dense_gelu1_kernel(const T* __restrict__ x, const T* __restrict__ w_1, const flo
           if (G != nullptr) store_chunk(G + o, v[0]);
           float h[GM::CHUNK];
 #pragma unroll
-          for (int i = 0; i < GM::CHUNK; ++i) h[i] = sq[j] * v[0][i] * gelu_cdf_f(v[0][i]);
+          for (int i = 0; i < GM::CHUNK; ++i) h[i] = sq[j] * v[0][i] * gelu_cdf_f<T>(v[0][i]);
           store_chunk(Ht + o, h);
         });
   }
@@ -251,8 +257,8 @@ dense_bwd_dh_kernel(const T* __restrict__ d_out, const T* __restrict__ w_down, c
           if constexpr (GELU) {
 #pragma unroll
             for (int i = 0; i < GM::CHUNK; ++i) {
-              part = fmaf(g[i] * gelu_cdf_f(g[i]), v[0][i], part);
-              dg[i] = s * v[0][i] * gelu_prime_f(g[i]);
+              part = fmaf(g[i] * gelu_cdf_f<T>(g[i]), v[0][i], part);
+              dg[i] = s * v[0][i] * gelu_prime_f<T>(g[i]);
             }
             store_chunk(dG + od, dg);
             return;

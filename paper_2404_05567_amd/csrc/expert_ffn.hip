@@ -284,7 +284,7 @@ down_bf16_kernel(const bf16_t* __restrict__ h, const int32_t* __restrict__ row_t
         acc, st,
         [&](int, int, int, const float (&v)[1][4], float (&o)[1][4]) {
 #pragma unroll
-          for (int i = 0; i < 4; ++i) o[0][i] = GELU ? gelu_f(v[0][i]) : v[0][i];
+          for (int i = 0; i < 4; ++i) o[0][i] = GELU ? gelu_bf16_f(v[0][i]) : v[0][i];
         },
         [&](int m, int n, const u32x4 (&p)[1]) {
           if (m >= t.valid || n0 + n >= d) return;

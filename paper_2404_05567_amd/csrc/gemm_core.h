@@ -410,5 +410,19 @@ struct SplitWalker {
 __device__ __forceinline__ float silu_f(float g) { return g * __builtin_amdgcn_rcpf(1.f + __expf(-g)); }
 // exact GeLU: g * Phi(g)
 __device__ __forceinline__ float gelu_f(float g) { return 0.5f * g * (1.f + erff(g * 0.70710678118654752f)); }
+// Phi(g) for results that are rounded to bf16: erf by a degree-5 polynomial in 1 / (1 + p |x|) times the Gaussian
+// (Abramowitz & Stegun 7.1.26, absolute error 1.5e-7: three orders below the 2^-9 step of the storage type), about
+// a third of the instructions of the library erf, which weigh on the epilogue of a 64-step tile.
+__device__ __forceinline__ float gelu_cdf_bf16_f(float g) {
+  const float x = fabsf(g) * 0.70710678118654752f;
+  const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f, x, 1.f));
+  float p = fmaf(1.061405429f, t, -1.453152027f);
+  p = fmaf(p, t, 1.421413741f);
+  p = fmaf(p, t, -0.284496736f);
+  p = fmaf(p, t, 0.254829592f);
+  const float half_tail = 0.5f * p * t * __expf(-x * x);     // (1 - erf |x|) / 2
+  return g < 0.f ? half_tail : 1.f - half_tail;
+}
+__device__ __forceinline__ float gelu_bf16_f(float g) { return g * gelu_cdf_bf16_f(g); }
 
 }  // namespace dsmoe
