@@ -650,3 +650,40 @@ def test_the_library_reports_which_kernels_a_call_would_run(torch, dsmoe):
     assert path(5000, dsmoe.SEL_TOPK, 4, 0.0) == -1 and path(8, 77, 4, 0.0) == -1
     f32 = dsmoe.Layer(256, 64, 8, "f32", max_tokens=64)
     assert dsmoe.sparse_fwd_path(f32, 1, dsmoe.SEL_TOPK, 2, 0.0) == dsmoe.PATH_GROUPED
+
+
+@pytest.mark.parametrize("T,d,E,f,mode,k,eps,expert", [
+    (48, 512, 64, 128, "topk", 8, 0.0, "swiglu"),          # 64 experts: eight per XCD, the six-stage variant
+    (16, 320, 16, 192, "threshold", 0, 0.02, "swiglu"),    # ragged column slices in both phases
+    (64, 256, 8, 64, "topk", 4, 0.0, "swiglu"),            # one expert per XCD, one slice per expert
+    (24, 1024, 32, 256, "topk", 6, 0.0, "gelu"),
+    (9, 2048, 32, 512, "threshold", 0, 0.01, "swiglu"),
+])
+def test_all_expert_decode_kernel_shapes(torch, dsmoe, T, d, E, f, mode, k, eps, expert):
+    cfg = gen.LayerConfig("dense_decode", 25, T=T, d=d, E=E, f=f, dtype="bf16", mode=mode, k=k, eps=eps,
+                          router_std=1.5 / np.sqrt(d))
+    inp = conditioned(cfg, mode, k, eps, variant=T)
+    if expert == "gelu":
+        inp.w_up = None
+    say(f"[case] all-expert decode kernel T={T} d={d} E={E} f={f} {mode} k={k} eps={eps} {expert}")
+    w = weights_to_dev(torch, inp)
+    layer = dsmoe.Layer(d, f, E, "bf16", max_tokens=T, expert=expert)
+    code = mode_code(dsmoe, mode)
+    assert dsmoe.sparse_fwd_path(layer, T, code, k, eps) == dsmoe.PATH_ALL_EXPERTS
+    args = (w["x"], w["w_r"], w["b_r"], w["w_gate"], w["w_up"], w["w_down"], code, k, eps)
+    out = layer.sparse_fwd(*args).clone()
+    assert layer.poll_error() == dsmoe.OK
+    probs, mask, eo, rt = layer.sparse_fwd_routing(T)
+    torch.cuda.synchronize()
+    O_ref, S_ref, M_ref = orc.sparse_forward(inp.x, inp.w_r, inp.b_r, inp.w_gate, inp.w_up, inp.w_down, mode, k, eps)
+    assert helpers.rel_err(probs.cpu().numpy(), S_ref) <= 1e-5
+    np.testing.assert_array_equal(mask_to_bool(mask, E), M_ref)
+    r_ref = orc.dispatch(M_ref, S_ref)
+    np.testing.assert_array_equal(eo.cpu().numpy(), r_ref.expert_off)
+    np.testing.assert_array_equal(rt.cpu().numpy()[:r_ref.nnz], r_ref.row_token)
+    err = helpers.rel_err(out.float().cpu().numpy(), O_ref)
+    say(f"  rel err {err:.3e}")
+    assert err <= TOL["bf16"]
+    for _ in range(3):
+        assert torch.equal(layer.sparse_fwd(*args), out)
+    assert layer.poll_error() == dsmoe.OK
