@@ -183,7 +183,7 @@ def test_backward_m1_and_bitwise_repeat(torch, dsmoe):
 
 
 @pytest.mark.parametrize("T,L,n_head,d_head", [(1, 1, 2, 64), (1, 37, 1, 128), (129, 129, 2, 64), (300, 555, 2, 128),
-                                               (257, 700, 3, 64)])
+                                               (257, 700, 3, 64), (64, 2000, 2, 128), (33, 1000, 4, 64)])
 def test_backward_ragged_shapes(torch, dsmoe, T, L, n_head, d_head):
     cfg = gen.MoaConfig("bwd_ragged", 16, T=T, L=L, d=256, E=8, n_head=n_head, d_head=d_head, dtype="bf16", mode="dense",
                         router_std=0.1)
